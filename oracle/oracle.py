@@ -1,0 +1,242 @@
+"""CPU oracle, Python side: bucketing, graph loading, exhaustive ground truth, recall,
+and a ctypes front for the scalar C search/append in ``grab_oracle.c``.
+
+THIS IS TEST INFRASTRUCTURE (see the C file's header).  It imports nothing from the
+product package and the product package imports nothing from here.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+EMPTY = np.uint32(0xFFFFFFFF)
+L2SQ, IP = 0, 1
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libgrab_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (no fast-math, no contraction: the fp32 order is fixed)."""
+    src = os.path.join(_HERE, "grab_oracle.c")
+    if force or not os.path.exists(_LIB_PATH) or os.path.getmtime(_LIB_PATH) < os.path.getmtime(src):
+        subprocess.check_call(["gcc", "-O2", "-ffp-contract=off", "-fopenmp", "-shared", "-fPIC",
+                               "-Wall", "-o", _LIB_PATH, src, "-lm"])
+    return _LIB_PATH
+
+
+class _Index(ctypes.Structure):
+    _fields_ = [("dim", ctypes.c_int32), ("metric", ctypes.c_int32), ("k_local", ctypes.c_int32),
+                ("k_remote", ctypes.c_int32), ("n_buckets", ctypes.c_int32), ("pad_", ctypes.c_int32),
+                ("n_cap", ctypes.c_int64), ("X", ctypes.c_void_p), ("attr", ctypes.c_void_p),
+                ("A", ctypes.c_void_p), ("slot2id", ctypes.c_void_p), ("table", ctypes.c_void_p)]
+
+
+class _Params(ctypes.Structure):
+    _fields_ = [("search_width", ctypes.c_int32), ("max_iter", ctypes.c_int32),
+                ("n_seeds", ctypes.c_int32), ("visited_cap", ctypes.c_int32),
+                ("seed_salt", ctypes.c_uint32)]
+
+
+class _AppendParams(ctypes.Structure):
+    _fields_ = [("alpha", ctypes.c_float), ("append_beam", ctypes.c_int32)]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = ctypes.CDLL(_LIB_PATH)
+        _lib.oracle_distance.restype = ctypes.c_float
+        _lib.oracle_distance.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int32, ctypes.c_int32]
+        _lib.oracle_search.restype = ctypes.c_int
+        _lib.oracle_max_threads.restype = ctypes.c_int
+    return _lib
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def distance(q: np.ndarray, v: np.ndarray, metric: int = L2SQ) -> np.float32:
+    """fp32 distance with the fixed summation tree (see the C file)."""
+    q = np.ascontiguousarray(q, dtype=np.float32)
+    v = np.ascontiguousarray(v, dtype=np.float32)
+    return np.float32(_load().oracle_distance(_ptr(q), _ptr(v), q.shape[0], metric))
+
+
+# ------------------------------------------------------------------------ bucketing (A1)
+
+def bucket_layout(attrs: np.ndarray, n_buckets: int, n_cap: int):
+    """Section 4.2.1: partition into ``n_buckets`` disjoint ordered buckets by the scalar.
+
+    reading: ids sorted by (attribute, id); bucket b takes sorted ranks
+    [floor(b*n/B), floor((b+1)*n/B)) (equal counts, ties split by id); bucket b owns the slot
+    slab [base[b], base[b]+cap[b]) with cap[b] = count[b] + floor((n_cap-n)/B) and
+    base[b] = sum of earlier caps.  Returns (table[B,6] int32, id2slot[n], slot2id[total]).
+    """
+    n = len(attrs)
+    B = n_buckets
+    if B < 1 or n < B or n_cap < n:
+        raise ValueError("need 1 <= B <= n <= n_cap")
+    order = np.lexsort((np.arange(n), attrs))
+    slack = (n_cap - n) // B
+    starts = (np.arange(B + 1, dtype=np.int64) * n) // B
+    counts = np.diff(starts)
+    caps = counts + slack
+    bases = np.concatenate([[0], np.cumsum(caps)[:-1]])
+    total = int(caps.sum())
+    table = np.zeros((B, 6), dtype=np.int32)
+    id2slot = np.empty(n, dtype=np.uint32)
+    slot2id = np.full(total, EMPTY, dtype=np.uint32)
+    for b in range(B):
+        ids = order[starts[b]:starts[b + 1]]
+        slots = bases[b] + np.arange(counts[b])
+        id2slot[ids] = slots
+        slot2id[slots] = ids
+        table[b] = (bases[b], counts[b], counts[b], caps[b], attrs[ids[0]], attrs[ids[-1]])
+    return table, id2slot, slot2id
+
+
+class Index:
+    """Slot-space arrays of one index plus the calls that act on them."""
+
+    def __init__(self, vectors: np.ndarray, attrs: np.ndarray, n_buckets: int,
+                 n_cap: Optional[int] = None, metric: int = L2SQ):
+        vectors = np.ascontiguousarray(vectors, dtype=np.float32)
+        attrs = np.ascontiguousarray(attrs, dtype=np.int32)
+        n, d = vectors.shape
+        if d % 32:
+            raise ValueError("dim must be a multiple of 32")
+        n_cap = n if n_cap is None else n_cap
+        self.dim, self.metric, self.n, self.n_buckets = d, metric, n, n_buckets
+        self.table, self.id2slot, self.slot2id = bucket_layout(attrs, n_buckets, n_cap)
+        self.n_cap = len(self.slot2id)
+        self.id2slot = np.concatenate([self.id2slot, np.full(self.n_cap - n, EMPTY, np.uint32)])
+        self.X = np.zeros((self.n_cap, d), dtype=np.float32)
+        self.attr = np.zeros(self.n_cap, dtype=np.int32)
+        live = self.slot2id != EMPTY
+        self.X[live] = vectors[self.slot2id[live]]
+        self.attr[live] = attrs[self.slot2id[live]]
+        self.k_local = self.k_remote = 0
+        self.A = None
+        self.params = dict(search_width=1, max_iter=None, n_seeds=None, visited_cap=2800,
+                           seed_salt=0, alpha=0.6, append_beam=64)
+
+    # -- M_I2B: bucket of every external id
+    def bucket_of_ids(self) -> np.ndarray:
+        return self.bucket_of_slots(self.id2slot[:self.n])
+
+    def bucket_of_slots(self, slots: np.ndarray) -> np.ndarray:
+        ends = self.table[:, 0].astype(np.int64) + self.table[:, 3]
+        return np.searchsorted(ends, np.asarray(slots, dtype=np.int64), side="right")
+
+    # -- load_graph: ids -> slots, [local | remote] per row, checked (Section 4.2.2)
+    def load_graph(self, local_adj: np.ndarray, remote_adj: np.ndarray):
+        n = self.n
+        kl, kr = local_adj.shape[1], remote_adj.shape[1]
+        if local_adj.shape[0] != n or remote_adj.shape[0] != n:
+            raise ValueError("adjacency must have one row per base vector")
+        adj = np.concatenate([local_adj, remote_adj], axis=1).astype(np.uint32)
+        live = adj != EMPTY
+        if (adj[live] >= n).any():
+            raise ValueError("neighbour id out of range")
+        slots = np.full(adj.shape, EMPTY, dtype=np.uint32)
+        slots[live] = self.id2slot[adj[live]]
+        own = self.bucket_of_ids()[:, None]
+        nb = np.where(live, self.bucket_of_slots(np.where(live, slots, 0)), -1)
+        if ((nb[:, :kl] != own) & live[:, :kl]).any():
+            raise ValueError("a local edge leaves its bucket")
+        if ((nb[:, kl:] == own) & live[:, kl:]).any():
+            raise ValueError("a remote edge stays in its bucket")
+        self.k_local, self.k_remote = kl, kr
+        self.A = np.full((self.n_cap, kl + kr), EMPTY, dtype=np.uint32)
+        self.A[self.id2slot[:n]] = slots
+
+    # -- ctypes views
+    def _c_index(self) -> _Index:
+        A = self.A if self.A is not None else np.zeros((1, 1), np.uint32)
+        return _Index(self.dim, self.metric, self.k_local, self.k_remote, self.n_buckets, 0,
+                      self.n_cap, _ptr(self.X).value, _ptr(self.attr).value, _ptr(A).value,
+                      _ptr(self.slot2id).value, _ptr(self.table).value)
+
+    def _c_params(self, beam: int) -> _Params:
+        p = self.params
+        max_iter = p["max_iter"] if p["max_iter"] is not None else 2 * beam
+        n_seeds = p["n_seeds"] if p["n_seeds"] is not None else min(beam, 64)
+        return _Params(p["search_width"], max_iter, n_seeds, p["visited_cap"], p["seed_salt"])
+
+    def select(self, lo: int, hi: int, beam: int = 64):
+        """(info[6], seeds): bucket run, population size, valid sorted span ends, seed slots."""
+        pr = self._c_params(beam)
+        info = np.zeros(6, dtype=np.int64)
+        seeds = np.full(pr.n_seeds, EMPTY, dtype=np.uint32)
+        ix = self._c_index()
+        _load().oracle_select(ctypes.byref(ix), ctypes.byref(pr), ctypes.c_int32(lo), ctypes.c_int32(hi),
+                              _ptr(info), _ptr(seeds))
+        return info, seeds
+
+    def search(self, queries: np.ndarray, lo: np.ndarray, hi: np.ndarray, k: int, beam: int,
+               threads: int = 1):
+        """Algorithm 2 for a batch.  Returns (ids[nq,k] uint32, dist[nq,k] fp32, counters[nq,8])."""
+        if self.A is None:
+            raise RuntimeError("load_graph first")
+        queries = np.ascontiguousarray(queries, dtype=np.float32)
+        lo = np.ascontiguousarray(lo, dtype=np.int32)
+        hi = np.ascontiguousarray(hi, dtype=np.int32)
+        nq = queries.shape[0]
+        ids = np.empty((nq, k), dtype=np.uint32)
+        dist = np.empty((nq, k), dtype=np.float32)
+        ctr = np.zeros((nq, 8), dtype=np.uint32)
+        ix, pr = self._c_index(), self._c_params(beam)
+        rc = _load().oracle_search(ctypes.byref(ix), ctypes.byref(pr), _ptr(queries), _ptr(lo), _ptr(hi),
+                                   ctypes.c_int64(nq), ctypes.c_int32(k), ctypes.c_int32(beam),
+                                   _ptr(ids), _ptr(dist), _ptr(ctr), ctypes.c_int32(threads))
+        if rc:
+            raise ValueError("oracle_search rejected its arguments")
+        return ids, dist, ctr
+
+
+def max_threads() -> int:
+    return int(_load().oracle_max_threads())
+
+
+# ------------------------------------------------------------- exact answer (Definition, Eq. 1)
+
+def exact_filtered_knn(vectors: np.ndarray, attrs: np.ndarray, queries: np.ndarray, lo, hi,
+                       k: int, metric: int = L2SQ) -> Tuple[np.ndarray, np.ndarray]:
+    """Hybrid Search definition (Section 2.4): among objects with lo <= s_i <= hi the k with
+    the smallest distance, in float64, ties by id.  Missing entries: (EMPTY, +inf)."""
+    v64 = vectors.astype(np.float64)
+    nq = len(queries)
+    ids = np.full((nq, k), EMPTY, dtype=np.uint32)
+    dist = np.full((nq, k), np.inf, dtype=np.float64)
+    for i in range(nq):
+        ok = np.nonzero((attrs >= lo[i]) & (attrs <= hi[i]))[0]
+        if len(ok) == 0:
+            continue
+        q = queries[i].astype(np.float64)
+        if metric == L2SQ:
+            diff = v64[ok] - q
+            d = np.einsum("ij,ij->i", diff, diff)
+        else:
+            d = -(v64[ok] @ q)
+        o = np.lexsort((ok, d))[:k]
+        ids[i, :len(o)] = ok[o]
+        dist[i, :len(o)] = d[o]
+    return ids, dist
+
+
+def recall_at_k(result_ids: np.ndarray, truth_ids: np.ndarray) -> float:
+    """Eq. 1 averaged over queries: |R intersect R*| / k; padding never counts as a hit and
+    a query with fewer than k valid objects is scored against the number it has."""
+    hits, total = 0, 0
+    for r, t in zip(result_ids, truth_ids):
+        t = t[t != EMPTY]
+        total += len(t)
+        hits += len(np.intersect1d(r[r != EMPTY], t))
+    return hits / max(total, 1)

@@ -1,0 +1,143 @@
+"""Pins for the oracle's bucketing, bucket selection and seeding
+(Section 4.2.1, Section 4.2.4, Algorithm 2 lines 1-2)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2604_16402_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _tiny_index(attrs, B, n_cap, dim=32, seed=0):
+    rng = np.random.default_rng(seed)
+    X = rng.standard_normal((len(attrs), dim)).astype(np.float32)
+    return O.Index(X, np.asarray(attrs, np.int32), B, n_cap), X
+
+
+def test_hand_worked_layout():
+    g = json.load(open(os.path.join(GOLD, "layout_small.json")))
+    ix, _ = _tiny_index(g["attrs"], g["n_buckets"], g["n_cap"])
+    assert ix.table.tolist() == g["table"]
+    assert ix.id2slot[:len(g["attrs"])].tolist() == g["id2slot"]
+    for s in g["selections"]:
+        info, _ = ix.select(s["lo"], s["hi"])
+        assert info[:5].tolist() == [s["b0"], s["b1"], s["V"], s["first_valid_slot"], s["end_valid_slot"]], s
+
+
+@pytest.mark.parametrize("n,B,n_cap", [(1000, 7, 1000), (1000, 16, 1300), (4097, 64, 5000), (64, 64, 64)])
+def test_layout_invariants(n, B, n_cap):
+    rng = np.random.default_rng(n + B)
+    attrs = rng.integers(0, 50, n).astype(np.int32)          # many ties
+    ix, X = _tiny_index(attrs, B, n_cap)
+    t = ix.table
+    assert t[:, 1].sum() == n and t[:, 1].max() - t[:, 1].min() <= 1      # equal counts
+    assert (t[:, 3] == t[:, 1] + (n_cap - n) // B).all()                   # capacity = count + slack share
+    assert (t[1:, 0] == t[:-1, 0] + t[:-1, 3]).all() and t[0, 0] == 0     # slabs are contiguous
+    assert (t[:-1, 5] <= t[1:, 4]).all()                                   # intervals ordered, may touch
+    ids = np.arange(n)
+    assert (ix.slot2id[ix.id2slot[:n]] == ids).all()                       # maps are inverse
+    assert (ix.slot2id != O.EMPTY).sum() == n
+    for b in range(B):
+        s = ix.attr[t[b, 0]:t[b, 0] + t[b, 1]]
+        assert (np.diff(s) >= 0).all() and s[0] == t[b, 4] and s[-1] == t[b, 5]
+        own = ix.slot2id[t[b, 0]:t[b, 0] + t[b, 1]]
+        key = attrs[own].astype(np.int64) * n + own                         # (attr, id) strictly increasing
+        assert (np.diff(key) > 0).all()
+    assert (ix.X[ix.id2slot[:n]] == X).all() and (ix.attr[ix.id2slot[:n]] == attrs).all()
+    assert (ix.bucket_of_ids() == np.searchsorted(np.cumsum(t[:, 1]), np.argsort(np.lexsort((ids, attrs))), side="right")).all()
+
+
+def test_selection_against_brute_force():
+    rng = np.random.default_rng(5)
+    n, B = 3000, 12
+    attrs = rng.integers(0, 400, n).astype(np.int32)
+    ix, _ = _tiny_index(attrs, B, 3300)
+    t = ix.table
+    for _ in range(300):
+        lo = int(rng.integers(-20, 420)); hi = lo + int(rng.integers(-3, 200))
+        info, _ = ix.select(lo, hi)
+        meets = [b for b in range(B) if lo <= hi and t[b, 5] >= lo and t[b, 4] <= hi]
+        valid_slots = np.nonzero((ix.slot2id != O.EMPTY) & (ix.attr >= lo) & (ix.attr <= hi))[0]
+        if not meets:
+            assert info[1] < info[0] and info[2] == 0 and len(valid_slots) == 0
+            continue
+        assert (info[0], info[1]) == (meets[0], meets[-1])
+        assert info[2] == len(valid_slots)                                   # no tails here: V = exact count
+        # completeness: every object in range lies in a selected bucket
+        assert set(ix.bucket_of_slots(valid_slots).tolist()) <= set(meets)
+        if len(valid_slots):
+            assert info[3] == valid_slots.min() and info[4] == valid_slots.max() + 1
+
+
+def test_seeds_all_when_population_small():
+    attrs = np.arange(200, dtype=np.int32)
+    ix, _ = _tiny_index(attrs, 4, 200)
+    ix.params["n_seeds"] = 64
+    info, seeds = ix.select(10, 40)
+    assert info[2] == 31 and info[5] == 31
+    assert sorted(ix.slot2id[seeds[:31]].tolist()) == list(range(10, 41))
+    assert (seeds[31:] == O.EMPTY).all()
+
+
+@pytest.mark.parametrize("salt", [0, 1, 12345])
+def test_seeds_are_stratified_distinct_and_valid(salt):
+    rng = np.random.default_rng(9)
+    n, B, S = 5000, 8, 64
+    attrs = rng.integers(0, 5000, n).astype(np.int32)
+    ix, _ = _tiny_index(attrs, B, n)
+    ix.params.update(n_seeds=S, seed_salt=salt)
+    for lo, hi in [(0, 4999), (100, 2100), (2500, 2700), (4000, 4999)]:
+        info, seeds = ix.select(lo, hi)
+        V = int(info[2])
+        pop = np.nonzero((ix.slot2id != O.EMPTY) & (ix.attr >= lo) & (ix.attr <= hi))[0]   # slot order = population order
+        assert V == len(pop) and info[5] == S
+        pos = np.searchsorted(pop, seeds)
+        assert (pop[pos] == seeds).all()                     # every seed is a valid object
+        lo_edge = (np.arange(S) * V) // S
+        assert (pos >= lo_edge).all() and (pos < lo_edge + V // S).all()   # one per stratum, inside its jitter window
+        assert len(set(seeds.tolist())) == S
+    a, _ = ix.select(0, 4999)
+    ix.params["seed_salt"] = salt + 1
+    _, other = ix.select(0, 4999)
+    ix.params["seed_salt"] = salt
+    _, again = ix.select(0, 4999)
+    _, base = ix.select(0, 4999)
+    assert (again == base).all() and (other != base).any()   # deterministic; salt moves the jitter
+
+
+def test_load_graph_checks_local_and_remote():
+    attrs = np.arange(40, dtype=np.int32)
+    ix, X = _tiny_index(attrs, 4, 40)
+    local = np.full((40, 2), O.EMPTY, np.uint32); remote = np.full((40, 1), O.EMPTY, np.uint32)
+    local[0] = [1, 2]; remote[0] = [15]
+    ix.load_graph(local, remote)
+    assert ix.A[ix.id2slot[0]].tolist() == [ix.id2slot[1], ix.id2slot[2], ix.id2slot[15]]
+    bad = local.copy(); bad[0, 0] = 15
+    with pytest.raises(ValueError):
+        ix.load_graph(bad, remote)
+    bad = remote.copy(); bad[0, 0] = 3
+    with pytest.raises(ValueError):
+        ix.load_graph(local, bad)
+    bad = local.copy(); bad[0, 0] = 40
+    with pytest.raises(ValueError):
+        ix.load_graph(bad, remote)
+
+
+def test_harness_graph_respects_bucket_rules(c1_small):
+    ix, cfg = c1_small["oracle"], c1_small["cfg"]
+    A = ix.A[ix.id2slot[:cfg.n]]
+    own = ix.bucket_of_ids()[:, None]
+    kl = cfg.k_local
+    live = A != O.EMPTY
+    nb = ix.bucket_of_slots(np.where(live, A, 0))
+    assert ((nb[:, :kl] == own) | ~live[:, :kl]).all()       # local edges stay inside the bucket
+    assert ((nb[:, kl:] != own) | ~live[:, kl:]).all()       # remote edges leave it
+    assert A.shape[1] == cfg.k_local + cfg.k_remote           # fixed degree
+    assert live.all()
+    srt = np.sort(A, axis=1)
+    assert (np.diff(srt.astype(np.int64), axis=1) != 0).all()  # no duplicate neighbour in a row
+    assert (A != ix.id2slot[:cfg.n, None]).all()               # no self loops
