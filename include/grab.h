@@ -1,0 +1,153 @@
+/*
+ * grab.h - C ABI of the MI355X range-filtered graph search library (libgrab.so).
+ *
+ * The library holds one bucketed graph index per handle, entirely in device memory, and
+ * runs every step of the search and append path in HIP kernels written for gfx950.
+ * The calls follow the paper's problem statement: a data set of (vector, scalar) objects
+ * and queries Q = (q, k, [l, u]) (Section 2.4, Hybrid Search definition), answered by the
+ * range-constrained graph search of Algorithm 2 over the bucketed topology of Section 4.2,
+ * and batches of new objects inserted as in Section 4.4.
+ *
+ * Conventions for every call
+ *   - Returns a grab_status.  On anything but GRAB_OK the index is unchanged unless the
+ *     call's comment says otherwise, and grab_last_error() gives a message.
+ *   - Every pointer argument may be a device pointer (e.g. torch-allocated) or an ordinary
+ *     host pointer; the library finds out with hipPointerGetAttributes.  The caller owns
+ *     all input and output buffers; the library copies what it needs into arrays it owns
+ *     and keeps no caller pointer after the call returns.
+ *   - Work is enqueued on the HIP stream given to grab_create.  A call with device outputs
+ *     returns after enqueueing; a call with host outputs (or host inputs) synchronises the
+ *     stream before returning.  Calls that report GRAB_EFULL / GRAB_EINVAL from device-side
+ *     checks (grab_load_graph, grab_append_batch) synchronise too.
+ *   - Arguments are validated on the host before any kernel is launched.
+ *   - Matrices are dense row-major.  Object ids ("external ids") are row numbers of the
+ *     grab_build_buckets input and continue n, n+1, ... in append order.  "Slots" are
+ *     physical row numbers of the bucket-major device arrays.
+ *   - 0xFFFFFFFF marks an empty adjacency entry and a missing result.
+ *   - dim must be a multiple of 32 (rows are whole 128-byte lines) and at most 2048.
+ *   - Not thread-safe per handle; different handles are independent.
+ */
+#ifndef GRAB_H
+#define GRAB_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct grab_index grab_index; /* opaque; owns all device arrays */
+
+typedef enum {
+    GRAB_OK = 0,
+    GRAB_EINVAL = 1, /* bad argument (sizes, null pointer, k > beam, malformed graph, ...) */
+    GRAB_ESTATE = 2, /* call out of order (search before load_graph, ...)                   */
+    GRAB_EFULL = 3,  /* a bucket has no tail room left for an append                        */
+    GRAB_ENOMEM = 4, /* device or host allocation failed                                    */
+    GRAB_EHIP = 5    /* a HIP runtime call failed                                           */
+} grab_status;
+
+typedef enum {
+    GRAB_L2SQ = 0, /* sum_j (q_j - v_j)^2  (Euclidean ranking, Table 2; no square root) */
+    GRAB_IP = 1    /* -sum_j q_j v_j       (smaller is better)                           */
+} grab_metric;
+
+/* Tunables of Algorithm 2 and Section 4.4 (names as in Section 5's hyper-parameter study). */
+typedef enum {
+    GRAB_P_SEARCH_WIDTH = 0, /* parents expanded per iteration, 1..8; default 1            */
+    GRAB_P_MAX_ITER = 1,     /* iteration cap; 0 = 2*beam (default)                        */
+    GRAB_P_N_SEEDS = 2,      /* seeds per query; 0 = min(beam, 64) (default)               */
+    GRAB_P_VISITED_CAP = 3,  /* the search stops before its visited set could exceed this;
+                                default 2800, at most 24000                                */
+    GRAB_P_SEED_SALT = 4,    /* moves the seed jitter; default 0                           */
+    GRAB_P_ALPHA = 5,        /* freshness bias of Eq. 3, in (0, 1]; default 0.6            */
+    GRAB_P_APPEND_BEAM = 6   /* candidate queue size of append's searches; default 64      */
+} grab_param;
+
+/* Creates an empty index for `dim`-dimensional fp32 vectors under `metric`.
+ * `hip_stream` is a hipStream_t (NULL = the default stream); it must outlive the index. */
+grab_status grab_create(grab_index **out, int32_t dim, int32_t metric, void *hip_stream);
+
+/* Frees every device and host array of the index.  NULL is allowed. */
+void grab_destroy(grab_index *ix);
+
+/* Message for the last non-OK status of this handle ("" if none).  Owned by the handle. */
+const char *grab_last_error(const grab_index *ix);
+
+/* Predicate-based bucket partitioning (Section 4.2.1) into the unified device layout
+ * (Section 4.2.4).  vectors[n][dim] fp32, attrs[n] int32.  Objects are ordered by
+ * (attribute, id) and cut into n_buckets buckets of equal count (ranks floor(b*n/B) ..
+ * floor((b+1)*n/B)); bucket b owns a contiguous slab of count_b + floor((n_cap-n)/B) slots,
+ * the extra ones being tail room for grab_append_batch.  Builds the feature matrix,
+ * attribute array, id<->slot maps and bucket table; drops any graph loaded before.
+ * Requires 1 <= n_buckets <= 1024, n_buckets <= n <= n_cap < 2^31.
+ * Errors: GRAB_EINVAL (arguments), GRAB_ENOMEM, GRAB_EHIP; the index is empty afterwards. */
+grab_status grab_build_buckets(grab_index *ix, const float *vectors, const int32_t *attrs,
+                               int64_t n, int32_t n_buckets, int64_t n_cap);
+
+/* Installs the hybrid edge topology (Section 4.2.2) with fixed degree k_local + k_remote
+ * (Section 4.2.3).  local_adj[n][k_local] and remote_adj[n][k_remote] hold external ids
+ * (0xFFFFFFFF = no edge), one row per object currently in the index.  Ids are translated
+ * to slots and each row is stored as [local | remote].  Checked on the device: ids < n,
+ * local edges stay inside the node's bucket, remote edges leave it; a violation gives
+ * GRAB_EINVAL and leaves the index without a graph.  k_local + k_remote must be 1..64;
+ * k_remote may be 0 (remote_adj then unused).  GRAB_ESTATE before grab_build_buckets. */
+grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k_local,
+                            const uint32_t *remote_adj, int32_t k_remote);
+
+/* Range-constrained search (Algorithm 2) for nq queries: queries[nq][dim], closed ranges
+ * lo[i] <= attribute <= hi[i], k results per query from a candidate queue of `beam` entries
+ * (the paper's itopk).  out_ids[nq][k] external ids and out_dist[nq][k] distances, ascending
+ * by (distance, slot); rows with fewer than k reachable valid objects are padded with
+ * (0xFFFFFFFF, +inf); lo > hi or a range that meets no bucket gives a fully padded row.
+ * Requires 1 <= k <= beam <= 512, n_seeds <= visited_cap, search_width * degree <= 512.
+ * Allocates nothing once its per-batch work buffers have grown to nq.
+ * Errors: GRAB_EINVAL, GRAB_ESTATE (no graph), GRAB_ENOMEM, GRAB_EHIP. */
+grab_status grab_search_range(grab_index *ix, const float *queries, const int32_t *lo,
+                              const int32_t *hi, int64_t nq, int32_t k, int32_t beam,
+                              uint32_t *out_ids, float *out_dist);
+
+/* Batched insertion (Section 4.4): appends m objects at the tails of their buckets without
+ * moving any existing slot, searches candidate neighbours in the target bucket and
+ * globally, selects forward edges by the diversity rule (Eq. 2) and rewires reverse edges
+ * with the freshness bias (Eq. 3).  New external ids are n_prev .. n_prev+m-1 in input
+ * order.  GRAB_EFULL if any bucket would overflow its slab: nothing is written then.
+ * Errors: GRAB_EINVAL, GRAB_ESTATE (no graph), GRAB_EFULL, GRAB_ENOMEM, GRAB_EHIP. */
+grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_t *attrs, int64_t m);
+
+/* Sets a grab_param.  GRAB_EINVAL if `which` is unknown or `value` is out of range. */
+grab_status grab_set_param(grab_index *ix, int32_t which, double value);
+
+/* Sizes of the index: out[0] objects, out[1] slots, out[2] buckets, out[3] k_local,
+ * out[4] k_remote, out[5] dim, out[6] metric, out[7] 1 if a graph is loaded. (host array) */
+grab_status grab_get_sizes(const grab_index *ix, int64_t out[8]);
+
+/* Copies out the layout: bucket_table[B][6] = {base, n_sorted, n_total, cap, min_attr,
+ * max_attr}, id2slot[objects], slot2id[slots].  Any pointer may be NULL to skip it. */
+grab_status grab_get_layout(grab_index *ix, int32_t *bucket_table, uint32_t *id2slot, uint32_t *slot2id);
+
+/* Copies out the adjacency in slot space: adj[slots][k_local + k_remote]. */
+grab_status grab_get_graph(grab_index *ix, uint32_t *adj_slots);
+
+/* Copies out the stored feature rows and attributes in slot space (either may be NULL). */
+grab_status grab_get_rows(grab_index *ix, float *vectors_slots, int32_t *attr_slots);
+
+/* Bucket selection and seeding alone (Algorithm 2, lines 1-2) for nq ranges, as the search
+ * computes them: info[nq][6] int32 = {first bucket, last bucket (< first when none),
+ * population size V, first valid sorted slot of the first bucket, end of valid sorted slots
+ * of the last bucket, seed count}; seeds[nq][n_seeds] slots, 0xFFFFFFFF-padded.  `beam`
+ * only fixes the default seed count.  seeds may be NULL. */
+grab_status grab_select_range(grab_index *ix, const int32_t *lo, const int32_t *hi, int64_t nq,
+                              int32_t beam, int32_t *info, uint32_t *seeds);
+
+/* Per-query counters of the most recent grab_search_range: per_query[nq][8] uint32 =
+ * {iterations, parents expanded, distance evaluations (seeds included), seed evaluations,
+ *  neighbours rejected by the scalar pre-check, slots whose attribute had to be read
+ *  (appended tails of the two edge buckets), visited-set size, stop reason
+ *  (0 queue exhausted, 1 max_iter, 2 visited capacity, 3 empty range)}. */
+grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRAB_H */

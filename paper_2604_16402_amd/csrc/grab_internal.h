@@ -1,0 +1,115 @@
+// Internal declarations shared by the translation units of libgrab.so (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+
+#include "grab.h"
+
+#define GRAB_EMPTY 0xFFFFFFFFu
+#define GRAB_MAX_BUCKETS 1024
+#define GRAB_MAX_BEAM 512
+#define GRAB_MAX_CAND 512   // search_width * degree, and the seed chunk size
+#define GRAB_WAVE 64
+
+// bucket table columns (Section 4.2.4: the bucket<->index metadata)
+enum { T_BASE = 0, T_NSORT = 1, T_NTOT = 2, T_CAP = 3, T_MIN = 4, T_MAX = 5, T_COLS = 6 };
+
+// What the select kernel hands to the beam kernel for one query: the bucket run and the
+// slot intervals that decide the scalar pre-check without reading an attribute.
+struct QueryPlan {
+    int32_t b0, b1;    // selected bucket run; b1 < b0: the range meets no bucket
+    int32_t V;         // seed population size
+    int32_t n_seeds;   // seeds written for this query
+    int32_t s0, e0;    // valid sorted slots of bucket b0
+    int32_t t0s, t0e;  // appended tail of b0: attribute must be read
+    int32_t ms, e1;    // buckets after b0 up to the valid sorted end of b1: all valid
+    int32_t t1s, t1e;  // appended tail of b1 (b1 > b0): attribute must be read
+    int32_t first_valid, end_valid;
+    int32_t pad0, pad1;
+};
+
+struct SearchParams {
+    int32_t search_width = 1;
+    int32_t max_iter = 0;      // 0: 2 * beam
+    int32_t n_seeds = 0;       // 0: min(beam, 64)
+    int32_t visited_cap = 2800;
+    uint32_t seed_salt = 0;
+    float alpha = 0.6f;
+    int32_t append_beam = 64;
+};
+
+struct DevBuf {
+    void *p = nullptr;
+    size_t bytes = 0;
+};
+
+struct grab_index {
+    int32_t dim = 0;
+    int32_t metric = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+
+    // layout (device)
+    int64_t n = 0;        // objects
+    int64_t n_slots = 0;  // physical rows
+    int32_t B = 0;
+    float *X = nullptr;          // [n_slots][dim]
+    int32_t *attr = nullptr;     // [n_slots]
+    uint32_t *slot2id = nullptr; // [n_slots]
+    uint32_t *id2slot = nullptr; // [n_slots] (ids grow up to the slot count)
+    int32_t *table = nullptr;    // [B][6] device copy
+    int32_t *h_table = nullptr;  // host copy (pinned)
+
+    // graph (device)
+    int32_t kl = 0, kr = 0;
+    uint32_t *A = nullptr;       // [n_slots][kl+kr]
+    bool has_graph = false;
+
+    SearchParams prm;
+
+    // grow-only work buffers
+    DevBuf plans, seeds, counters, stage_q, stage_lo, stage_hi, stage_ids, stage_dist, stage_misc, flags;
+    int64_t last_nq = 0;
+};
+
+// error plumbing ------------------------------------------------------------------------
+grab_status grab_fail(grab_index *ix, grab_status st, const char *fmt, ...);
+#define GRAB_HIP(ix, call)                                                                     \
+    do {                                                                                       \
+        hipError_t e__ = (call);                                                               \
+        if (e__ != hipSuccess)                                                                 \
+            return grab_fail((ix), e__ == hipErrorOutOfMemory ? GRAB_ENOMEM : GRAB_EHIP,       \
+                             "%s failed: %s", #call, hipGetErrorString(e__));                  \
+    } while (0)
+
+bool grab_is_device_ptr(const void *p);
+grab_status grab_reserve(grab_index *ix, DevBuf &b, size_t bytes);
+// returns a device view of `src` (copying from host through `stage` when needed)
+grab_status grab_to_device(grab_index *ix, const void *src, size_t bytes, DevBuf &stage, const void **out);
+
+// kernels' host launchers -----------------------------------------------------------------
+// layout
+grab_status grab_launch_build(grab_index *ix, const float *d_vectors, const int32_t *d_attrs,
+                              int64_t n, int32_t B, int64_t slack);
+grab_status grab_launch_load_graph(grab_index *ix, const uint32_t *d_local, int32_t kl,
+                                   const uint32_t *d_remote, int32_t kr, int32_t *d_err);
+// search
+struct SearchLaunch {
+    const float *queries;   // device [nq][dim]
+    const int32_t *lo, *hi; // device [nq]
+    const int32_t *only_bucket; // device [nq] or nullptr: restrict to one bucket's slab (append)
+    int64_t nq;
+    int32_t k, beam, width, max_iter, n_seeds, visited_cap;
+    uint32_t salt;
+    QueryPlan *plans;   // device [nq]
+    uint32_t *seeds;    // device [nq][n_seeds]
+    uint32_t *counters; // device [nq][8]
+    uint32_t *out_ids;  // device [nq][k] (external ids, or slots when out_slots)
+    float *out_dist;    // device [nq][k]
+    bool out_slots;
+};
+grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s);
+grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s);

@@ -1,0 +1,535 @@
+// Range-constrained graph search (Algorithm 2) for gfx950: a bucket-select + seeding kernel
+// and a beam-search kernel that runs one query per 64-lane wavefront.
+//
+// Data movement per query: the query row once, one 128-byte-aligned feature row per
+// distance evaluation (8 lanes x 16 B per 128-byte line, all lines of up to 8*R rows in
+// flight at once), one adjacency row per expanded parent.  The candidate queue, the new
+// candidates and the visited hash live in LDS.  The scalar pre-check is decided from slot
+// intervals prepared by the select kernel, so only slots in the appended tails of the two
+// edge buckets cost an attribute read.
+#include "grab_internal.h"
+
+namespace {
+
+typedef unsigned long long u64;
+constexpr u64 SENT = ~0ull;  // empty queue entry; sorts last
+
+// order-preserving image of an fp32 value in uint32
+__device__ __forceinline__ uint32_t dist_image(float d) {
+    uint32_t b = __float_as_uint(d);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float image_dist(uint32_t m) {
+    return __uint_as_float((m & 0x80000000u) ? (m & 0x7FFFFFFFu) : ~m);
+}
+// queue key: distance image | slot | expanded flag.  Keys of different slots never tie.
+__device__ __forceinline__ u64 make_key(float d, uint32_t slot) { return ((u64)dist_image(d) << 32) | ((u64)slot << 1); }
+__device__ __forceinline__ uint32_t key_slot(u64 k) { return (uint32_t)(k & 0xFFFFFFFFull) >> 1; }
+
+// integer finaliser used for the seed jitter (the public-domain MurmurHash3 finaliser)
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+    return x;
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m);
+    return v;
+}
+
+// first index i in sorted a[0..n) with a[i] >= key (strict=false) or a[i] > key (strict=true):
+// a 64-way search, each step probing 64 evenly spaced positions with the whole wave
+__device__ int wave_bound(const int32_t *__restrict__ a, int n, int key, bool strict, int lane) {
+    int lo = 0, hi = n;
+    while (hi > lo) {
+        int chunk = (hi - lo + 63) >> 6;
+        int pos = lo + lane * chunk;
+        bool below = false;
+        if (pos < hi) {
+            int x = a[pos];
+            below = strict ? (x <= key) : (x < key);
+        }
+        int c = __popcll(__ballot(below));  // sorted input: the first c probes are below
+        if (c == 0) {
+            hi = lo;
+        } else {
+            int nlo = lo + (c - 1) * chunk + 1;
+            int nhi = lo + c * chunk;
+            hi = nhi < hi ? nhi : hi;
+            lo = nlo;
+        }
+    }
+    return lo;
+}
+
+// ----------------------------------------------------------------------------- select + seed
+// Algorithm 2 lines 1-2: the run of buckets whose [min,max] meets [lo,hi]; the valid part of
+// the sorted prefix of the two edge buckets by search; the seed population (valid sorted part
+// then appended tail of every selected bucket, in bucket order) and one stratified, jittered
+// seed per stratum.  One wavefront per query.
+__global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ table, int32_t B,
+                                                    const int32_t *__restrict__ attr,
+                                                    const int32_t *__restrict__ lo_, const int32_t *__restrict__ hi_,
+                                                    const int32_t *__restrict__ only_bucket, int32_t S, uint32_t salt,
+                                                    QueryPlan *__restrict__ plans, uint32_t *__restrict__ seeds) {
+    __shared__ int32_t pre[GRAB_MAX_BUCKETS + 1];
+    const int64_t q = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int lo = lo_[q], hi = hi_[q];
+    const int only = only_bucket ? only_bucket[q] : -1;
+    int b0 = 0, b1 = -1;
+    if (only >= 0) {
+        b0 = b1 = only;
+    } else if (lo <= hi) {
+        // bucket intervals are ordered, so counting gives the run: buckets entirely below lo
+        // come first, buckets starting at or below hi form a prefix
+        int below = 0, start_ok = 0;
+        for (int b = lane; b < B; b += 64) {
+            below += table[T_COLS * b + T_MAX] < lo;
+            start_ok += table[T_COLS * b + T_MIN] <= hi;
+        }
+        b0 = wave_sum(below);
+        b1 = wave_sum(start_ok) - 1;
+        if (b1 < b0) { b0 = 0; b1 = -1; }
+    }
+    QueryPlan p;
+    p.b0 = b0; p.b1 = b1; p.V = 0; p.n_seeds = 0;
+    p.s0 = p.e0 = p.t0s = p.t0e = p.ms = p.e1 = p.t1s = p.t1e = 0;
+    p.first_valid = p.end_valid = 0; p.pad0 = p.pad1 = 0;
+    if (b1 < b0) {
+        if (lane == 0) plans[q] = p;
+        for (int j = lane; j < S; j += 64) seeds[q * S + j] = GRAB_EMPTY;
+        return;
+    }
+    const int32_t *t0 = table + T_COLS * b0, *t1 = table + T_COLS * b1;
+    const int base0 = t0[T_BASE], ns0 = t0[T_NSORT], nt0 = t0[T_NTOT];
+    const int base1 = t1[T_BASE], ns1 = t1[T_NSORT], nt1 = t1[T_NTOT];
+    int sa0, se0, se1 = 0, tail0, tail1 = 0;
+    if (only >= 0) {           // whole slab, nothing to check
+        sa0 = 0; se0 = nt0; tail0 = 0;
+    } else {
+        sa0 = wave_bound(attr + base0, ns0, lo, false, lane);
+        se0 = (b1 == b0) ? wave_bound(attr + base0, ns0, hi, true, lane) : ns0;
+        if (se0 < sa0) se0 = sa0;
+        tail0 = nt0 - ns0;
+        if (b1 > b0) {
+            se1 = wave_bound(attr + base1, ns1, hi, true, lane);
+            tail1 = nt1 - ns1;
+        }
+    }
+    // population count per selected bucket, exclusive prefix in LDS
+    const int nb = b1 - b0 + 1;
+    int carry = 0;
+    for (int i0 = 0; i0 < nb; i0 += 64) {
+        int i = i0 + lane, c = 0;
+        if (i < nb) {
+            int b = b0 + i;
+            if (b == b0) c = (se0 - sa0) + tail0;
+            else if (b == b1) c = se1 + tail1;
+            else c = table[T_COLS * b + T_NTOT];
+        }
+        int inc = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            int up = __shfl_up(inc, d);
+            if (lane >= d) inc += up;
+        }
+        if (i < nb) pre[i] = carry + inc - c;
+        carry += __shfl(inc, 63);
+    }
+    if (lane == 0) pre[nb] = carry;
+    __syncthreads();
+    const int V = carry;
+    const int count = V < S ? V : S;
+    const uint32_t stride = (V > S) ? (uint32_t)(V / S) : 1u;
+    for (int j = lane; j < S; j += 64) {
+        uint32_t slot = GRAB_EMPTY;
+        if (j < count) {
+            int64_t pos = j;
+            if (V > S) pos = ((int64_t)j * V) / S + (int64_t)(mix32((uint32_t)j ^ salt) % stride);
+            int l = 0, r = nb;  // last selected bucket whose prefix <= pos
+            while (r - l > 1) {
+                int m = (l + r) >> 1;
+                if (pre[m] <= pos) l = m; else r = m;
+            }
+            int off = (int)(pos - pre[l]);
+            int b = b0 + l;
+            if (b == b0) slot = off < se0 - sa0 ? base0 + sa0 + off : base0 + ns0 + (off - (se0 - sa0));
+            else if (b == b1) slot = off < se1 ? base1 + off : base1 + ns1 + (off - se1);
+            else slot = table[T_COLS * b + T_BASE] + off;
+        }
+        seeds[q * S + j] = slot;
+    }
+    if (lane == 0) {
+        p.V = V; p.n_seeds = count;
+        p.s0 = base0 + sa0; p.e0 = base0 + se0;
+        p.t0s = base0 + ns0; p.t0e = base0 + ns0 + tail0;
+        if (b1 > b0) {
+            p.ms = table[T_COLS * (b0 + 1) + T_BASE];
+            p.e1 = base1 + se1;
+            p.t1s = base1 + ns1; p.t1e = base1 + ns1 + tail1;
+        }
+        p.first_valid = p.s0;
+        p.end_valid = b1 > b0 ? p.e1 : p.e0;
+        plans[q] = p;
+    }
+}
+
+// ------------------------------------------------------------------------------- beam search
+struct BeamArgs {
+    const float *X;
+    const int32_t *attr;
+    const uint32_t *A;
+    const uint32_t *slot2id;
+    const float *queries;
+    const int32_t *lo, *hi;
+    const QueryPlan *plans;
+    const uint32_t *seeds;
+    uint32_t *counters;
+    uint32_t *out_ids;
+    float *out_dist;
+    int32_t K, k, beam, QP, width, max_iter, S, visited_cap, hbits, maxc, metric, out_slots;
+};
+
+// scalar pre-check (Algorithm 2, the range test ahead of ComputeDistance) from slot
+// intervals; reads the attribute only for slots in the appended tail of an edge bucket
+__device__ __forceinline__ bool precheck(const QueryPlan &p, uint32_t v, const int32_t *__restrict__ attr, int lo,
+                                         int hi, bool &tail) {
+    const int s = (int)v;
+    tail = false;
+    if (s >= p.s0 && s < p.e0) return true;
+    if (s >= p.ms && s < p.e1) return true;
+    if ((s >= p.t0s && s < p.t0e) || (s >= p.t1s && s < p.t1e)) {
+        tail = true;
+        int a = attr[s];
+        return a >= lo && a <= hi;
+    }
+    return false;
+}
+
+// exact visited set: open addressing, linear probing, one LDS compare-and-swap per probe
+__device__ __forceinline__ bool visited_insert(uint32_t *tab, uint32_t mask, int shift, uint32_t v) {
+    uint32_t h = (v * 0x9E3779B1u) >> shift;
+    for (uint32_t probe = 0; probe <= mask; ++probe) {
+        uint32_t old = atomicCAS(&tab[h], GRAB_EMPTY, v);
+        if (old == GRAB_EMPTY) return true;
+        if (old == v) return false;
+        h = (h + 1) & mask;
+    }
+    return false;
+}
+
+__device__ __forceinline__ void cmpx(u64 *a, int i, int l, bool up) {
+    u64 x = a[i], y = a[l];
+    if ((x > y) == up) { a[i] = y; a[l] = x; }
+}
+
+// ascending bitonic sort of a[0..n), n a power of two >= 2, by one wavefront
+__device__ void bitonic_sort(u64 *a, int n, int lane) {
+    for (int k = 2; k <= n; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int t = lane; t < (n >> 1); t += 64) {
+                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+                cmpx(a, i, i | j, (i & k) == 0);
+            }
+            __syncthreads();
+        }
+}
+
+// Q (sorted, QP entries) <- the QP smallest of Q and C (sorted, CP entries), sorted; then cut to beam
+__device__ void merge_queue(u64 *Q, int QP, const u64 *C, int CP, int beam, int lane) {
+    for (int i = lane; i < QP; i += 64) {
+        int r = QP - 1 - i;
+        u64 c = r < CP ? C[r] : SENT;
+        u64 q = Q[i];
+        Q[i] = q < c ? q : c;  // min against the reversed other list: bitonic, holds the QP smallest
+    }
+    __syncthreads();
+    for (int j = QP >> 1; j > 0; j >>= 1) {
+        for (int t = lane; t < (QP >> 1); t += 64) {
+            int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
+            cmpx(Q, i, i | j, true);
+        }
+        __syncthreads();
+    }
+    if (beam < QP) {
+        for (int i = beam + lane; i < QP; i += 64) Q[i] = SENT;
+        __syncthreads();
+    }
+}
+
+template <int NCH>
+struct EvalShape {
+    // pieces of a row held in registers at once, and rows per lane group in flight
+    static constexpr int CB = NCH <= 8 ? NCH
+                              : (NCH % 10 == 0 ? 10 : (NCH % 8 == 0 ? 8 : (NCH % 6 == 0 ? 6 : (NCH % 4 == 0 ? 4 : (NCH % 3 == 0 ? 3 : (NCH % 2 == 0 ? 2 : 1))))));
+    static constexpr int R0 = 16 / CB;
+    static constexpr int R = R0 < 1 ? 1 : (R0 > 8 ? 8 : R0);
+    static constexpr bool QREG = NCH <= 8;
+};
+
+// Gathered distances (Algorithm 2, ComputeDistance) for the n slots in L: eight lanes share a
+// row, lane `sub` of a group takes the 16-byte pieces 8c+sub (one 128-byte line per piece
+// index across the group) and accumulates them in index order with fused multiply-adds; the
+// eight partial sums are combined by an xor-butterfly (1, 2, 4).  This fixed order makes the
+// fp32 result reproducible bit for bit.  Writes the keys to C[0..n).
+template <int NCH>
+__device__ __forceinline__ void eval_rows(const float *__restrict__ X, const float4 *qreg, const float *qlds,
+                                          const uint32_t *L, int n, u64 *C, int lane, int metric) {
+    constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R;
+    constexpr int D4 = NCH * 8;  // 16-byte pieces per row
+    const int sub = lane & 7, grp = lane >> 3;
+    for (int base = 0; base < n; base += 8 * R) {
+        float acc[R];
+        uint32_t v[R];
+        bool act[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int idx = base + r * 8 + grp;
+            act[r] = idx < n;
+            v[r] = act[r] ? L[idx] : 0u;
+            acc[r] = 0.0f;
+        }
+#pragma unroll
+        for (int c0 = 0; c0 < NCH; c0 += CB) {
+            float4 buf[R][CB];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v[r] * D4 + sub;
+#pragma unroll
+                for (int cc = 0; cc < CB; ++cc)
+                    buf[r][cc] = act[r] ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int cc = 0; cc < CB; ++cc) {
+                float4 qv;
+                if constexpr (EvalShape<NCH>::QREG) qv = qreg[c0 + cc];
+                else qv = reinterpret_cast<const float4 *>(qlds)[(c0 + cc) * 8 + sub];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float4 x = buf[r][cc];
+                    if (metric == GRAB_L2SQ) {
+                        float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+                        acc[r] = __builtin_fmaf(dx, dx, acc[r]);
+                        acc[r] = __builtin_fmaf(dy, dy, acc[r]);
+                        acc[r] = __builtin_fmaf(dz, dz, acc[r]);
+                        acc[r] = __builtin_fmaf(dw, dw, acc[r]);
+                    } else {
+                        acc[r] = __builtin_fmaf(qv.x, x.x, acc[r]);
+                        acc[r] = __builtin_fmaf(qv.y, x.y, acc[r]);
+                        acc[r] = __builtin_fmaf(qv.z, x.z, acc[r]);
+                        acc[r] = __builtin_fmaf(qv.w, x.w, acc[r]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float s = acc[r];
+            s += __shfl_xor(s, 1);
+            s += __shfl_xor(s, 2);
+            s += __shfl_xor(s, 4);
+            if (metric != GRAB_L2SQ) s = -s;
+            if (act[r] && sub == 0) C[base + r * 8 + grp] = make_key(s, v[r]);
+        }
+    }
+}
+
+template <int NCH>
+__global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int D = NCH * 32;
+    const int lane = threadIdx.x;
+    const int64_t q = blockIdx.x;
+    const int H = 1 << a.hbits;
+    u64 *Q = reinterpret_cast<u64 *>(smem);
+    u64 *C = Q + a.QP;
+    uint32_t *hash = reinterpret_cast<uint32_t *>(C + a.maxc);
+    uint32_t *L = hash + H;
+    uint32_t *par = L + a.maxc;   // 8 parent slots + 8 queue positions
+    float *qlds = reinterpret_cast<float *>(par + 16);
+
+    const QueryPlan p = a.plans[q];
+    const int lo = a.lo[q], hi = a.hi[q];
+    uint32_t c_iters = 0, c_par = 0, c_evals = 0, c_seed = 0, c_rej = 0, c_tail = 0, c_vis = 0, c_stop = 0;
+
+    // query row -> registers (or LDS for long rows), in the piece order eval_rows uses
+    float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
+    {
+        const float4 *qsrc = reinterpret_cast<const float4 *>(a.queries + q * D);
+        if constexpr (EvalShape<NCH>::QREG) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) qreg[c] = qsrc[c * 8 + (lane & 7)];
+        } else {
+            for (int i = lane; i < D / 4; i += 64) reinterpret_cast<float4 *>(qlds)[i] = qsrc[i];
+        }
+    }
+    for (int i = lane; i < H / 4; i += 64) reinterpret_cast<uint4 *>(hash)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
+    for (int i = lane; i < a.QP; i += 64) Q[i] = SENT;
+    __syncthreads();
+
+    const uint32_t hmask = (uint32_t)H - 1;
+    const int hshift = 32 - a.hbits;
+    const u64 lt_mask = (1ull << lane) - 1ull;
+
+    if (p.b1 < p.b0) {
+        c_stop = 3;
+    } else {
+        // ---- seeds (Algorithm 2, lines 2-3), in chunks of maxc
+        const uint32_t *sd = a.seeds + q * a.S;
+        for (int s0 = 0; s0 < p.n_seeds; s0 += a.maxc) {
+            const int lim = min(p.n_seeds, s0 + a.maxc);
+            int n_c = 0;
+            for (int e0 = s0; e0 < lim; e0 += 64) {
+                const int e = e0 + lane;
+                uint32_t v = e < lim ? sd[e] : GRAB_EMPTY;
+                bool tail = false, ok = false;
+                if (v != GRAB_EMPTY) ok = precheck(p, v, a.attr, lo, hi, tail);
+                c_tail += __popcll(__ballot(tail));
+                bool fresh = ok && visited_insert(hash, hmask, hshift, v);
+                u64 m = __ballot(fresh);
+                if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
+                n_c += __popcll(m);
+            }
+            __syncthreads();
+            if (n_c > 0) {
+                c_vis += n_c; c_evals += n_c; c_seed += n_c;
+                eval_rows<NCH>(a.X, qreg, qlds, L, n_c, C, lane, a.metric);
+                int CP = 2;
+                while (CP < n_c) CP <<= 1;
+                for (int i = n_c + lane; i < CP; i += 64) C[i] = SENT;
+                __syncthreads();
+                bitonic_sort(C, CP, lane);
+                merge_queue(Q, a.QP, C, CP, a.beam, lane);
+            }
+        }
+        // ---- greedy expansion (Algorithm 2, the while loop)
+        const uint32_t recipK = (65536u + (uint32_t)a.K - 1u) / (uint32_t)a.K;
+        while (true) {
+            if ((int)c_iters == a.max_iter) { c_stop = 1; break; }
+            // PopUnvisited: first `width` queue entries not yet expanded
+            int np = 0;
+            for (int c = 0; c < a.QP && np < a.width; c += 64) {
+                u64 key = Q[c + lane];
+                u64 m = __ballot(key != SENT && !(key & 1ull));
+                while (m && np < a.width) {
+                    int b = __ffsll((long long)m) - 1;
+                    m &= m - 1;
+                    if (lane == b) { par[np] = key_slot(key); par[8 + np] = (uint32_t)(c + lane); }
+                    ++np;
+                }
+            }
+            if (np == 0) break;
+            if ((int)c_vis + np * a.K > a.visited_cap) { c_stop = 2; break; }
+            __syncthreads();
+            if (lane < np) Q[par[8 + lane]] |= 1ull;
+            c_iters += 1; c_par += np;
+            // GatherNeighbors + pre-check + visited test, all parents' rows at once
+            const int total = np * a.K;
+            int n_c = 0;
+            for (int e0 = 0; e0 < total; e0 += 64) {
+                const int e = e0 + lane;
+                uint32_t v = GRAB_EMPTY;
+                if (e < total) {
+                    uint32_t pi = ((uint32_t)e * recipK) >> 16;
+                    uint32_t j = (uint32_t)e - pi * (uint32_t)a.K;
+                    v = a.A[(size_t)par[pi] * a.K + j];
+                }
+                bool tail = false, ok = false;
+                const bool live = v != GRAB_EMPTY;
+                if (live) ok = precheck(p, v, a.attr, lo, hi, tail);
+                c_rej += __popcll(__ballot(live && !ok));
+                c_tail += __popcll(__ballot(tail));
+                bool fresh = ok && visited_insert(hash, hmask, hshift, v);
+                u64 m = __ballot(fresh);
+                if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
+                n_c += __popcll(m);
+            }
+            __syncthreads();
+            if (n_c > 0) {
+                c_vis += n_c; c_evals += n_c;
+                eval_rows<NCH>(a.X, qreg, qlds, L, n_c, C, lane, a.metric);
+                int CP = 2;
+                while (CP < n_c) CP <<= 1;
+                for (int i = n_c + lane; i < CP; i += 64) C[i] = SENT;
+                __syncthreads();
+                bitonic_sort(C, CP, lane);
+                merge_queue(Q, a.QP, C, CP, a.beam, lane);   // UpdateQueue
+            }
+        }
+    }
+    // ---- Top-k from the queue
+    for (int j = lane; j < a.k; j += 64) {
+        u64 key = Q[j];
+        uint32_t id = GRAB_EMPTY;
+        float d = __builtin_inff();
+        if (key != SENT) {
+            uint32_t slot = key_slot(key);
+            id = a.out_slots ? slot : a.slot2id[slot];
+            d = image_dist((uint32_t)(key >> 32));
+        }
+        a.out_ids[q * a.k + j] = id;
+        a.out_dist[q * a.k + j] = d;
+    }
+    if (lane < 8) {
+        uint32_t val = lane == 0 ? c_iters : lane == 1 ? c_par : lane == 2 ? c_evals : lane == 3 ? c_seed
+                     : lane == 4 ? c_rej : lane == 5 ? c_tail : lane == 6 ? c_vis : c_stop;
+        a.counters[q * 8 + lane] = val;
+    }
+}
+
+template <int NCH>
+grab_status launch_beam_t(grab_index *ix, const BeamArgs &a, int64_t nq, size_t lds) {
+    if (lds > 64 * 1024) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_search<NCH>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return grab_fail(ix, GRAB_EHIP, "LDS request of %zu bytes refused: %s", lds, hipGetErrorString(e));
+    }
+    k_beam_search<NCH><<<dim3((unsigned)nq), dim3(64), lds, ix->stream>>>(a);
+    GRAB_HIP(ix, hipGetLastError());
+    return GRAB_OK;
+}
+
+inline int pow2_at_least(int x, int floor_) {
+    int p = floor_;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+}  // namespace
+
+grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
+    if (s.nq == 0) return GRAB_OK;
+    k_select_seed<<<dim3((unsigned)s.nq), dim3(64), 0, ix->stream>>>(ix->table, ix->B, ix->attr, s.lo, s.hi, s.only_bucket,
+                                                                    s.n_seeds, s.salt, s.plans, s.seeds);
+    GRAB_HIP(ix, hipGetLastError());
+    return GRAB_OK;
+}
+
+grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s) {
+    if (s.nq == 0) return GRAB_OK;
+    BeamArgs a;
+    a.X = ix->X; a.attr = ix->attr; a.A = ix->A; a.slot2id = ix->slot2id;
+    a.queries = s.queries; a.lo = s.lo; a.hi = s.hi; a.plans = s.plans; a.seeds = s.seeds;
+    a.counters = s.counters; a.out_ids = s.out_ids; a.out_dist = s.out_dist;
+    a.K = ix->kl + ix->kr; a.k = s.k; a.beam = s.beam; a.QP = pow2_at_least(s.beam, 64);
+    a.width = s.width; a.max_iter = s.max_iter; a.S = s.n_seeds; a.visited_cap = s.visited_cap;
+    // table at most 3/4 full when the capacity rule stops the search
+    int H = pow2_at_least((int)(((int64_t)s.visited_cap * 4 + 2) / 3) + 1, 256);
+    a.hbits = 0;
+    while ((1 << a.hbits) < H) ++a.hbits;
+    a.maxc = pow2_at_least(s.width * a.K, 64);
+    a.metric = ix->metric; a.out_slots = s.out_slots ? 1 : 0;
+    const int nch = ix->dim / 32;
+    size_t lds = (size_t)a.QP * 8 + (size_t)a.maxc * 8 + (size_t)H * 4 + (size_t)a.maxc * 4 + 16 * 4;
+    if (nch > 8) lds += (size_t)ix->dim * 4;
+    switch (nch) {
+#define GRAB_CASE(N) case N: return launch_beam_t<N>(ix, a, s.nq, lds);
+        GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
+        GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
+#undef GRAB_CASE
+        default:
+            return grab_fail(ix, GRAB_EINVAL, "dim %d has no search kernel (supported: 32,64,96,128,256,512,768,960,1024,1536,2048)", ix->dim);
+    }
+}
