@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the range-filtered search hot path on one MI355X.
+
+One step = one `grab_search_range` call (bucket-select + seeding kernel, then the
+wave-per-query beam-search kernel) over the whole query batch of the headline workload:
+1,000,000 x 128 fp32 base vectors (256-component Gaussian mixture), uniform integer attribute,
+64 buckets, local degree 32 + remote degree 8, 10,000 queries with 10 % ranges, k = 10.
+All inputs are seeded synthetic data resident in HBM before the timed region.
+
+The search parameters (beam, seeds, width, visited capacity) are the fastest of a small grid
+whose measured Recall@10 against exhaustive filtered k-NN is at least 0.95, which is how the
+paper reports "QPS at Recall@95 %" (Section 5.2).  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBS = 8000.0
+METRIC = "filtered queries/sec at recall@10>=0.95 (1M x 128 fp32, 10% range), % peak HBM BW"
+
+# (beam, n_seeds, search_width, visited_cap)
+GRID = [
+    (64, 64, 1, 2800), (64, 128, 1, 1400), (64, 256, 1, 1400), (64, 256, 2, 1400), (64, 256, 4, 1400),
+    (64, 512, 1, 1400), (64, 512, 2, 1400), (64, 512, 4, 1400), (32, 512, 2, 1400), (32, 512, 4, 1400),
+    (48, 384, 4, 1400), (64, 384, 4, 1400), (64, 1024, 4, 2800), (128, 256, 4, 2800),
+]
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--selectivity", type=float, default=0.1)
+    ap.add_argument("--scale", type=int, default=0, help="shrink the workload to this many base vectors (debug)")
+    ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap: skip the grid")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2604_16402_amd import binding, groundtruth as GT, workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the search path has no CPU fallback", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS[args.workload]
+    if args.scale:
+        cfg = W.scaled(cfg, args.scale)
+    K = cfg.k_local + cfg.k_remote
+    k = cfg.k
+
+    t0 = time.time()
+    X = W.base_vectors(cfg)
+    attrs = W.attributes(cfg)
+    q = W.query_vectors(cfg)
+    lo, hi = W.ranges(cfg, args.selectivity)
+    log(f"[bench] inputs generated in {time.time() - t0:.1f}s: {cfg.name} n={cfg.n} d={cfg.dim} nq={len(q)}")
+
+    stream = torch.cuda.current_stream(dev)
+    ix = binding.Index(cfg.dim, cfg.metric, stream=stream.cuda_stream)
+    Xd, ad = torch.from_numpy(X).to(dev), torch.from_numpy(attrs).to(dev)
+    t0 = time.time()
+    ix.build_buckets(Xd, ad, cfg.buckets)
+    table, id2slot, _ = ix.get_layout()
+    ends = table[:, 0].astype(np.int64) + table[:, 3]
+    bucket_of = np.searchsorted(ends, id2slot.astype(np.int64), side="right")
+    la, ra = W.build_graph(X, bucket_of, cfg.buckets, cfg.k_local, cfg.k_remote, metric=cfg.metric,
+                           device="cuda:0", chunk=16384)
+    ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
+    torch.cuda.synchronize()
+    log(f"[bench] index + harness graph built in {time.time() - t0:.1f}s")
+
+    qd = torch.from_numpy(q).to(dev)
+    lod, hid = torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)
+    gt = GT.exact_filtered_knn(Xd, ad, qd, lod, hid, k, cfg.metric)
+    nq = len(q)
+    ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
+    dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
+
+    def set_cfg(c):
+        beam, S, w, vc = c
+        ix.set_param("visited_cap", max(vc, S))
+        ix.set_param("n_seeds", S)
+        ix.set_param("search_width", w)
+        return beam
+
+    def run_once(beam):
+        ix.search_range(qd, lod, hid, k, beam, ids, dist)
+
+    def timed(beam, reps):
+        run_once(beam)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(reps):
+            run_once(beam)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t) / reps
+
+    # ---- pick the fastest setting with Recall@10 >= 0.95 (Section 5.2 protocol)
+    if args.config:
+        chosen = tuple(int(x) for x in args.config.split(","))
+        beam = set_cfg(chosen)
+        run_once(beam)
+        torch.cuda.synchronize()
+        chosen_recall = GT.recall(ids, gt)
+    else:
+        best = None
+        for c in GRID:
+            beam = set_cfg(c)
+            sec = timed(beam, 3)
+            rec = GT.recall(ids, gt)
+            log(f"[bench] grid beam={c[0]} seeds={c[1]} width={c[2]} visited_cap={c[3]}: recall@10={rec:.4f} {nq / sec:,.0f} q/s")
+            if rec >= 0.95 and (best is None or sec < best[0]):
+                best = (sec, c, rec)
+        if best is None:
+            log("[bench] no grid point reached recall 0.95; using the widest")
+            c = GRID[-2]
+            beam = set_cfg(c)
+            run_once(beam)
+            torch.cuda.synchronize()
+            best = (0.0, c, GT.recall(ids, gt))
+        chosen, chosen_recall = best[1], best[2]
+    beam = set_cfg(chosen)
+
+    # ---- timed region: W warm-up steps, then exactly K steps
+    for _ in range(args.warmup):
+        run_once(beam)
+    torch.cuda.synchronize()
+    t = time.perf_counter()
+    for _ in range(args.steps):
+        run_once(beam)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t
+    ms_per_step = elapsed / args.steps * 1e3
+    qps = nq * args.steps / elapsed
+
+    # ---- roofline of the dominant kernel (beam search), HIP events on the launch stream
+    ix.set_param("profile", 1)
+    beam_ms, select_ms = [], []
+    for _ in range(max(5, min(args.steps, 20))):
+        run_once(beam)
+        s_ms, b_ms = ix.get_timing()
+        select_ms.append(s_ms)
+        beam_ms.append(b_ms)
+    ix.set_param("profile", 0)
+    ctr = ix.get_counters(nq).astype(np.float64)
+    # algorithmic bytes per query: query row + one feature row per distance evaluation (seeds
+    # included) + one adjacency row per expanded parent + 4 B per tail attribute read + output
+    row = cfg.dim * 4
+    bytes_per_launch = float((row + ctr[:, 2] * row + ctr[:, 1] * K * 4 + ctr[:, 5] * 4 + k * 8).sum())
+    avg_beam_ms = float(np.mean(beam_ms))
+    achieved = bytes_per_launch / (avg_beam_ms * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic_beam_search_c2.json")
+    if os.path.exists(tpath) and args.workload == "c2" and not args.scale:
+        try:
+            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+        except Exception:
+            traffic = None
+    roofline = {"bound": "hbm", "kernel": "k_beam_search<4>", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+                "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
+                "bytes_per_launch": bytes_per_launch, "avg_kernel_ms": round(avg_beam_ms, 4),
+                "select_kernel_ms": round(float(np.mean(select_ms)), 4),
+                "evals_per_query": round(float(ctr[:, 2].mean()), 1), "parents_per_query": round(float(ctr[:, 1].mean()), 1)}
+
+    # ---- CPU baseline: the oracle as it stands, all host cores, same inputs and graph
+    cpu = None
+    parity = None
+    if not args.no_cpu:
+        from oracle import oracle as O
+        t0 = time.time()
+        ora = O.Index(X, attrs, cfg.buckets, metric=cfg.metric)
+        ora.load_graph(la, ra)
+        ora.params.update(search_width=chosen[2], n_seeds=chosen[1], visited_cap=max(chosen[3], chosen[1]))
+        cores = min(O.max_threads(), os.cpu_count() or 1)
+        log(f"[bench] oracle index ready in {time.time() - t0:.1f}s; timing on {cores} threads")
+        sample = nq
+        reps, t_used = 0, 0.0
+        while t_used < 10.0 and reps < 50:
+            t = time.perf_counter()
+            o_ids, o_dist, _ = ora.search(q[:sample], lo[:sample], hi[:sample], k, chosen[0], threads=cores)
+            t_used += time.perf_counter() - t
+            reps += 1
+        cpu = {"value": round(sample * reps / t_used, 1), "unit": "queries/s", "cores": cores, "kind": "oracle",
+               "sample": f"all {sample} queries of the workload x {reps} passes, same graph and parameters, gcc -O2 -ffp-contract=off, OpenMP static"}
+        g_ids = ids.cpu().numpy().view(np.uint32)
+        g_dist = dist.cpu().numpy()
+        parity = {"queries": int(sample), "ids_identical": bool(np.array_equal(g_ids[:sample], o_ids)),
+                  "dist_identical": bool(np.array_equal(g_dist[:sample], o_dist))}
+
+    out = {
+        "metric": METRIC, "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32, {cfg.components}-component Gaussian mixture, "
+                               f"uniform int attribute, {cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, "
+                               f"{nq} queries, {args.selectivity:.0%} range, k={k}",
+                   "beam": chosen[0], "n_seeds": chosen[1], "search_width": chosen[2], "visited_cap": max(chosen[3], chosen[1]),
+                   "recall_at_10": round(chosen_recall, 4)},
+        "roofline": roofline, "cpu_baseline": cpu, "parity_vs_oracle": parity,
+        "hbm_frac_of_peak": round(achieved / PEAK_HBM_GBS, 4),
+    }
+    ix.close()
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -61,7 +61,9 @@ typedef enum {
                                 default 2800, at most 24000                                */
     GRAB_P_SEED_SALT = 4,    /* moves the seed jitter; default 0                           */
     GRAB_P_ALPHA = 5,        /* freshness bias of Eq. 3, in (0, 1]; default 0.6            */
-    GRAB_P_APPEND_BEAM = 6   /* candidate queue size of append's searches; default 64      */
+    GRAB_P_APPEND_BEAM = 6,  /* candidate queue size of append's searches; default 64      */
+    GRAB_P_PROFILE = 7       /* 1: bracket the search kernels with HIP events on the index's
+                                stream so that grab_get_timing can report them; default 0  */
 } grab_param;
 
 /* Creates an empty index for `dim`-dimensional fp32 vectors under `metric`.
@@ -146,6 +148,12 @@ grab_status grab_select_range(grab_index *ix, const int32_t *lo, const int32_t *
  *  (appended tails of the two edge buckets), visited-set size, stop reason
  *  (0 queue exhausted, 1 max_iter, 2 visited capacity, 3 empty range)}. */
 grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq);
+
+/* Kernel durations of the most recent grab_search_range, measured with HIP events on the
+ * index's stream (needs GRAB_P_PROFILE = 1 before that search): ms[0] bucket-select + seeding
+ * kernel, ms[1] beam-search kernel, in milliseconds (host array).  Waits for the search to
+ * finish.  GRAB_ESTATE if profiling was off. */
+grab_status grab_get_timing(grab_index *ix, float ms[2]);
 
 #ifdef __cplusplus
 }

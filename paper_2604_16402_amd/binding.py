@@ -18,14 +18,14 @@ OK, EINVAL, ESTATE, EFULL, ENOMEM, EHIP = range(6)
 STATUS_NAMES = {OK: "GRAB_OK", EINVAL: "GRAB_EINVAL", ESTATE: "GRAB_ESTATE", EFULL: "GRAB_EFULL",
                 ENOMEM: "GRAB_ENOMEM", EHIP: "GRAB_EHIP"}
 L2SQ, IP = 0, 1
-P_SEARCH_WIDTH, P_MAX_ITER, P_N_SEEDS, P_VISITED_CAP, P_SEED_SALT, P_ALPHA, P_APPEND_BEAM = range(7)
+P_SEARCH_WIDTH, P_MAX_ITER, P_N_SEEDS, P_VISITED_CAP, P_SEED_SALT, P_ALPHA, P_APPEND_BEAM, P_PROFILE = range(8)
 PARAMS = dict(search_width=P_SEARCH_WIDTH, max_iter=P_MAX_ITER, n_seeds=P_N_SEEDS, visited_cap=P_VISITED_CAP,
-              seed_salt=P_SEED_SALT, alpha=P_ALPHA, append_beam=P_APPEND_BEAM)
+              seed_salt=P_SEED_SALT, alpha=P_ALPHA, append_beam=P_APPEND_BEAM, profile=P_PROFILE)
 EMPTY = 0xFFFFFFFF
 
 EXPORTS = ["grab_create", "grab_destroy", "grab_last_error", "grab_build_buckets", "grab_load_graph",
            "grab_search_range", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
-           "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters"]
+           "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing"]
 
 _lib = None
 
@@ -62,6 +62,7 @@ def load_library() -> ctypes.CDLL:
     lib.grab_get_rows.argtypes = [vp, vp, vp]
     lib.grab_select_range.argtypes = [vp, vp, vp, i64, i32, vp, vp]
     lib.grab_get_counters.argtypes = [vp, vp, i64]
+    lib.grab_get_timing.argtypes = [vp, vp]
     for name in EXPORTS:
         if name not in ("grab_destroy", "grab_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -195,3 +196,9 @@ class Index:
         out = np.empty((nq, 8), dtype=np.uint32)
         self._check(self._lib.grab_get_counters(self._h, out.ctypes.data, nq))
         return out
+
+    def get_timing(self):
+        """(select_ms, beam_ms) of the last search; needs set_param("profile", 1) before it."""
+        out = np.zeros(2, dtype=np.float32)
+        self._check(self._lib.grab_get_timing(self._h, out.ctypes.data))
+        return float(out[0]), float(out[1])

@@ -96,6 +96,8 @@ void grab_destroy(grab_index *ix) {
     DevBuf *bufs[] = {&ix->plans, &ix->seeds, &ix->counters, &ix->stage_q, &ix->stage_lo, &ix->stage_hi,
                       &ix->stage_ids, &ix->stage_dist, &ix->stage_misc, &ix->flags};
     for (DevBuf *b : bufs) free_buf(*b);
+    for (hipEvent_t e : ix->ev)
+        if (e) (void)hipEventDestroy(e);
     delete ix;
 }
 
@@ -126,6 +128,12 @@ grab_status grab_set_param(grab_index *ix, int32_t which, double value) {
         case GRAB_P_APPEND_BEAM:
             if (value < 1 || value > GRAB_MAX_BEAM) return grab_fail(ix, GRAB_EINVAL, "append_beam must be 1..512");
             p.append_beam = (int32_t)value; return GRAB_OK;
+        case GRAB_P_PROFILE:
+            if (value != 0.0 && value != 1.0) return grab_fail(ix, GRAB_EINVAL, "profile must be 0 or 1");
+            if (value == 1.0)
+                for (hipEvent_t &e : ix->ev)
+                    if (!e) GRAB_HIP(ix, hipEventCreate(&e));
+            ix->profile = value == 1.0; return GRAB_OK;
         default:
             return grab_fail(ix, GRAB_EINVAL, "unknown parameter %d", which);
     }
@@ -262,8 +270,12 @@ grab_status grab_search_range(grab_index *ix, const float *queries, const int32_
     s.plans = (QueryPlan *)ix->plans.p; s.seeds = (uint32_t *)ix->seeds.p; s.counters = (uint32_t *)ix->counters.p;
     s.out_ids = ids_dev ? out_ids : (uint32_t *)ix->stage_ids.p;
     s.out_dist = dist_dev ? out_dist : (float *)ix->stage_dist.p;
+    ix->timed = false;
+    if (ix->profile) GRAB_HIP(ix, hipEventRecord(ix->ev[0], ix->stream));
     if ((st = grab_launch_select(ix, s)) != GRAB_OK) return st;
+    if (ix->profile) GRAB_HIP(ix, hipEventRecord(ix->ev[1], ix->stream));
     if ((st = grab_launch_beam(ix, s)) != GRAB_OK) return st;
+    if (ix->profile) { GRAB_HIP(ix, hipEventRecord(ix->ev[2], ix->stream)); ix->timed = true; }
     ix->last_nq = nq;
     if (!ids_dev) GRAB_HIP(ix, hipMemcpyAsync(out_ids, s.out_ids, (size_t)nq * k * 4, hipMemcpyDeviceToHost, ix->stream));
     if (!dist_dev) GRAB_HIP(ix, hipMemcpyAsync(out_dist, s.out_dist, (size_t)nq * k * 4, hipMemcpyDeviceToHost, ix->stream));
@@ -353,6 +365,16 @@ grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq) {
     if (nq == 0) return GRAB_OK;
     GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
     GRAB_HIP(ix, hipMemcpy(per_query, ix->counters.p, (size_t)nq * 8 * 4, hipMemcpyDefault));
+    return GRAB_OK;
+}
+
+grab_status grab_get_timing(grab_index *ix, float ms[2]) {
+    if (!ix) return GRAB_EINVAL;
+    if (!ms) return grab_fail(ix, GRAB_EINVAL, "null argument");
+    if (!ix->timed) return grab_fail(ix, GRAB_ESTATE, "the last search was not profiled");
+    GRAB_HIP(ix, hipEventSynchronize(ix->ev[2]));
+    GRAB_HIP(ix, hipEventElapsedTime(&ms[0], ix->ev[0], ix->ev[1]));
+    GRAB_HIP(ix, hipEventElapsedTime(&ms[1], ix->ev[1], ix->ev[2]));
     return GRAB_OK;
 }
 

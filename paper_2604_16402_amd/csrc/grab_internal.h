@@ -73,6 +73,10 @@ struct grab_index {
     // grow-only work buffers
     DevBuf plans, seeds, counters, stage_q, stage_lo, stage_hi, stage_ids, stage_dist, stage_misc, flags;
     int64_t last_nq = 0;
+
+    bool profile = false;
+    bool timed = false;          // the last search recorded events
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
 };
 
 // error plumbing ------------------------------------------------------------------------
