@@ -49,6 +49,8 @@ def main():
     ap.add_argument("--scale", type=int, default=0, help="shrink the workload to this many base vectors (debug)")
     ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap: skip the grid")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy five times (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
@@ -87,6 +89,14 @@ def main():
     ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
     torch.cuda.synchronize()
     log(f"[bench] index + harness graph built in {time.time() - t0:.1f}s")
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     qd = torch.from_numpy(q).to(dev)
     lod, hid = torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)

@@ -77,3 +77,153 @@ def test_search_matches_oracle_exactly(c1_small, torch_dev, beam, width):
     assert np.array_equal(dist, want_dist)           # fp32 bits equal: same summation tree
     assert np.array_equal(ids, want_ids)
     assert np.array_equal(ctr, want_ctr)             # same traversal, step for step
+
+
+def _random_case(n, dim, B, kl, kr, metric, seed, n_cap=None, nq=300, domain=None):
+    cfg = W.Config(f"t{seed}", n, dim, 8, 0.4, domain or n, B, kl, kr, nq, (0.2,), metric=metric,
+                   normalise=(metric == W.IP), seed=seed)
+    X, a, q = W.base_vectors(cfg), W.attributes(cfg), W.query_vectors(cfg)
+    ora = O.Index(X, a, B, n_cap=n_cap, metric=metric)
+    la, ra = W.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric)
+    ora.load_graph(la, ra)
+    return dict(cfg=cfg, X=X, attrs=a, queries=q, local=la, remote=ra, oracle=ora)
+
+
+@pytest.mark.parametrize("dim,metric,n,B,kl,kr,n_cap", [
+    (32, W.L2SQ, 3001, 7, 12, 3, None),        # ragged sizes, one 128-byte line per row
+    (64, W.L2SQ, 2500, 5, 16, 4, 3100),        # slack between slabs
+    (96, W.IP, 4000, 9, 24, 8, None),          # inner product on unit vectors, 3 lines per row
+    (256, W.L2SQ, 1500, 4, 20, 2, None),       # 8 lines per row (still register-resident query)
+    (960, W.L2SQ, 1200, 3, 48, 8, None),       # 30 lines per row, query staged in LDS
+    (128, W.L2SQ, 2000, 4, 61, 3, None),       # degree 64
+])
+def test_other_shapes_match_oracle(torch_dev, dim, metric, n, B, kl, kr, n_cap):
+    c = _random_case(n, dim, B, kl, kr, metric, seed=dim + n, n_cap=n_cap)
+    ix = _gpu_index(c, torch_dev, n_cap)
+    ora = c["oracle"]
+    table, id2slot, slot2id = ix.get_layout()
+    assert np.array_equal(table, ora.table) and np.array_equal(slot2id, ora.slot2id)
+    rng = np.random.default_rng(dim)
+    nq = len(c["queries"])
+    width = rng.integers(1, n, nq)
+    lo = rng.integers(-10, n, nq).astype(np.int32)
+    hi = (lo + width).astype(np.int32)
+    for beam, w, S in [(64, 1, 0), (33, 3, 200)]:
+        if w * (kl + kr) > 512:
+            continue
+        ix.set_param("search_width", w); ix.set_param("n_seeds", S)
+        ora.params.update(search_width=w, n_seeds=S or None)
+        ids, dist, ctr = _search_gpu(ix, torch_dev, c["queries"], lo, hi, 10, beam)
+        want_ids, want_dist, want_ctr = ora.search(c["queries"], lo, hi, 10, beam)
+        assert np.array_equal(dist, want_dist), (beam, w, S)
+        assert np.array_equal(ids, want_ids), (beam, w, S)
+        assert np.array_equal(ctr, want_ctr), (beam, w, S)
+    ix.close()
+
+
+def test_edge_cases(c1_small, torch_dev):
+    import torch
+    c = c1_small
+    ix = _gpu_index(c, torch_dev)
+    ora = c["oracle"]
+    q = c["queries"][:8]
+    # empty, inverted and out-of-domain ranges; single-value range; whole domain
+    lo = np.array([10, 20000, -5, 5000, 0, 9999, 777, -100], np.int32)
+    hi = np.array([5, 30000, -1, 5000, 9999, 9999, 790, 100000], np.int32)
+    ids, dist, ctr = _search_gpu(ix, torch_dev, q, lo, hi, 10, 64)
+    want = ora.search(q, lo, hi, 10, 64)
+    assert np.array_equal(ids, want[0]) and np.array_equal(dist, want[1]) and np.array_equal(ctr, want[2])
+    assert (ids[:3] == 0xFFFFFFFF).all() and np.isinf(dist[:3]).all() and (ctr[:3, 7] == 3).all()
+    # V <= S: the answer is the exhaustive filtered k-NN
+    rng = np.random.default_rng(3)
+    lo2 = rng.integers(0, 9900, 256).astype(np.int32)
+    hi2 = (lo2 + rng.integers(0, 50, 256)).astype(np.int32)
+    ids2, dist2, _ = _search_gpu(ix, torch_dev, c["queries"][:256], lo2, hi2, 10, 64)
+    gt, _ = O.exact_filtered_knn(c["X"], c["attrs"], c["queries"][:256], lo2, hi2, 10)
+    small = np.array([((c["attrs"] >= l) & (c["attrs"] <= h)).sum() <= 64 for l, h in zip(lo2, hi2)])
+    assert small.sum() > 100 and np.array_equal(ids2[small], gt[small])
+    # k == beam, k == 1, host (numpy) buffers in and out, a single query, no query
+    for k, beam in [(16, 16), (1, 64), (64, 64)]:
+        got_ids, got_dist = ix.search_range(q, lo, hi, k, beam)
+        w_ids, w_dist, _ = ora.search(q, lo, hi, k, beam)
+        assert np.array_equal(got_ids, w_ids) and np.array_equal(got_dist, w_dist)
+    one_ids, one_dist = ix.search_range(q[4:5], lo[4:5], hi[4:5], 10, 64)
+    assert np.array_equal(one_ids, want[0][4:5]) and np.array_equal(one_dist, want[1][4:5])
+    none_ids, _ = ix.search_range(q[:0], lo[:0], hi[:0], 10, 64)
+    assert none_ids.shape == (0, 10)
+    # stopping rules: iteration cap and visited capacity
+    for name, val, oname in [("max_iter", 3, "max_iter"), ("visited_cap", 150, "visited_cap")]:
+        ix.set_param(name, val); ora.params[oname] = val
+        g = _search_gpu(ix, torch_dev, c["queries"][:200], c["lo"][:200], c["hi"][:200], 10, 64)
+        w = ora.search(c["queries"][:200], c["lo"][:200], c["hi"][:200], 10, 64)
+        assert all(np.array_equal(x, y) for x, y in zip(g, w))
+        ix.set_param("max_iter", 0); ix.set_param("visited_cap", 2800)
+        ora.params.update(max_iter=None, visited_cap=2800)
+    # argument errors are reported, not executed
+    from paper_2604_16402_amd import binding as B
+    for k, beam in [(0, 64), (65, 64), (10, 1000)]:
+        with pytest.raises(B.GrabError) as e:
+            ix.search_range(q, lo, hi, k, beam)
+        assert e.value.status == B.EINVAL
+    ix.set_param("n_seeds", 5000)
+    with pytest.raises(B.GrabError) as e:
+        ix.search_range(q, lo, hi, 10, 64)
+    assert e.value.status == B.EINVAL
+    ix.close()
+
+
+def test_malformed_graph_is_rejected(c1_small, torch_dev):
+    from paper_2604_16402_amd import binding as B
+    c = c1_small
+    ix = _gpu_index(c, torch_dev)
+    ora = c["oracle"]
+    bad = c["local"].copy()
+    other = np.nonzero(ora.bucket_of_ids() != ora.bucket_of_ids()[0])[0][0]
+    bad[0, 0] = other                                     # a local edge that leaves its bucket
+    with pytest.raises(B.GrabError) as e:
+        ix.load_graph(bad, c["remote"])
+    assert e.value.status == B.EINVAL and ix.sizes()["has_graph"] == 0
+    bad = c["remote"].copy()
+    bad[5, 0] = 10_000_000                                 # id out of range
+    with pytest.raises(B.GrabError) as e:
+        ix.load_graph(c["local"], bad)
+    assert e.value.status == B.EINVAL
+    ix.load_graph(c["local"], c["remote"])                 # a good graph still loads afterwards
+    assert ix.sizes()["has_graph"] == 1
+    ix.close()
+
+
+def test_hand_traced_example_on_gpu(torch_dev):
+    import json, os
+    g = json.load(open(os.path.join(os.path.dirname(__file__), "golden", "trace_2d.json")))
+    pts = np.zeros((8, 32), np.float32); pts[:, :2] = np.asarray(g["points"], np.float32)
+    qv = np.zeros((1, 32), np.float32); qv[0, :2] = g["query"]
+    from paper_2604_16402_amd import binding as B
+    ix = B.Index(32)
+    ix.build_buckets(pts, np.asarray(g["attrs"], np.int32), g["n_buckets"])
+    ix.load_graph(np.asarray(g["local"], np.uint32), np.asarray(g["remote"], np.uint32))
+    ix.set_param("n_seeds", g["n_seeds"])
+    info, seeds = ix.select_range(np.array([g["lo"]], np.int32), np.array([g["hi"]], np.int32), g["beam"])
+    e = g["expected_select"]
+    assert info[0].tolist() == [e["b0"], e["b1"], e["V"], e["first_valid_slot"], e["end_valid_slot"], len(e["seeds"])]
+    assert seeds[0].tolist() == e["seeds"]
+    for case in g["cases"]:
+        if case["max_iter"] == 0:
+            continue                                       # 0 means "default" at the C boundary
+        ix.set_param("max_iter", case["max_iter"]); ix.set_param("visited_cap", case["visited_cap"])
+        ids, dist = ix.search_range(qv, np.array([g["lo"]], np.int32), np.array([g["hi"]], np.int32), g["k"], g["beam"])
+        assert ids[0].tolist() == case["ids"] and dist[0].tolist() == case["dist"]
+        ctr = ix.get_counters(1)[0]
+        names = ["iters", "parents", "evals", "seed_evals", "rejects", "tail", "visited", "stop"]
+        for name, want in case["counters"].items():
+            assert ctr[names.index(name)] == want, (name, case)
+    ix.close()
+
+
+def test_search_twice_gives_identical_bytes(c1_small, torch_dev):
+    c = c1_small
+    ix = _gpu_index(c, torch_dev)
+    a = _search_gpu(ix, torch_dev, c["queries"], c["lo"], c["hi"], 10, 64)
+    b = _search_gpu(ix, torch_dev, c["queries"], c["lo"], c["hi"], 10, 64)
+    assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    ix.close()
