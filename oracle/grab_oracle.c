@@ -406,3 +406,205 @@ int oracle_max_threads(void) {
     return 1;
 #endif
 }
+
+/* ============================================================== batched append (Section 4.4)
+ * The paper gives the stages (append at the tail, logical assignment, candidate search in the
+ * target bucket and globally, forward selection by heuristic pruning, reverse rewiring from a
+ * request buffer) and two rules (Eq. 2 diversity, Eq. 3 freshness bias).  It gives no candidate
+ * counts, no eviction choice and no order for conflicting updates, and it claims slots with
+ * an atomic counter whose order is not reproducible.  reading (normative for this build):
+ *
+ *  0. Snapshot: every decision below about existing nodes uses the index as it was before
+ *     the batch; new nodes are not candidates for each other.
+ *  1. Bucket of a new attribute x: the buckets with min <= x <= max form a run [e0,e1]; take
+ *     e0 + (external id mod run length).  If the run is empty take the first bucket with
+ *     max >= x (the last bucket if none); its interval is widened after the batch.
+ *  2. Slot: base + n_total + (number of earlier batch items sent to the same bucket), i.e. a
+ *     stable counting sort in batch order.  If any bucket would pass its capacity the call
+ *     fails (status 3) and nothing is written.  External id = n_prev + position in the batch.
+ *     Existing slots never move.
+ *  3. Candidates: two runs of the search above with the new vector as query and
+ *     beam = append_beam: (L) restricted to the target bucket's slab, (G) over the whole
+ *     attribute domain, keeping only results outside the target bucket.  The whole final
+ *     queue is the candidate list, ordered by (distance, slot).
+ *  4. Forward selection (Eq. 2): scan the list in order; keep c iff dist(q,c) < dist(c,n) for
+ *     every n kept so far; stop when K_local (K_remote) are kept; then back-fill the row with
+ *     the earliest rejected candidates; still short -> empty entries.  Row = [local | remote].
+ *  5. Reverse requests: one per written edge q->v: (v, kind, dist(v,q), q).  Sorted by
+ *     (v, kind, distance image, q's slot) and applied one after another per target.  With R the
+ *     current local (or remote) part of v's row and a = alpha (squared for the squared-L2
+ *     metric, so that the test is the paper's on true Euclidean distances):
+ *       pass  = a*dist(v,q) < dist(q,n) for every n in R           (Eq. 2 with Eq. 3's d_eff)
+ *       if !pass: drop.  Else if R has an empty entry: fill the first one.  Else let n* be the
+ *       entry of R farthest from v (ties: larger slot); replace it iff a*dist(v,q) < dist(v,n*).
+ *     Fresh nodes already placed in R by this batch count as ordinary neighbours.
+ *  6. Table: n_total grows by the bucket's batch count; min/max absorb the new attributes.
+ */
+typedef struct {
+    uint32_t v;      /* target (existing node) slot */
+    uint32_t kind;   /* 0 local, 1 remote */
+    uint32_t img;    /* dist_image(dist(v,q)) */
+    uint32_t q;      /* new node slot */
+    float dist;
+} request;
+
+static int request_cmp(const void *a, const void *b) {
+    const request *x = (const request *)a, *y = (const request *)b;
+    if (x->v != y->v) return x->v < y->v ? -1 : 1;
+    if (x->kind != y->kind) return x->kind < y->kind ? -1 : 1;
+    if (x->img != y->img) return x->img < y->img ? -1 : 1;
+    if (x->q != y->q) return x->q < y->q ? -1 : 1;
+    return 0;
+}
+
+/* Eq. 2 scan over `nc` ordered candidates (slot, dist to q); writes up to `cap` slots to row,
+ * returns how many were kept by the rule (the rest of the row is back-fill, then EMPTY) */
+static int forward_select(const oracle_index *ix, const uint32_t *cs, const float *cd, int nc, int cap,
+                          uint32_t *row) {
+    int kept = 0, nrej = 0;
+    uint32_t *rej = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(nc > 0 ? nc : 1));
+    for (int t = 0; t < nc && kept < cap; ++t) {
+        int ok = 1;
+        for (int j = 0; j < kept && ok; ++j) {
+            float dcn = oracle_distance(ix->X + (size_t)cs[t] * ix->dim, ix->X + (size_t)row[j] * ix->dim, ix->dim, ix->metric);
+            if (!(cd[t] < dcn)) ok = 0;
+        }
+        if (ok) row[kept++] = cs[t]; else rej[nrej++] = cs[t];
+    }
+    int fill = kept;
+    for (int j = 0; j < nrej && fill < cap; ++j) row[fill++] = rej[j];
+    for (; fill < cap; ++fill) row[fill] = EMPTY;
+    free(rej);
+    return kept;
+}
+
+/* Returns 0, or 3 when a bucket is out of tail room (nothing written).  `pr` holds the search
+ * parameters already resolved for beam = append_beam.  id2slot has room for n_prev + m entries.
+ * kept_out (may be NULL): per new node {entries kept by Eq. 2 in the local part, in the remote part}. */
+int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_t append_beam,
+                  const float *vecs, const int32_t *attrs, int64_t m, int64_t n_prev, uint32_t *id2slot,
+                  int32_t *kept_out, int32_t threads) {
+    const int B = ix->n_buckets, kl = ix->k_local, kr = ix->k_remote, K = kl + kr, dim = ix->dim;
+    int32_t *bucket = (int32_t *)malloc(sizeof(int32_t) * (size_t)m);
+    uint32_t *slot = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)m);
+    int64_t *count = (int64_t *)calloc((size_t)B, sizeof(int64_t));
+    /* 1 */
+    for (int64_t i = 0; i < m; ++i) {
+        int32_t x = attrs[i];
+        int e0 = -1, e1 = -1;
+        for (int b = 0; b < B; ++b)
+            if (ix->table[6 * b + T_MIN] <= x && x <= ix->table[6 * b + T_MAX]) { if (e0 < 0) e0 = b; e1 = b; }
+        int b;
+        if (e0 >= 0) {
+            b = e0 + (int)((uint64_t)(n_prev + i) % (uint64_t)(e1 - e0 + 1));
+        } else {
+            b = B - 1;
+            for (int c = 0; c < B; ++c) if (ix->table[6 * c + T_MAX] >= x) { b = c; break; }
+        }
+        bucket[i] = b;
+    }
+    /* 2 */
+    for (int64_t i = 0; i < m; ++i) {
+        const int32_t *t = ix->table + 6 * bucket[i];
+        slot[i] = (uint32_t)((int64_t)t[T_BASE] + t[T_NTOT] + count[bucket[i]]);
+        count[bucket[i]]++;
+    }
+    for (int b = 0; b < B; ++b)
+        if (ix->table[6 * b + T_NTOT] + count[b] > ix->table[6 * b + T_CAP]) {
+            free(bucket); free(slot); free(count);
+            return 3;
+        }
+    /* 3 + 4 on the snapshot */
+    uint32_t *rows = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)m * K);
+    float *rowd = (float *)malloc(sizeof(float) * (size_t)m * K);   /* dist(q, row entry) */
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+#pragma omp parallel num_threads(threads)
+#endif
+    {
+        scratch *sc = scratch_new(ix->n_cap);
+        uint32_t *cs = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)append_beam);
+        float *cd = (float *)malloc(sizeof(float) * (size_t)append_beam);
+#ifdef _OPENMP
+#pragma omp for schedule(static)
+#endif
+        for (int64_t i = 0; i < m; ++i) {
+            const float *q = vecs + (size_t)i * dim;
+            uint32_t *row = rows + (size_t)i * K;
+            int kept[2];
+            for (int kind = 0; kind < 2; ++kind) {
+                int64_t nQ = kind == 0 ? search_one(ix, pr, q, 0, 0, bucket[i], append_beam, sc, NULL)
+                                       : search_one(ix, pr, q, INT32_MIN, INT32_MAX, -1, append_beam, sc, NULL);
+                int nc = 0;
+                for (int64_t j = 0; j < nQ; ++j) {
+                    if (kind == 1 && bucket_of_slot(ix, sc->Q[j].slot) == bucket[i]) continue;
+                    cs[nc] = sc->Q[j].slot; cd[nc] = sc->Q[j].dist; nc++;
+                }
+                uint32_t *part = row + (kind == 0 ? 0 : kl);
+                int cap = kind == 0 ? kl : kr;
+                kept[kind] = forward_select(ix, cs, cd, nc, cap, part);
+                for (int j = 0; j < cap; ++j) {
+                    float d = 0.0f;
+                    if (part[j] != EMPTY)
+                        for (int t = 0; t < nc; ++t) if (cs[t] == part[j]) d = cd[t];
+                    rowd[(size_t)i * K + (kind == 0 ? 0 : kl) + j] = d;
+                }
+            }
+            if (kept_out) { kept_out[2 * i] = kept[0]; kept_out[2 * i + 1] = kept[1]; }
+        }
+        free(cs); free(cd);
+        scratch_free(sc);
+    }
+    /* write the new nodes */
+    int64_t nreq = 0;
+    request *req = (request *)malloc(sizeof(request) * (size_t)(m * K > 0 ? m * K : 1));
+    for (int64_t i = 0; i < m; ++i) {
+        uint32_t s = slot[i];
+        memcpy(ix->X + (size_t)s * dim, vecs + (size_t)i * dim, sizeof(float) * (size_t)dim);
+        ix->attr[s] = attrs[i];
+        ix->slot2id[s] = (uint32_t)(n_prev + i);
+        id2slot[n_prev + i] = s;
+        memcpy(ix->A + (size_t)s * K, rows + (size_t)i * K, sizeof(uint32_t) * (size_t)K);
+        for (int j = 0; j < K; ++j) {
+            uint32_t v = rows[(size_t)i * K + j];
+            if (v == EMPTY) continue;
+            float d = rowd[(size_t)i * K + j];
+            req[nreq].v = v; req[nreq].kind = j < kl ? 0u : 1u; req[nreq].img = dist_image(d);
+            req[nreq].q = s; req[nreq].dist = d;
+            nreq++;
+        }
+    }
+    /* 5 */
+    qsort(req, (size_t)nreq, sizeof(request), request_cmp);
+    const float a = ix->metric == 0 ? alpha * alpha : alpha;
+    for (int64_t r = 0; r < nreq; ++r) {
+        uint32_t *R = ix->A + (size_t)req[r].v * K + (req[r].kind == 0 ? 0 : kl);
+        int len = req[r].kind == 0 ? kl : kr;
+        const float *xq = ix->X + (size_t)req[r].q * dim, *xv = ix->X + (size_t)req[r].v * dim;
+        float lhs = a * req[r].dist;
+        int pass = 1, empty_at = -1;
+        for (int j = 0; j < len; ++j) {
+            if (R[j] == EMPTY) { if (empty_at < 0) empty_at = j; continue; }
+            float dqn = oracle_distance(xq, ix->X + (size_t)R[j] * dim, dim, ix->metric);
+            if (!(lhs < dqn)) pass = 0;
+        }
+        if (!pass) continue;
+        if (empty_at >= 0) { R[empty_at] = req[r].q; continue; }
+        int far = -1; uint32_t far_img = 0;
+        for (int j = 0; j < len; ++j) {
+            uint32_t im = dist_image(oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric));
+            if (far < 0 || im > far_img || (im == far_img && R[j] > R[far])) { far = j; far_img = im; }
+        }
+        float dfar = oracle_distance(xv, ix->X + (size_t)R[far] * dim, dim, ix->metric);
+        if (lhs < dfar) R[far] = req[r].q;
+    }
+    /* 6 */
+    for (int64_t i = 0; i < m; ++i) {
+        int32_t *t = ix->table + 6 * bucket[i];
+        if (attrs[i] < t[T_MIN]) t[T_MIN] = attrs[i];
+        if (attrs[i] > t[T_MAX]) t[T_MAX] = attrs[i];
+    }
+    for (int b = 0; b < B; ++b) ix->table[6 * b + T_NTOT] += (int32_t)count[b];
+    free(req); free(rows); free(rowd); free(bucket); free(slot); free(count);
+    return 0;
+}

@@ -201,6 +201,37 @@ class Index:
         return ids, dist, ctr
 
 
+    def _resolved_append_params(self) -> _Params:
+        return self._c_params(self.params["append_beam"])
+
+    def append(self, vectors: np.ndarray, attrs: np.ndarray, threads: int = 1):
+        """Section 4.4 batched insertion (see the reading in grab_oracle.c).  Raises
+        OverflowError, leaving the index untouched, if a bucket has no tail room.
+        Returns kept[m,2]: entries of each new row kept by the diversity rule (local, remote)."""
+        if self.A is None:
+            raise RuntimeError("load_graph first")
+        vectors = np.ascontiguousarray(vectors, dtype=np.float32)
+        attrs = np.ascontiguousarray(attrs, dtype=np.int32)
+        m = len(attrs)
+        if vectors.shape != (m, self.dim):
+            raise ValueError("bad shape")
+        if self.n + m > len(self.id2slot):
+            raise OverflowError("more objects than slots")
+        kept = np.zeros((m, 2), dtype=np.int32)
+        ix, pr = self._c_index(), self._resolved_append_params()
+        f = _load().oracle_append
+        f.restype = ctypes.c_int
+        rc = f(ctypes.byref(ix), ctypes.byref(pr), ctypes.c_float(self.params["alpha"]),
+               ctypes.c_int32(self.params["append_beam"]), _ptr(vectors), _ptr(attrs), ctypes.c_int64(m),
+               ctypes.c_int64(self.n), _ptr(self.id2slot), _ptr(kept), ctypes.c_int32(threads))
+        if rc == 3:
+            raise OverflowError("a bucket is out of tail room")
+        if rc:
+            raise ValueError("oracle_append rejected its arguments")
+        self.n += m
+        return kept
+
+
 def max_threads() -> int:
     return int(_load().oracle_max_threads())
 

@@ -1,0 +1,209 @@
+"""Pins for the oracle's batched insertion (Section 4.4, Eq. 2, Eq. 3)."""
+import json
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2604_16402_amd import workloads as W
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _pad(points, dim=32):
+    out = np.zeros((len(points), dim), np.float32)
+    out[:, :len(points[0])] = np.asarray(points, np.float32)
+    return out
+
+
+@pytest.mark.parametrize("alpha", [0.6, 1.0])
+def test_hand_worked_append(alpha):
+    g = json.load(open(os.path.join(GOLD, "append_2d.json")))
+    ix = O.Index(_pad(g["points"]), np.asarray(g["attrs"], np.int32), g["n_buckets"], n_cap=g["n_cap"])
+    ix.load_graph(np.asarray(g["local"], np.uint32), np.asarray(g["remote"], np.uint32))
+    ix.params.update(n_seeds=g["n_seeds"], append_beam=g["append_beam"], visited_cap=g["visited_cap"], alpha=alpha)
+    kept = ix.append(_pad(g["new_points"]), np.asarray(g["new_attrs"], np.int32))
+    want = g[f"alpha_{alpha}"]
+    assert ix.id2slot[8:10].tolist() == g["new_slots"]
+    assert kept.tolist() == g["kept"]
+    assert ix.A.tolist() == want["adj_slots"]
+    assert ix.table.tolist() == want["table"]
+    assert ix.slot2id[[4, 10]].tolist() == [8, 9] and ix.attr[[4, 10]].tolist() == g["new_attrs"]
+    assert (ix.X[4, :2] == [2, 1]).all() and (ix.X[10, :2] == [5, 2]).all()
+
+
+@pytest.fixture(scope="module")
+def grown():
+    """A 6k-object index (8 buckets) before and after appending 1.5k objects in two batches."""
+    cfg = W.scaled(W.CONFIGS["c5"], 6000, n_queries=300, buckets=8, components=16, append_batch=750)
+    X, a = W.base_vectors(cfg), W.attributes(cfg)
+    ix = O.Index(X, a, cfg.buckets, n_cap=8000)
+    la, ra = W.build_graph(X, ix.bucket_of_ids(), cfg.buckets, 16, 4)
+    ix.load_graph(la, ra)
+    before = dict(X=ix.X.copy(), attr=ix.attr.copy(), slot2id=ix.slot2id.copy(), A=ix.A.copy(), table=ix.table.copy())
+    batches = []
+    for r in range(2):
+        nx, na = W.append_vectors(cfg, r), W.append_attributes(cfg, r)
+        pre = dict(A=ix.A.copy(), table=ix.table.copy(), n=ix.n)
+        kept = ix.append(nx, na, threads=4)
+        batches.append(dict(x=nx, a=na, kept=kept, pre=pre))
+    allX = np.concatenate([X] + [b["x"] for b in batches])
+    alla = np.concatenate([a] + [b["a"] for b in batches])
+    return dict(cfg=cfg, ix=ix, before=before, batches=batches, X=allX, attrs=alla, n0=cfg.n)
+
+
+def test_existing_slots_never_move(grown):
+    ix, b = grown["ix"], grown["before"]
+    old = b["slot2id"] != O.EMPTY
+    assert np.array_equal(ix.X[old], b["X"][old]) and np.array_equal(ix.attr[old], b["attr"][old])
+    assert np.array_equal(ix.slot2id[old], b["slot2id"][old])
+    n = ix.n
+    assert n == grown["n0"] + 1500
+    assert np.array_equal(ix.slot2id[ix.id2slot[:n]], np.arange(n))
+    assert np.array_equal(ix.X[ix.id2slot[:n]], grown["X"]) and np.array_equal(ix.attr[ix.id2slot[:n]], grown["attrs"])
+
+
+def test_table_and_slot_assignment(grown):
+    ix, b0 = grown["ix"], grown["before"]
+    t, t0 = ix.table, b0["table"]
+    assert np.array_equal(t[:, [0, 1, 3]], t0[:, [0, 1, 3]])                  # base, n_sorted, cap fixed
+    assert t[:, 2].sum() == ix.n and (t[:, 2] <= t[:, 3]).all()
+    assert (t[:-1, 5] <= t[1:, 4]).all()                                       # intervals stay ordered
+    n = grown["n0"]
+    for r, batch in enumerate(grown["batches"]):
+        pre = batch["pre"]["table"]
+        slots = ix.id2slot[n:n + 750].astype(np.int64)
+        bk = ix.bucket_of_slots(slots)
+        a = batch["a"]
+        for i in range(750):
+            elig = [b for b in range(len(pre)) if pre[b, 4] <= a[i] <= pre[b, 5]]
+            if elig:
+                assert bk[i] == elig[0] + (n + i) % len(elig)
+            else:
+                later = [b for b in range(len(pre)) if pre[b, 5] >= a[i]]
+                assert bk[i] == (later[0] if later else len(pre) - 1)
+        for b in range(len(pre)):                                              # stable ranks inside the bucket
+            mine = slots[bk == b]
+            assert np.array_equal(mine, pre[b, 0] + pre[b, 2] + np.arange(len(mine)))
+        n += 750
+    lo_new = [min(grown["attrs"][ix.slot2id[t[b, 0]:t[b, 0] + t[b, 2]]]) for b in range(len(t))]
+    hi_new = [max(grown["attrs"][ix.slot2id[t[b, 0]:t[b, 0] + t[b, 2]]]) for b in range(len(t))]
+    assert t[:, 4].tolist() == lo_new and t[:, 5].tolist() == hi_new
+
+
+def test_degree_and_bucket_rules_hold_after_append(grown):
+    ix = grown["ix"]
+    n = ix.n
+    A = ix.A[ix.id2slot[:n]]
+    kl = ix.k_local
+    own = ix.bucket_of_slots(ix.id2slot[:n])[:, None]
+    live = A != O.EMPTY
+    nb = ix.bucket_of_slots(np.where(live, A, 0))
+    assert ((nb[:, :kl] == own) | ~live[:, :kl]).all()
+    assert ((nb[:, kl:] != own) | ~live[:, kl:]).all()
+    assert (ix.slot2id[np.where(live, A, ix.id2slot[0])] != O.EMPTY).all()     # every edge points at an object
+    assert (A != ix.id2slot[:n, None]).all()
+    unused = ix.slot2id == O.EMPTY
+    assert (ix.A[unused] == O.EMPTY).all()
+    for row in A[grown["n0"]:]:                                                # new rows: no duplicates
+        r = row[row != O.EMPTY]
+        assert len(set(r.tolist())) == len(r)
+
+
+def test_forward_rows_obey_the_diversity_rule(grown):
+    # Eq. 2 re-checked by brute force on the rows the first batch wrote (they are not rewired later
+    # within that batch): kept entries are pairwise diverse, back-filled ones are hidden by a kept one
+    ix = grown["ix"]
+    batch = grown["batches"][1]
+    n = batch["pre"]["n"]
+    kl, kr = ix.k_local, ix.k_remote
+    checked = 0
+    for i in range(0, 750, 7):
+        s = ix.id2slot[n + i]
+        q = batch["x"][i]
+        row = ix.A[s]
+        for part, kept in ((row[:kl], batch["kept"][i, 0]), (row[kl:], batch["kept"][i, 1])):
+            part = part[part != O.EMPTY]
+            d = [O.distance(q, ix.X[c]) for c in part]
+            assert all(d[j] <= d[j + 1] for j in range(kept - 1))               # scanned in distance order
+            for t in range(len(part)):
+                hidden = any(not (d[t] < O.distance(ix.X[part[t]], ix.X[part[j]])) for j in range(min(t, kept)))
+                if t < kept:
+                    assert not hidden
+                else:
+                    hidden_by_kept = any(not (d[t] < O.distance(ix.X[part[t]], ix.X[part[j]])) for j in range(kept)
+                                         if d[j] < d[t] or (d[j] == d[t] and part[j] < part[t]))
+                    assert hidden_by_kept or kept == len(part)
+            checked += 1
+    assert checked > 100
+
+
+def test_new_nodes_are_reachable_and_found(grown):
+    ix, cfg = grown["ix"], grown["cfg"]
+    n = ix.n
+    A = ix.A[ix.id2slot[:n]]
+    indeg = np.bincount(A[A != O.EMPTY].astype(np.int64), minlength=ix.n_cap)
+    new_slots = ix.id2slot[grown["n0"]:n]
+    assert (indeg[new_slots] > 0).mean() > 0.97                                 # (almost) no orphan newcomer
+    q = W.query_vectors(cfg)
+    lo, hi = W.ranges(cfg, 0.25)
+    ids, dist, _ = ix.search(q, lo, hi, 10, 64)
+    gt, _ = O.exact_filtered_knn(grown["X"], grown["attrs"], q, lo, hi, 10)
+    assert O.recall_at_k(ids, gt) > 0.9
+    assert (ids[ids != O.EMPTY] >= grown["n0"]).any()                            # appended objects are returned
+    for r, l, h in zip(ids, lo, hi):
+        r = r[r != O.EMPTY]
+        assert ((grown["attrs"][r] >= l) & (grown["attrs"][r] <= h)).all()
+
+
+def _fresh(alpha, cap=8000):
+    cfg = W.scaled(W.CONFIGS["c5"], 3000, n_queries=100, buckets=4, components=8, append_batch=400)
+    X, a = W.base_vectors(cfg), W.attributes(cfg)
+    ix = O.Index(X, a, cfg.buckets, n_cap=cap)
+    la, ra = W.build_graph(X, ix.bucket_of_ids(), cfg.buckets, 12, 3)
+    ix.load_graph(la, ra)
+    ix.params["alpha"] = alpha
+    return cfg, ix
+
+
+def test_bias_opens_rows_for_newcomers():
+    # Eq. 3: a smaller alpha can only make the check easier, so fresh nodes gain in-edges
+    got = {}
+    for alpha in (1.0, 0.6, 1e-6):
+        cfg, ix = _fresh(alpha)
+        pre = ix.A.copy()
+        ix.append(W.append_vectors(cfg, 0), W.append_attributes(cfg, 0))
+        new = set(ix.id2slot[3000:3400].tolist())
+        old_rows = ix.A[ix.id2slot[:3000]]
+        got[alpha] = int(np.isin(old_rows, list(new)).sum())
+        changed = (ix.A[ix.id2slot[:3000]] != pre[ix.id2slot[:3000]])
+        assert (np.isin(ix.A[ix.id2slot[:3000]][changed], list(new))).all()      # old rows change only by gaining fresh nodes
+    assert got[1e-6] >= got[0.6] >= got[1.0] and got[0.6] > got[1.0]
+    # alpha -> 0: every rewiring request passes and evicts the farthest neighbour, so the last
+    # request applied to a row is always present in it: every fresh node points to targets that...
+    cfg, ix = _fresh(1e-6)
+    ix.append(W.append_vectors(cfg, 0)[:1], W.append_attributes(cfg, 0)[:1])
+    s = ix.id2slot[3000]
+    targets = ix.A[s][ix.A[s] != O.EMPTY]
+    assert all(s in ix.A[t] for t in targets)                                    # batch of one: every target took it
+
+
+def test_full_bucket_fails_without_partial_writes():
+    cfg, ix = _fresh(0.6, cap=3000 + 4 * 50)
+    before = (ix.X.copy(), ix.A.copy(), ix.table.copy(), ix.slot2id.copy(), ix.n)
+    with pytest.raises(OverflowError):
+        ix.append(W.append_vectors(cfg, 0), W.append_attributes(cfg, 0))      # 400 > 4 x 50 free slots
+    assert np.array_equal(ix.X, before[0]) and np.array_equal(ix.A, before[1])
+    assert np.array_equal(ix.table, before[2]) and np.array_equal(ix.slot2id, before[3]) and ix.n == before[4]
+    ix.append(W.append_vectors(cfg, 0)[:40], W.append_attributes(cfg, 0)[:40])   # a batch that fits still works
+    assert ix.n == 3040
+
+
+def test_append_is_deterministic_and_thread_independent():
+    out = []
+    for threads in (1, 4):
+        cfg, ix = _fresh(0.6)
+        ix.append(W.append_vectors(cfg, 0), W.append_attributes(cfg, 0), threads=threads)
+        out.append((ix.A.copy(), ix.table.copy(), ix.id2slot.copy()))
+    assert all(np.array_equal(x, y) for x, y in zip(*out))
