@@ -44,6 +44,12 @@ def load_library() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is not built; run `python -m paper_2604_16402_amd.build` "
                            "(or __graft_entry__.build()) first")
+    # torch ships its own copy of the HIP runtime; load it first so that this library, torch's
+    # allocator and torch's streams all live in one runtime (device pointers are shared)
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
     lib.grab_create.argtypes = [ctypes.POINTER(vp), i32, i32, vp]

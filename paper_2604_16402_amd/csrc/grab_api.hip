@@ -96,6 +96,7 @@ void grab_destroy(grab_index *ix) {
     DevBuf *bufs[] = {&ix->plans, &ix->seeds, &ix->counters, &ix->stage_q, &ix->stage_lo, &ix->stage_hi,
                       &ix->stage_ids, &ix->stage_dist, &ix->stage_misc, &ix->flags};
     for (DevBuf *b : bufs) free_buf(*b);
+    for (DevBuf &b : ix->app) free_buf(b);
     for (hipEvent_t e : ix->ev)
         if (e) (void)hipEventDestroy(e);
     delete ix;
@@ -380,8 +381,21 @@ grab_status grab_get_timing(grab_index *ix, float ms[2]) {
 
 grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_t *attrs, int64_t m) {
     if (!ix) return GRAB_EINVAL;
-    (void)vectors; (void)attrs; (void)m;
-    return grab_fail(ix, GRAB_ESTATE, "append_batch is not built into this library yet");
+    if (!ix->has_graph) return grab_fail(ix, GRAB_ESTATE, "no graph loaded");
+    if (m < 0) return grab_fail(ix, GRAB_EINVAL, "bad batch size");
+    if (m == 0) return GRAB_OK;
+    if (!vectors || !attrs) return grab_fail(ix, GRAB_EINVAL, "null argument");
+    if (ix->n + m > ix->n_slots)
+        return grab_fail(ix, GRAB_EFULL, "%lld objects + %lld new exceed the %lld slots of the index", (long long)ix->n,
+                         (long long)m, (long long)ix->n_slots);
+    SearchLaunch proto;
+    grab_status st = resolve_search(ix, ix->prm.append_beam, ix->prm.append_beam, proto);
+    if (st != GRAB_OK) return st;
+    const void *dv, *da;
+    if ((st = grab_to_device(ix, vectors, (size_t)m * ix->dim * 4, ix->stage_q, &dv)) != GRAB_OK) return st;
+    if ((st = grab_to_device(ix, attrs, (size_t)m * 4, ix->stage_lo, &da)) != GRAB_OK) return st;
+    ix->timed = false;
+    return grab_append_device(ix, (const float *)dv, (const int32_t *)da, m, proto);
 }
 
 }  // extern "C"

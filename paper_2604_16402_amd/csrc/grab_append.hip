@@ -1,0 +1,412 @@
+// Batched insertion (Section 4.4) for gfx950: append at the bucket tails without moving any
+// slot, candidate search against the pre-batch graph, forward selection by the diversity rule
+// (Eq. 2) and reverse rewiring with the freshness bias (Eq. 3).
+//
+// The paper claims slots with an atomic counter and fills a request buffer atomically; both
+// orders are irreproducible.  Here slots come from a stable sort of (bucket, batch position)
+// and reverse requests are sorted by (target, kind, distance, source) and applied serially
+// per target by one wavefront, so that the same batch always yields the same bytes.
+#include <cstring>
+
+#include <rocprim/device/device_radix_sort.hpp>
+
+#include "grab_device.h"
+
+namespace {
+
+constexpr int TPB = 256;
+inline unsigned blocks_for(int64_t work) { return (unsigned)((work + TPB - 1) / TPB); }
+
+// Bucket of a new attribute x against the pre-batch table: the run of buckets with
+// min <= x <= max, spread by external id; else the first bucket with max >= x (else the last).
+__global__ void k_assign_bucket(const int32_t *__restrict__ table, int32_t B, const int32_t *__restrict__ attrs,
+                                int64_t m, int64_t n_prev, int32_t *__restrict__ bucket, uint32_t *__restrict__ keys,
+                                uint32_t *__restrict__ idx) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= m) return;
+    const int32_t x = attrs[i];
+    int l = 0, r = B;  // e0 = number of buckets with max < x
+    while (l < r) { int mid = (l + r) >> 1; if (table[T_COLS * mid + T_MAX] < x) l = mid + 1; else r = mid; }
+    const int e0 = l;
+    l = 0; r = B;      // e1 + 1 = number of buckets with min <= x
+    while (l < r) { int mid = (l + r) >> 1; if (table[T_COLS * mid + T_MIN] <= x) l = mid + 1; else r = mid; }
+    const int e1 = l - 1;
+    int b;
+    if (e0 <= e1) b = e0 + (int)((uint64_t)(n_prev + i) % (uint64_t)(e1 - e0 + 1));
+    else b = e0 < B ? e0 : B - 1;
+    bucket[i] = b;
+    keys[i] = (uint32_t)b;
+    idx[i] = (uint32_t)i;
+}
+
+// per bucket: first position and count of its items in the bucket-sorted batch
+__global__ void k_bucket_spans(const uint32_t *__restrict__ sorted_keys, int64_t m, int32_t B,
+                               int32_t *__restrict__ starts, int32_t *__restrict__ counts) {
+    int b = blockIdx.x * TPB + threadIdx.x;
+    if (b >= B) return;
+    int64_t l = 0, r = m;
+    while (l < r) { int64_t mid = (l + r) >> 1; if (sorted_keys[mid] < (uint32_t)b) l = mid + 1; else r = mid; }
+    const int64_t s = l;
+    r = m;
+    while (l < r) { int64_t mid = (l + r) >> 1; if (sorted_keys[mid] <= (uint32_t)b) l = mid + 1; else r = mid; }
+    starts[b] = (int32_t)s;
+    counts[b] = (int32_t)(l - s);
+}
+
+// slot = base + n_total + rank among the batch items of the same bucket, in batch order
+__global__ void k_assign_slots(const uint32_t *__restrict__ sorted_keys, const uint32_t *__restrict__ sorted_idx,
+                               int64_t m, const int32_t *__restrict__ starts, const int32_t *__restrict__ table,
+                               uint32_t *__restrict__ slot) {
+    int64_t p = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (p >= m) return;
+    const uint32_t b = sorted_keys[p];
+    const int32_t *t = table + T_COLS * b;
+    slot[sorted_idx[p]] = (uint32_t)(t[T_BASE] + t[T_NTOT] + (int32_t)(p - starts[b]));
+}
+
+__global__ void k_fill_range(int32_t *__restrict__ lo, int32_t *__restrict__ hi, int64_t m) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < m) { lo[i] = INT32_MIN; hi[i] = INT32_MAX; }
+}
+
+// feature row, attribute and id maps of the new objects (one thread per 16-byte piece)
+__global__ void k_write_new(const float4 *__restrict__ vecs, const int32_t *__restrict__ attrs,
+                            const uint32_t *__restrict__ slot, int64_t m, int64_t n_prev, int32_t row_f4,
+                            float4 *__restrict__ X, int32_t *__restrict__ attr_s, uint32_t *__restrict__ slot2id,
+                            uint32_t *__restrict__ id2slot) {
+    int64_t t = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    int64_t i = t / row_f4;
+    if (i >= m) return;
+    int32_t c = (int32_t)(t - i * row_f4);
+    const uint32_t s = slot[i];
+    X[(int64_t)s * row_f4 + c] = vecs[i * row_f4 + c];
+    if (c == 0) {
+        attr_s[s] = attrs[i];
+        slot2id[s] = (uint32_t)(n_prev + i);
+        id2slot[n_prev + i] = s;
+    }
+}
+
+__global__ void k_widen(const int32_t *__restrict__ attrs, const int32_t *__restrict__ bucket, int64_t m,
+                        int32_t *__restrict__ table) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= m) return;
+    int32_t *t = table + T_COLS * bucket[i];
+    atomicMin(&t[T_MIN], attrs[i]);
+    atomicMax(&t[T_MAX], attrs[i]);
+}
+
+__global__ void k_grow(int32_t *__restrict__ table, const int32_t *__restrict__ counts, int32_t B) {
+    int b = blockIdx.x * TPB + threadIdx.x;
+    if (b < B) table[T_COLS * b + T_NTOT] += counts[b];
+}
+
+__global__ void k_gather_u64(const u64 *__restrict__ src, const uint32_t *__restrict__ order, int64_t n,
+                             u64 *__restrict__ dst) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < n) dst[i] = src[order[i]];
+}
+
+__global__ void k_iota(uint32_t *__restrict__ a, int64_t n) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < n) a[i] = (uint32_t)i;
+}
+
+struct ForwardArgs {
+    const float *X;
+    uint32_t *A;
+    const int32_t *table;
+    const int32_t *bucket;
+    const uint32_t *slot;
+    const uint32_t *cand_s[2];  // [local search, global search] results: slots
+    const float *cand_d[2];     //                                          distances to the new vector
+    u64 *key1, *key2;           // request keys, one per row entry
+    float *reqd;
+    int32_t beam, kl, kr, metric;
+};
+
+// Forward edge selection for one new node per wavefront (Section 4.4 step 2, Eq. 2): scan the
+// candidates in (distance, slot) order, keep c iff dist(q,c) < dist(c,n) for every kept n, stop
+// at the part's width, back-fill with the earliest rejected ones.  Writes the new adjacency
+// row [local | remote] and one reverse request per written edge.
+template <int NCH>
+__global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int D = NCH * 32;
+    const int lane = threadIdx.x;
+    const int64_t i = blockIdx.x;
+    const int K = a.kl + a.kr;
+    uint32_t *cs = reinterpret_cast<uint32_t *>(smem);
+    float *cd = reinterpret_cast<float *>(cs + a.beam);
+    uint32_t *kept = reinterpret_cast<uint32_t *>(cd + a.beam);
+    float *keptd = reinterpret_cast<float *>(kept + 64);
+    uint32_t *rej = reinterpret_cast<uint32_t *>(keptd + 64);
+    float *rejd = reinterpret_cast<float *>(rej + 64);
+    float *dtmp = rejd + 64;
+    float *qlds = dtmp + 64;
+    float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
+    const int b = a.bucket[i];
+    const int slab_lo = a.table[T_COLS * b + T_BASE], slab_hi = slab_lo + a.table[T_COLS * b + T_CAP];
+    const uint32_t self = a.slot[i];
+    const u64 lt_mask = (1ull << lane) - 1ull;
+    for (int kind = 0; kind < 2; ++kind) {
+        const int cap = kind ? a.kr : a.kl, off = kind ? a.kl : 0;
+        const uint32_t *src_s = a.cand_s[kind] + i * a.beam;
+        const float *src_d = a.cand_d[kind] + i * a.beam;
+        int nc = 0;
+        for (int c0 = 0; c0 < a.beam; c0 += 64) {   // remote candidates: results outside the own slab
+            const int idx = c0 + lane;
+            uint32_t s = idx < a.beam ? src_s[idx] : GRAB_EMPTY;
+            bool ok = s != GRAB_EMPTY && (kind == 0 || !((int)s >= slab_lo && (int)s < slab_hi));
+            u64 m = __ballot(ok);
+            if (ok) { int pos = nc + __popcll(m & lt_mask); cs[pos] = s; cd[pos] = src_d[idx]; }
+            nc += __popcll(m);
+        }
+        __syncthreads();
+        int nk = 0, nrej = 0;
+        for (int t = 0; t < nc && nk < cap; ++t) {
+            const uint32_t c = cs[t];
+            const float dqc = cd[t];
+            bool ok = true;
+            if (nk > 0) {
+                load_query<NCH>(a.X + (size_t)c * D, qreg, qlds, lane);
+                if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
+                eval_rows<NCH, false>(a.X, qreg, qlds, kept, nk, nullptr, lane, a.metric, dtmp);
+                __syncthreads();
+                bool hidden = lane < nk && !(dqc < dtmp[lane]);
+                ok = __ballot(hidden) == 0;
+            }
+            if (lane == 0) {
+                if (ok) { kept[nk] = c; keptd[nk] = dqc; }
+                else if (nrej < 64) { rej[nrej] = c; rejd[nrej] = dqc; }
+            }
+            if (ok) ++nk; else if (nrej < 64) ++nrej;
+            __syncthreads();
+        }
+        for (int j = lane; j < cap; j += 64) {
+            uint32_t v = GRAB_EMPTY;
+            float d = 0.0f;
+            if (j < nk) { v = kept[j]; d = keptd[j]; }
+            else if (j - nk < nrej) { v = rej[j - nk]; d = rejd[j - nk]; }
+            a.A[(size_t)self * K + off + j] = v;
+            const int64_t r = i * K + off + j;
+            a.key1[r] = v == GRAB_EMPTY ? ~0ull : (((u64)v << 1) | (u64)kind);
+            a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
+            a.reqd[r] = d;
+        }
+        __syncthreads();
+    }
+}
+
+struct RewireArgs {
+    const float *X;
+    uint32_t *A;
+    const u64 *key1s;       // sorted (target << 1 | kind); ~0 for "no request"
+    const uint32_t *order;  // request index at each sorted position
+    const u64 *key2;        // by request index: distance image << 32 | source slot
+    const float *reqd;      // by request index: dist(target, source)
+    int64_t nreq;
+    int32_t kl, kr, metric;
+    float a;                // alpha, squared for the squared-L2 metric
+};
+
+// Reverse rewiring (Section 4.4 step 3, Eq. 2 with Eq. 3's effective distance): the wavefront
+// that sits on the first request of a (target, kind) group applies the whole group in order.
+template <int NCH>
+__global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int D = NCH * 32;
+    const int lane = threadIdx.x;
+    const int64_t p0 = blockIdx.x;
+    const u64 key = a.key1s[p0];
+    if (key == ~0ull) return;
+    if (p0 > 0 && a.key1s[p0 - 1] == key) return;
+    const uint32_t v = (uint32_t)(key >> 1);
+    const int kind = (int)(key & 1ull);
+    const int K = a.kl + a.kr, off = kind ? a.kl : 0, len = kind ? a.kr : a.kl;
+    uint32_t *R = reinterpret_cast<uint32_t *>(smem);   // current part of v's row
+    uint32_t *Rl = R + 64;                                // same with empty entries pointing at row 0
+    float *dv = reinterpret_cast<float *>(Rl + 64);       // dist(v, R[j])
+    float *dq = dv + 64;                                  // dist(q, R[j])
+    float *qlds = dq + 64;
+    float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
+    if (lane < len) {
+        uint32_t e = a.A[(size_t)v * K + off + lane];
+        R[lane] = e;
+        Rl[lane] = e == GRAB_EMPTY ? 0u : e;
+    }
+    load_query<NCH>(a.X + (size_t)v * D, qreg, qlds, lane);
+    __syncthreads();
+    eval_rows<NCH, false>(a.X, qreg, qlds, Rl, len, nullptr, lane, a.metric, dv);
+    __syncthreads();
+    bool changed = false;
+    for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
+        const uint32_t ridx = a.order[p];
+        const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
+        const float dvq = a.reqd[ridx];
+        const float lhs = a.a * dvq;
+        load_query<NCH>(a.X + (size_t)q * D, qreg, qlds, lane);
+        if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
+        eval_rows<NCH, false>(a.X, qreg, qlds, Rl, len, nullptr, lane, a.metric, dq);
+        __syncthreads();
+        const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
+        const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < dq[lane]);
+        if (__ballot(blocked) == 0) {
+            const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+            int at = -1;
+            if (empties) {
+                at = __ffsll((long long)empties) - 1;
+            } else {
+                u64 kf = lane < len ? (((u64)dist_image(dv[lane]) << 32) | (u64)mine) : 0ull;
+                u64 kmax = kf;
+#pragma unroll
+                for (int s = 32; s > 0; s >>= 1) {
+                    uint32_t hi = __shfl_xor((uint32_t)(kmax >> 32), s), lo = __shfl_xor((uint32_t)kmax, s);
+                    u64 other = ((u64)hi << 32) | lo;
+                    kmax = other > kmax ? other : kmax;
+                }
+                const int far = __ffsll((long long)__ballot(lane < len && kf == kmax)) - 1;
+                if (lhs < dv[far]) at = far;
+            }
+            __syncthreads();
+            if (at >= 0) {
+                if (lane == at) { R[at] = q; Rl[at] = q; dv[at] = dvq; }
+                changed = true;
+            }
+        }
+        __syncthreads();
+    }
+    if (changed && lane < len) a.A[(size_t)v * K + off + lane] = R[lane];
+}
+
+template <int NCH>
+grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
+    const size_t qbytes = EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4;
+    if (phase == 0) {
+        size_t lds = (size_t)f.beam * 8 + 64 * 4 * 5 + qbytes;
+        k_forward<NCH><<<dim3((unsigned)m), dim3(64), lds, ix->stream>>>(f);
+    } else {
+        size_t lds = 64 * 4 * 4 + qbytes;
+        k_rewire<NCH><<<dim3((unsigned)r.nreq), dim3(64), lds, ix->stream>>>(r);
+    }
+    GRAB_HIP(ix, hipGetLastError());
+    return GRAB_OK;
+}
+
+grab_status launch_append(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
+    switch (ix->dim / 32) {
+#define GRAB_CASE(N) case N: return launch_append_t<N>(ix, f, r, m, phase);
+        GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
+        GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
+#undef GRAB_CASE
+        default:
+            return grab_fail(ix, GRAB_EINVAL, "dim %d has no append kernel", ix->dim);
+    }
+}
+
+}  // namespace
+
+// Runs the whole insertion for m new objects whose vectors/attributes are already on the device.
+grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_t *d_attrs, int64_t m,
+                               const SearchLaunch &proto) {
+    hipStream_t st = ix->stream;
+    const int32_t B = ix->B, kl = ix->kl, kr = ix->kr, K = kl + kr, beam = proto.beam;
+    const int64_t nreq = m * K;
+    grab_status rc;
+    // ---- arena
+    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_CG_S,
+           A_CG_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_N };
+    size_t need[A_N];
+    for (size_t &x : need) x = 0;
+    need[A_BUCKET] = need[A_KEYS] = need[A_IDX] = need[A_KEYS_S] = need[A_IDX_S] = need[A_SLOT] = need[A_LO] = need[A_HI] = (size_t)m * 4;
+    need[A_STARTS] = need[A_COUNTS] = (size_t)B * 4;
+    need[A_CL_S] = need[A_CL_D] = need[A_CG_S] = need[A_CG_D] = (size_t)m * beam * 4;
+    need[A_KEY1] = need[A_KEY2] = need[A_K2S] = need[A_K1G] = need[A_K1S] = (size_t)nreq * 8;
+    need[A_REQD] = need[A_ORD0] = need[A_ORD1] = need[A_ORD2] = (size_t)nreq * 4;
+    size_t tmp1 = 0, tmp2 = 0;
+    GRAB_HIP(ix, rocprim::radix_sort_pairs(nullptr, tmp1, (uint32_t *)nullptr, (uint32_t *)nullptr, (uint32_t *)nullptr,
+                                           (uint32_t *)nullptr, (size_t)m, 0, 32, st));
+    GRAB_HIP(ix, rocprim::radix_sort_pairs(nullptr, tmp2, (u64 *)nullptr, (u64 *)nullptr, (uint32_t *)nullptr,
+                                           (uint32_t *)nullptr, (size_t)nreq, 0, 64, st));
+    need[A_TMP] = (tmp1 > tmp2 ? tmp1 : tmp2) + 16;
+    if ((int)ix->app.size() < A_N) ix->app.resize(A_N);
+    for (int i = 0; i < A_N; ++i)
+        if ((rc = grab_reserve(ix, ix->app[i], need[i])) != GRAB_OK) return rc;
+    auto P = [&](int i) { return ix->app[i].p; };
+    int32_t *bucket = (int32_t *)P(A_BUCKET), *starts = (int32_t *)P(A_STARTS), *counts = (int32_t *)P(A_COUNTS);
+    uint32_t *slot = (uint32_t *)P(A_SLOT);
+
+    // ---- 1, 2: bucket and slot of every new object (pre-batch table), capacity check on the host
+    k_assign_bucket<<<blocks_for(m), TPB, 0, st>>>(ix->table, B, d_attrs, m, ix->n, bucket, (uint32_t *)P(A_KEYS), (uint32_t *)P(A_IDX));
+    GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp1, (uint32_t *)P(A_KEYS), (uint32_t *)P(A_KEYS_S), (uint32_t *)P(A_IDX),
+                                           (uint32_t *)P(A_IDX_S), (size_t)m, 0, 32, st));
+    k_bucket_spans<<<blocks_for(B), TPB, 0, st>>>((uint32_t *)P(A_KEYS_S), m, B, starts, counts);
+    k_assign_slots<<<blocks_for(m), TPB, 0, st>>>((uint32_t *)P(A_KEYS_S), (uint32_t *)P(A_IDX_S), m, starts, ix->table, slot);
+    GRAB_HIP(ix, hipGetLastError());
+    {
+        int32_t *h_counts = new (std::nothrow) int32_t[B];
+        if (!h_counts) return grab_fail(ix, GRAB_ENOMEM, "host allocation failed");
+        hipError_t e = hipMemcpyAsync(h_counts, counts, (size_t)B * 4, hipMemcpyDeviceToHost, st);
+        if (e == hipSuccess) e = hipStreamSynchronize(st);
+        int full = -1;
+        if (e == hipSuccess)
+            for (int b = 0; b < B; ++b)
+                if (ix->h_table[T_COLS * b + T_NTOT] + h_counts[b] > ix->h_table[T_COLS * b + T_CAP]) { full = b; break; }
+        int over = full >= 0 ? h_counts[full] : 0;
+        delete[] h_counts;
+        if (e != hipSuccess) return grab_fail(ix, GRAB_EHIP, "append failed: %s", hipGetErrorString(e));
+        if (full >= 0)
+            return grab_fail(ix, GRAB_EFULL, "bucket %d holds %d of %d slots and the batch adds %d", full,
+                             ix->h_table[T_COLS * full + T_NTOT], ix->h_table[T_COLS * full + T_CAP], over);
+    }
+    // ---- 3: candidate searches against the pre-batch index (new rows are not visible yet)
+    k_fill_range<<<blocks_for(m), TPB, 0, st>>>((int32_t *)P(A_LO), (int32_t *)P(A_HI), m);
+    if ((rc = grab_reserve(ix, ix->plans, m * sizeof(QueryPlan))) != GRAB_OK) return rc;
+    if ((rc = grab_reserve(ix, ix->seeds, (size_t)m * proto.n_seeds * 4)) != GRAB_OK) return rc;
+    if ((rc = grab_reserve(ix, ix->counters, (size_t)m * 8 * 4)) != GRAB_OK) return rc;
+    SearchLaunch s = proto;
+    s.queries = d_vecs; s.lo = (const int32_t *)P(A_LO); s.hi = (const int32_t *)P(A_HI); s.nq = m;
+    s.plans = (QueryPlan *)ix->plans.p; s.seeds = (uint32_t *)ix->seeds.p; s.counters = (uint32_t *)ix->counters.p;
+    s.out_slots = true;
+    s.only_bucket = bucket; s.out_ids = (uint32_t *)P(A_CL_S); s.out_dist = (float *)P(A_CL_D);
+    if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
+    if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
+    s.only_bucket = nullptr; s.out_ids = (uint32_t *)P(A_CG_S); s.out_dist = (float *)P(A_CG_D);
+    if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
+    if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
+    ix->last_nq = 0;
+    // ---- 4: forward selection, new adjacency rows, reverse requests
+    ForwardArgs f;
+    f.X = ix->X; f.A = ix->A; f.table = ix->table; f.bucket = bucket; f.slot = slot;
+    f.cand_s[0] = (const uint32_t *)P(A_CL_S); f.cand_d[0] = (const float *)P(A_CL_D);
+    f.cand_s[1] = (const uint32_t *)P(A_CG_S); f.cand_d[1] = (const float *)P(A_CG_D);
+    f.key1 = (u64 *)P(A_KEY1); f.key2 = (u64 *)P(A_KEY2); f.reqd = (float *)P(A_REQD);
+    f.beam = beam; f.kl = kl; f.kr = kr; f.metric = ix->metric;
+    RewireArgs r;
+    memset(&r, 0, sizeof(r));
+    if ((rc = launch_append(ix, f, r, m, 0)) != GRAB_OK) return rc;
+    // ---- the new objects themselves
+    const int32_t row_f4 = ix->dim / 4;
+    k_write_new<<<blocks_for(m * row_f4), TPB, 0, st>>>((const float4 *)d_vecs, d_attrs, slot, m, ix->n, row_f4, (float4 *)ix->X,
+                                                        ix->attr, ix->slot2id, ix->id2slot);
+    // ---- 5: requests ordered by (target, kind, distance, source): two stable radix passes
+    k_iota<<<blocks_for(nreq), TPB, 0, st>>>((uint32_t *)P(A_ORD0), nreq);
+    GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp2, (u64 *)P(A_KEY2), (u64 *)P(A_K2S), (uint32_t *)P(A_ORD0),
+                                           (uint32_t *)P(A_ORD1), (size_t)nreq, 0, 64, st));
+    k_gather_u64<<<blocks_for(nreq), TPB, 0, st>>>((const u64 *)P(A_KEY1), (const uint32_t *)P(A_ORD1), nreq, (u64 *)P(A_K1G));
+    GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp2, (u64 *)P(A_K1G), (u64 *)P(A_K1S), (uint32_t *)P(A_ORD1),
+                                           (uint32_t *)P(A_ORD2), (size_t)nreq, 0, 64, st));
+    r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.order = (const uint32_t *)P(A_ORD2);
+    r.key2 = (const u64 *)P(A_KEY2); r.reqd = (const float *)P(A_REQD); r.nreq = nreq;
+    r.kl = kl; r.kr = kr; r.metric = ix->metric;
+    r.a = ix->metric == GRAB_L2SQ ? ix->prm.alpha * ix->prm.alpha : ix->prm.alpha;
+    if ((rc = launch_append(ix, f, r, m, 1)) != GRAB_OK) return rc;
+    // ---- 6: table
+    k_widen<<<blocks_for(m), TPB, 0, st>>>(d_attrs, bucket, m, ix->table);
+    k_grow<<<blocks_for(B), TPB, 0, st>>>(ix->table, counts, B);
+    GRAB_HIP(ix, hipGetLastError());
+    GRAB_HIP(ix, hipMemcpyAsync(ix->h_table, ix->table, sizeof(int32_t) * T_COLS * B, hipMemcpyDeviceToHost, st));
+    GRAB_HIP(ix, hipStreamSynchronize(st));
+    ix->n += m;
+    return GRAB_OK;
+}

@@ -1,0 +1,156 @@
+// Device-side helpers shared by the search and append kernels (gfx950 only): queue keys,
+// wave reductions and the gathered fp32 distance with its fixed summation order.
+#pragma once
+
+#include "grab_internal.h"
+
+namespace {
+
+typedef unsigned long long u64;
+constexpr u64 SENT = ~0ull;  // empty queue entry; sorts last
+
+// order-preserving image of an fp32 value in uint32
+__device__ __forceinline__ uint32_t dist_image(float d) {
+    uint32_t b = __float_as_uint(d);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+__device__ __forceinline__ float image_dist(uint32_t m) {
+    return __uint_as_float((m & 0x80000000u) ? (m & 0x7FFFFFFFu) : ~m);
+}
+// queue key: distance image | slot | expanded flag.  Keys of different slots never tie.
+__device__ __forceinline__ u64 make_key(float d, uint32_t slot) { return ((u64)dist_image(d) << 32) | ((u64)slot << 1); }
+__device__ __forceinline__ uint32_t key_slot(u64 k) { return (uint32_t)(k & 0xFFFFFFFFull) >> 1; }
+
+// integer finaliser used for the seed jitter (the public-domain MurmurHash3 finaliser)
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+    return x;
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m);
+    return v;
+}
+
+// first index i in sorted a[0..n) with a[i] >= key (strict=false) or a[i] > key (strict=true):
+// a 64-way search, each step probing 64 evenly spaced positions with the whole wave
+__device__ int wave_bound(const int32_t *__restrict__ a, int n, int key, bool strict, int lane) {
+    int lo = 0, hi = n;
+    while (hi > lo) {
+        int chunk = (hi - lo + 63) >> 6;
+        int pos = lo + lane * chunk;
+        bool below = false;
+        if (pos < hi) {
+            int x = a[pos];
+            below = strict ? (x <= key) : (x < key);
+        }
+        int c = __popcll(__ballot(below));  // sorted input: the first c probes are below
+        if (c == 0) {
+            hi = lo;
+        } else {
+            int nlo = lo + (c - 1) * chunk + 1;
+            int nhi = lo + c * chunk;
+            hi = nhi < hi ? nhi : hi;
+            lo = nlo;
+        }
+    }
+    return lo;
+}
+
+template <int NCH>
+struct EvalShape {
+    // pieces of a row held in registers at once, and rows per lane group in flight
+    static constexpr int CB = NCH <= 8 ? NCH
+                              : (NCH % 10 == 0 ? 10 : (NCH % 8 == 0 ? 8 : (NCH % 6 == 0 ? 6 : (NCH % 4 == 0 ? 4 : (NCH % 3 == 0 ? 3 : (NCH % 2 == 0 ? 2 : 1))))));
+    static constexpr int R0 = 16 / CB;
+    static constexpr int R = R0 < 1 ? 1 : (R0 > 8 ? 8 : R0);
+    static constexpr bool QREG = NCH <= 8;
+};
+
+// Gathered distances (Algorithm 2, ComputeDistance) for the n slots in L: eight lanes share a
+// row, lane `sub` of a group takes the 16-byte pieces 8c+sub (one 128-byte line per piece
+// index across the group) and accumulates them in index order with fused multiply-adds; the
+// eight partial sums are combined by an xor-butterfly (1, 2, 4).  This fixed order makes the
+// fp32 result reproducible bit for bit.  Writes the keys to C[0..n).
+template <int NCH, bool KEYS = true>
+__device__ __forceinline__ void eval_rows(const float *__restrict__ X, const float4 *qreg, const float *qlds,
+                                          const uint32_t *L, int n, u64 *C, int lane, int metric,
+                                          float *dist_out = nullptr) {
+    constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R;
+    constexpr int D4 = NCH * 8;  // 16-byte pieces per row
+    const int sub = lane & 7, grp = lane >> 3;
+    for (int base = 0; base < n; base += 8 * R) {
+        float acc[R];
+        uint32_t v[R];
+        bool act[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            int idx = base + r * 8 + grp;
+            act[r] = idx < n;
+            v[r] = act[r] ? L[idx] : 0u;
+            acc[r] = 0.0f;
+        }
+#pragma unroll
+        for (int c0 = 0; c0 < NCH; c0 += CB) {
+            float4 buf[R][CB];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v[r] * D4 + sub;
+#pragma unroll
+                for (int cc = 0; cc < CB; ++cc)
+                    buf[r][cc] = act[r] ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
+            }
+#pragma unroll
+            for (int cc = 0; cc < CB; ++cc) {
+                float4 qv;
+                if constexpr (EvalShape<NCH>::QREG) qv = qreg[c0 + cc];
+                else qv = reinterpret_cast<const float4 *>(qlds)[(c0 + cc) * 8 + sub];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    float4 x = buf[r][cc];
+                    if (metric == GRAB_L2SQ) {
+                        float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+                        acc[r] = __builtin_fmaf(dx, dx, acc[r]);
+                        acc[r] = __builtin_fmaf(dy, dy, acc[r]);
+                        acc[r] = __builtin_fmaf(dz, dz, acc[r]);
+                        acc[r] = __builtin_fmaf(dw, dw, acc[r]);
+                    } else {
+                        acc[r] = __builtin_fmaf(qv.x, x.x, acc[r]);
+                        acc[r] = __builtin_fmaf(qv.y, x.y, acc[r]);
+                        acc[r] = __builtin_fmaf(qv.z, x.z, acc[r]);
+                        acc[r] = __builtin_fmaf(qv.w, x.w, acc[r]);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            float s = acc[r];
+            s += __shfl_xor(s, 1);
+            s += __shfl_xor(s, 2);
+            s += __shfl_xor(s, 4);
+            if (metric != GRAB_L2SQ) s = -s;
+            if (act[r] && sub == 0) {
+                if constexpr (KEYS) C[base + r * 8 + grp] = make_key(s, v[r]);
+                else dist_out[base + r * 8 + grp] = s;
+            }
+        }
+    }
+}
+
+
+// the "query" side of eval_rows from a row in memory: registers for rows up to 256 floats,
+// LDS (qlds, dim floats) beyond; callers synchronise before the next eval_rows
+template <int NCH>
+__device__ __forceinline__ void load_query(const float *__restrict__ row, float4 *qreg, float *qlds, int lane) {
+    const float4 *src = reinterpret_cast<const float4 *>(row);
+    if constexpr (EvalShape<NCH>::QREG) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) qreg[c] = src[c * 8 + (lane & 7)];
+    } else {
+        for (int i = lane; i < NCH * 8; i += 64) reinterpret_cast<float4 *>(qlds)[i] = src[i];
+    }
+}
+
+}  // namespace

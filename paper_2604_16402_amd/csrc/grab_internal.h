@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #include <string>
+#include <vector>
 
 #include "grab.h"
 
@@ -73,6 +74,7 @@ struct grab_index {
     // grow-only work buffers
     DevBuf plans, seeds, counters, stage_q, stage_lo, stage_hi, stage_ids, stage_dist, stage_misc, flags;
     int64_t last_nq = 0;
+    std::vector<DevBuf> app;     // append's work arena
 
     bool profile = false;
     bool timed = false;          // the last search recorded events
@@ -117,3 +119,7 @@ struct SearchLaunch {
 };
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s);
 grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s);
+// append: the whole insertion for m objects already on the device; `proto` carries the search
+// parameters resolved for beam = append_beam
+grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_t *d_attrs, int64_t m,
+                               const SearchLaunch &proto);
