@@ -80,7 +80,8 @@ def main():
     ix = binding.Index(cfg.dim, cfg.metric, stream=stream.cuda_stream)
     Xd, ad = torch.from_numpy(X).to(dev), torch.from_numpy(attrs).to(dev)
     t0 = time.time()
-    ix.build_buckets(Xd, ad, cfg.buckets)
+    n_cap = cfg.n + int(1.2 * cfg.append_rounds * cfg.append_batch)
+    ix.build_buckets(Xd, ad, cfg.buckets, n_cap)
     table, id2slot, _ = ix.get_layout()
     ends = table[:, 0].astype(np.int64) + table[:, 3]
     bucket_of = np.searchsorted(ends, id2slot.astype(np.int64), side="right")
@@ -97,6 +98,9 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if cfg.append_rounds:
+        return run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev)
 
     qd = torch.from_numpy(q).to(dev)
     lod, hid = torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)
@@ -228,6 +232,75 @@ def main():
         "roofline": roofline, "cpu_baseline": cpu, "parity_vs_oracle": parity,
         "hbm_frac_of_peak": round(achieved / PEAK_HBM_GBS, 4),
     }
+    ix.close()
+    print(json.dumps(out), flush=True)
+
+
+def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev):
+    """Dynamic workload: rounds of `grab_append_batch` (100k new objects with attributes over the
+    whole domain) each followed by a fresh 10k-query search batch at 10 % range (Section 5.3's
+    stability protocol on synthetic data).  Reports append vectors/s and search QPS per round."""
+    import torch
+    from paper_2604_16402_amd import groundtruth as GT, workloads as W
+    k = cfg.k
+    beam, S, w, vc = (int(x) for x in (args.config or "32,512,4,1400").split(","))
+    ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
+    rounds = []
+    allX, alla = Xd, ad
+    for r in range(cfg.append_rounds):
+        nx = torch.from_numpy(W.append_vectors(cfg, r)).to(dev)
+        na = torch.from_numpy(W.append_attributes(cfg, r)).to(dev)
+        # append's own searches use the library defaults (beam 64, 64 seeds, width 1)
+        ix.set_param("visited_cap", 2800); ix.set_param("n_seeds", 0); ix.set_param("search_width", 1)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        ix.append_batch(nx, na)
+        torch.cuda.synchronize()
+        t_app = time.perf_counter() - t
+        allX, alla = torch.cat([allX, nx]), torch.cat([alla, na])
+        ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
+        q = torch.from_numpy(W.query_vectors(cfg, stream=100 + r)).to(dev)
+        lo, hi = W.ranges(cfg, args.selectivity, stream=300 + r)
+        lod, hid = torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)
+        ids = torch.empty((len(q), k), dtype=torch.int32, device=dev)
+        dist = torch.empty((len(q), k), dtype=torch.float32, device=dev)
+        ix.search_range(q, lod, hid, k, beam, ids, dist)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        for _ in range(10):
+            ix.search_range(q, lod, hid, k, beam, ids, dist)
+        torch.cuda.synchronize()
+        t_s = (time.perf_counter() - t) / 10
+        gt = GT.exact_filtered_knn(allX, alla, q, lod, hid, k, cfg.metric)
+        new_frac = float((ids.cpu().numpy().view(np.uint32) >= cfg.n).mean())
+        rounds.append({"round": r + 1, "objects": ix.sizes()["n"], "append_vectors_per_s": round(cfg.append_batch / t_app, 1),
+                       "append_ms": round(t_app * 1e3, 2), "search_qps": round(len(q) / t_s, 1),
+                       "recall_at_10": round(GT.recall(ids, gt), 4), "results_from_appended": round(new_frac, 4)})
+        log(f"[bench] round {r + 1}: {rounds[-1]}")
+    # context: the same final data set bulk-built by the harness, searched with the same setting
+    from paper_2604_16402_amd import binding
+    ref = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
+    ref.build_buckets(allX, alla, cfg.buckets)
+    table, id2slot, _ = ref.get_layout()
+    ends = table[:, 0].astype(np.int64) + table[:, 3]
+    la, ra = W.build_graph(allX.cpu().numpy(), np.searchsorted(ends, id2slot.astype(np.int64), side="right"), cfg.buckets,
+                           cfg.k_local, cfg.k_remote, metric=cfg.metric, device="cuda:0", chunk=16384)
+    ref.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
+    ref.set_param("visited_cap", vc); ref.set_param("n_seeds", S); ref.set_param("search_width", w)
+    ref.search_range(q, lod, hid, k, beam, ids, dist)
+    torch.cuda.synchronize()
+    rebuilt = {"recall_at_10": round(GT.recall(ids, gt), 4)}
+    ref.close()
+    log(f"[bench] bulk-rebuilt reference on the final {ix.sizes()['n']} objects: {rebuilt}")
+    out = {"metric": "dynamic workload: append vectors/s and filtered queries/s per round (1M -> 2M x 128 fp32, 10% range)",
+           "value": round(float(np.mean([x["append_vectors_per_s"] for x in rounds])), 1), "unit": "appended vectors/s",
+           "n_gpus": 1, "higher_is_better": True, "dtype": "f32", "data": "synthetic", "vs_baseline": None,
+           "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32 growing by {cfg.append_rounds} x {cfg.append_batch}, "
+                                  f"{cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, 10000 queries per round, "
+                                  f"{args.selectivity:.0%} range, k={k}",
+                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": 64, "alpha": 0.6},
+           "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
+           "bulk_rebuilt_reference_final": rebuilt}
     ix.close()
     print(json.dumps(out), flush=True)
 

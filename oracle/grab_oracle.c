@@ -435,8 +435,12 @@ int oracle_max_threads(void) {
  *     current local (or remote) part of v's row and a = alpha (squared for the squared-L2
  *     metric, so that the test is the paper's on true Euclidean distances):
  *       pass  = a*dist(v,q) < dist(q,n) for every n in R           (Eq. 2 with Eq. 3's d_eff)
- *       if !pass: drop.  Else if R has an empty entry: fill the first one.  Else let n* be the
- *       entry of R farthest from v (ties: larger slot); replace it iff a*dist(v,q) < dist(v,n*).
+ *       if !pass: drop.  Else if R has an empty entry: fill the first one.  Else, among the
+ *       entries n with dist(q,n) < dist(v,n) (v can still reach n through q), the one nearest
+ *       to q (ties: smaller slot) is overwritten; if there is none the request is dropped.
+ *       Evicting the farthest neighbour instead would keep only the closest ones, which the
+ *       paper warns turns the graph into isolated cliques (Section 4.4, topology maintenance);
+ *       on clustered data it removed exactly the long links and recall fell with every batch.
  *     Fresh nodes already placed in R by this batch count as ordinary neighbours.
  *  6. Table: n_total grows by the bucket's batch count; min/max absorb the new attributes.
  */
@@ -590,13 +594,17 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         }
         if (!pass) continue;
         if (empty_at >= 0) { R[empty_at] = req[r].q; continue; }
-        int far = -1; uint32_t far_img = 0;
+        /* the newcomer takes the place of the neighbour whose pathway it covers best: among the
+         * entries n that are closer to q than to v, the one nearest to q (ties: smaller slot) */
+        int victim = -1; uint32_t victim_img = 0;
         for (int j = 0; j < len; ++j) {
-            uint32_t im = dist_image(oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric));
-            if (far < 0 || im > far_img || (im == far_img && R[j] > R[far])) { far = j; far_img = im; }
+            float dvn = oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric);
+            float dqn = oracle_distance(xq, ix->X + (size_t)R[j] * dim, dim, ix->metric);
+            if (!(dqn < dvn)) continue;
+            uint32_t im = dist_image(dqn);
+            if (victim < 0 || im < victim_img || (im == victim_img && R[j] < R[victim])) { victim = j; victim_img = im; }
         }
-        float dfar = oracle_distance(xv, ix->X + (size_t)R[far] * dim, dim, ix->metric);
-        if (lhs < dfar) R[far] = req[r].q;
+        if (victim >= 0) R[victim] = req[r].q;
     }
     /* 6 */
     for (int64_t i = 0; i < m; ++i) {

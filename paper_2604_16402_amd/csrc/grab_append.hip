@@ -257,16 +257,17 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
             if (empties) {
                 at = __ffsll((long long)empties) - 1;
             } else {
-                u64 kf = lane < len ? (((u64)dist_image(dv[lane]) << 32) | (u64)mine) : 0ull;
-                u64 kmax = kf;
+                // victim: among the entries closer to q than to v, the one nearest to q
+                const bool covered = lane < len && dq[lane] < dv[lane];
+                u64 kf = covered ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : ~0ull;
+                u64 kmin = kf;
 #pragma unroll
                 for (int s = 32; s > 0; s >>= 1) {
-                    uint32_t hi = __shfl_xor((uint32_t)(kmax >> 32), s), lo = __shfl_xor((uint32_t)kmax, s);
+                    uint32_t hi = __shfl_xor((uint32_t)(kmin >> 32), s), lo = __shfl_xor((uint32_t)kmin, s);
                     u64 other = ((u64)hi << 32) | lo;
-                    kmax = other > kmax ? other : kmax;
+                    kmin = other < kmin ? other : kmin;
                 }
-                const int far = __ffsll((long long)__ballot(lane < len && kf == kmax)) - 1;
-                if (lhs < dv[far]) at = far;
+                if (kmin != ~0ull) at = __ffsll((long long)__ballot(covered && kf == kmin)) - 1;
             }
             __syncthreads();
             if (at >= 0) {

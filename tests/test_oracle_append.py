@@ -180,13 +180,21 @@ def test_bias_opens_rows_for_newcomers():
         changed = (ix.A[ix.id2slot[:3000]] != pre[ix.id2slot[:3000]])
         assert (np.isin(ix.A[ix.id2slot[:3000]][changed], list(new))).all()      # old rows change only by gaining fresh nodes
     assert got[1e-6] >= got[0.6] >= got[1.0] and got[0.6] > got[1.0]
-    # alpha -> 0: every rewiring request passes and evicts the farthest neighbour, so the last
-    # request applied to a row is always present in it: every fresh node points to targets that...
+    # alpha -> 0 and a batch of one: every request passes the biased check, so a target takes the
+    # newcomer exactly when it has an empty entry or a neighbour closer to the newcomer than to itself
     cfg, ix = _fresh(1e-6)
-    ix.append(W.append_vectors(cfg, 0)[:1], W.append_attributes(cfg, 0)[:1])
+    pre = ix.A.copy()
+    nx = W.append_vectors(cfg, 0)[:1]
+    ix.append(nx, W.append_attributes(cfg, 0)[:1])
     s = ix.id2slot[3000]
-    targets = ix.A[s][ix.A[s] != O.EMPTY]
-    assert all(s in ix.A[t] for t in targets)                                    # batch of one: every target took it
+    kl = ix.k_local
+    row = ix.A[s]
+    for j, t in enumerate(row):
+        if t == O.EMPTY:
+            continue
+        part = pre[t][:kl] if j < kl else pre[t][kl:]
+        covered = any(n == O.EMPTY or O.distance(nx[0], ix.X[n]) < O.distance(ix.X[t], ix.X[n]) for n in part)
+        assert (s in ix.A[t]) == covered
 
 
 def test_full_bucket_fails_without_partial_writes():
