@@ -171,7 +171,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
             if (nk > 0) {
                 load_query<NCH>(a.X + (size_t)c * D, qreg, qlds, lane);
                 if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-                eval_rows<NCH, false>(a.X, qreg, qlds, kept, nk, nullptr, lane, a.metric, dtmp);
+                eval_rows<NCH>(a.X, qreg, qlds, kept, nk, lane, a.metric, dtmp);
                 __syncthreads();
                 bool hidden = lane < nk && !(dqc < dtmp[lane]);
                 ok = __ballot(hidden) == 0;
@@ -237,7 +237,7 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
     }
     load_query<NCH>(a.X + (size_t)v * D, qreg, qlds, lane);
     __syncthreads();
-    eval_rows<NCH, false>(a.X, qreg, qlds, Rl, len, nullptr, lane, a.metric, dv);
+    eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dv);
     __syncthreads();
     bool changed = false;
     for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
         const float lhs = a.a * dvq;
         load_query<NCH>(a.X + (size_t)q * D, qreg, qlds, lane);
         if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-        eval_rows<NCH, false>(a.X, qreg, qlds, Rl, len, nullptr, lane, a.metric, dq);
+        eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);
         __syncthreads();
         const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
         const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < dq[lane]);

@@ -68,77 +68,94 @@ struct EvalShape {
     static constexpr bool QREG = NCH <= 8;
 };
 
-// Gathered distances (Algorithm 2, ComputeDistance) for the n slots in L: eight lanes share a
-// row, lane `sub` of a group takes the 16-byte pieces 8c+sub (one 128-byte line per piece
-// index across the group) and accumulates them in index order with fused multiply-adds; the
-// eight partial sums are combined by an xor-butterfly (1, 2, 4).  This fixed order makes the
-// fp32 result reproducible bit for bit.  Writes the keys to C[0..n).
-template <int NCH, bool KEYS = true>
-__device__ __forceinline__ void eval_rows(const float *__restrict__ X, const float4 *qreg, const float *qlds,
-                                          const uint32_t *L, int n, u64 *C, int lane, int metric,
-                                          float *dist_out = nullptr) {
+// lane exchanges inside groups of eight lanes without touching LDS: DPP quad permutes give
+// xor 1 and xor 2, the half-row mirror pairs lane i with lane 7-i of its group
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+}
+
+// Gathered distances (Algorithm 2, ComputeDistance) for up to 8*R slots L[base..]: eight lanes
+// share a row, lane `sub` of a group takes the 16-byte pieces 8c+sub (one 128-byte line per
+// piece index across the group) and accumulates them in index order with fused multiply-adds;
+// the eight partial sums are combined pairwise (lanes 0+1, 2+3, ..., then pairs, then halves).
+// This fixed order makes the fp32 result reproducible bit for bit.  All loads of the batch are
+// issued before the first multiply.  Every lane of a group ends with the row's distance in
+// s[r]; v[r] is the row's slot and act[r] tells whether round r had a row for this group.
+template <int NCH>
+__device__ __forceinline__ void eval_batch(const float *__restrict__ X, const float4 *qreg, const float *qlds,
+                                           const uint32_t *L, int base, int n, int lane, int metric,
+                                           float (&s)[EvalShape<NCH>::R], uint32_t (&v)[EvalShape<NCH>::R],
+                                           bool (&act)[EvalShape<NCH>::R]) {
     constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R;
     constexpr int D4 = NCH * 8;  // 16-byte pieces per row
     const int sub = lane & 7, grp = lane >> 3;
-    for (int base = 0; base < n; base += 8 * R) {
-        float acc[R];
-        uint32_t v[R];
-        bool act[R];
+    float acc[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        int idx = base + r * 8 + grp;
+        act[r] = idx < n;
+        v[r] = act[r] ? L[idx] : 0u;
+        acc[r] = 0.0f;
+    }
+#pragma unroll
+    for (int c0 = 0; c0 < NCH; c0 += CB) {
+        float4 buf[R][CB];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            int idx = base + r * 8 + grp;
-            act[r] = idx < n;
-            v[r] = act[r] ? L[idx] : 0u;
-            acc[r] = 0.0f;
+            const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v[r] * D4 + sub;
+#pragma unroll
+            for (int cc = 0; cc < CB; ++cc)
+                buf[r][cc] = act[r] ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
 #pragma unroll
-        for (int c0 = 0; c0 < NCH; c0 += CB) {
-            float4 buf[R][CB];
+        for (int cc = 0; cc < CB; ++cc) {
+            float4 qv;
+            if constexpr (EvalShape<NCH>::QREG) qv = qreg[c0 + cc];
+            else qv = reinterpret_cast<const float4 *>(qlds)[(c0 + cc) * 8 + sub];
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v[r] * D4 + sub;
-#pragma unroll
-                for (int cc = 0; cc < CB; ++cc)
-                    buf[r][cc] = act[r] ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-#pragma unroll
-            for (int cc = 0; cc < CB; ++cc) {
-                float4 qv;
-                if constexpr (EvalShape<NCH>::QREG) qv = qreg[c0 + cc];
-                else qv = reinterpret_cast<const float4 *>(qlds)[(c0 + cc) * 8 + sub];
-#pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    float4 x = buf[r][cc];
-                    if (metric == GRAB_L2SQ) {
-                        float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
-                        acc[r] = __builtin_fmaf(dx, dx, acc[r]);
-                        acc[r] = __builtin_fmaf(dy, dy, acc[r]);
-                        acc[r] = __builtin_fmaf(dz, dz, acc[r]);
-                        acc[r] = __builtin_fmaf(dw, dw, acc[r]);
-                    } else {
-                        acc[r] = __builtin_fmaf(qv.x, x.x, acc[r]);
-                        acc[r] = __builtin_fmaf(qv.y, x.y, acc[r]);
-                        acc[r] = __builtin_fmaf(qv.z, x.z, acc[r]);
-                        acc[r] = __builtin_fmaf(qv.w, x.w, acc[r]);
-                    }
+                float4 x = buf[r][cc];
+                if (metric == GRAB_L2SQ) {
+                    float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+                    acc[r] = __builtin_fmaf(dx, dx, acc[r]);
+                    acc[r] = __builtin_fmaf(dy, dy, acc[r]);
+                    acc[r] = __builtin_fmaf(dz, dz, acc[r]);
+                    acc[r] = __builtin_fmaf(dw, dw, acc[r]);
+                } else {
+                    acc[r] = __builtin_fmaf(qv.x, x.x, acc[r]);
+                    acc[r] = __builtin_fmaf(qv.y, x.y, acc[r]);
+                    acc[r] = __builtin_fmaf(qv.z, x.z, acc[r]);
+                    acc[r] = __builtin_fmaf(qv.w, x.w, acc[r]);
                 }
             }
         }
+    }
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            float s = acc[r];
-            s += __shfl_xor(s, 1);
-            s += __shfl_xor(s, 2);
-            s += __shfl_xor(s, 4);
-            if (metric != GRAB_L2SQ) s = -s;
-            if (act[r] && sub == 0) {
-                if constexpr (KEYS) C[base + r * 8 + grp] = make_key(s, v[r]);
-                else dist_out[base + r * 8 + grp] = s;
-            }
-        }
+    for (int r = 0; r < R; ++r) {
+        float t = acc[r];
+        t += dpp_move<0xB1>(t);   // quad_perm [1,0,3,2]: lane ^ 1
+        t += dpp_move<0x4E>(t);   // quad_perm [2,3,0,1]: lane ^ 2
+        t += dpp_move<0x141>(t);  // row_half_mirror: the other half of the group of eight
+        s[r] = metric == GRAB_L2SQ ? t : -t;
     }
 }
 
+// distances of the n slots in L to the query, written to dist_out[0..n)
+template <int NCH>
+__device__ __forceinline__ void eval_rows(const float *__restrict__ X, const float4 *qreg, const float *qlds,
+                                          const uint32_t *L, int n, int lane, int metric, float *dist_out) {
+    constexpr int R = EvalShape<NCH>::R;
+    for (int base = 0; base < n; base += 8 * R) {
+        float s[R];
+        uint32_t v[R];
+        bool act[R];
+        eval_batch<NCH>(X, qreg, qlds, L, base, n, lane, metric, s, v, act);
+#pragma unroll
+        for (int r = 0; r < R; ++r)
+            if (act[r] && (lane & 7) == 0) dist_out[base + r * 8 + (lane >> 3)] = s[r];
+    }
+}
 
 // the "query" side of eval_rows from a row in memory: registers for rows up to 256 floats,
 // LDS (qlds, dim floats) beyond; callers synchronise before the next eval_rows

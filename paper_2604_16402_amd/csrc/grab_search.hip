@@ -207,34 +207,118 @@ __device__ void merge_queue(u64 *Q, int QP, const u64 *C, int CP, int beam, int 
     }
 }
 
-template <int NCH>
+// ---- a 64-entry queue held one key per lane, sorted and merged with lane exchanges ----------
+__device__ __forceinline__ u64 shfl64(u64 k, int src) {
+    return ((u64)(uint32_t)__shfl((int)(k >> 32), src) << 32) | (u64)(uint32_t)__shfl((int)(k & 0xFFFFFFFFull), src);
+}
+__device__ __forceinline__ u64 shfl_xor64(u64 k, int m) {
+    return ((u64)(uint32_t)__shfl_xor((int)(k >> 32), m) << 32) | (u64)(uint32_t)__shfl_xor((int)(k & 0xFFFFFFFFull), m);
+}
+// ascending bitonic sort of the keys of lanes [0,P); lanes beyond hold SENT and stay put
+__device__ __forceinline__ u64 sort_lanes(u64 key, int P, int lane) {
+    for (int k = 2; k <= P; k <<= 1)
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            u64 o = shfl_xor64(key, j);
+            bool take_min = ((lane & j) == 0) == ((lane & k) == 0);
+            bool less = key < o;
+            key = (less == take_min) ? key : o;
+        }
+    return key;
+}
+// queue (sorted, one key per lane) <- the 64 smallest of queue and ck (sorted), cut to beam
+__device__ __forceinline__ u64 merge_lanes(u64 qk, u64 ck, int beam, int lane) {
+    u64 r = shfl64(ck, 63 - lane);
+    u64 m = qk < r ? qk : r;
+#pragma unroll
+    for (int j = 32; j > 0; j >>= 1) {
+        u64 o = shfl_xor64(m, j);
+        bool take_min = (lane & j) == 0;
+        bool less = m < o;
+        m = (less == take_min) ? m : o;
+    }
+    return lane < beam ? m : SENT;
+}
+
+// One query per wavefront.  QR: the queue (beam <= 64) lives in registers, one key per lane,
+// and new keys are sorted/merged with lane exchanges in groups of at most 64; otherwise the
+// queue lives in LDS and is merged there.  In both variants a new key is dropped at once when
+// it is not smaller than the current worst key of a full queue: it could never enter.
+template <int NCH, bool QR>
 __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int D = NCH * 32;
+    constexpr int R = EvalShape<NCH>::R;
     const int lane = threadIdx.x;
     const int64_t q = blockIdx.x;
     const int H = 1 << a.hbits;
-    u64 *Q = reinterpret_cast<u64 *>(smem);
-    u64 *C = Q + a.QP;
-    uint32_t *hash = reinterpret_cast<uint32_t *>(C + a.maxc);
-    uint32_t *L = hash + H;
-    uint32_t *par = L + a.maxc;   // 8 parent slots + 8 queue positions
+    const int ccap = QR ? 64 : a.maxc;
+    u64 *Q = reinterpret_cast<u64 *>(smem);                 // LDS queue (unused when QR)
+    u64 *C = Q + (QR ? 0 : a.QP);                           // keys waiting to be merged
+    uint32_t *hash = reinterpret_cast<uint32_t *>(C + ccap);
+    uint32_t *L = hash + H;                                 // slots to evaluate
+    uint32_t *par = L + a.maxc;                             // parent slots
     float *qlds = reinterpret_cast<float *>(par + 16);
 
     const QueryPlan p = a.plans[q];
     const int lo = a.lo[q], hi = a.hi[q];
     uint32_t c_iters = 0, c_par = 0, c_evals = 0, c_seed = 0, c_rej = 0, c_tail = 0, c_vis = 0, c_stop = 0;
 
-    // query row -> registers (or LDS for long rows), in the piece order eval_rows uses
+    // query row -> registers (or LDS for long rows), in the piece order eval_batch uses
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
     load_query<NCH>(a.queries + q * D, qreg, qlds, lane);
     for (int i = lane; i < H / 4; i += 64) reinterpret_cast<uint4 *>(hash)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
-    for (int i = lane; i < a.QP; i += 64) Q[i] = SENT;
+    if constexpr (!QR)
+        for (int i = lane; i < a.QP; i += 64) Q[i] = SENT;
     __syncthreads();
 
     const uint32_t hmask = (uint32_t)H - 1;
     const int hshift = 32 - a.hbits;
     const u64 lt_mask = (1ull << lane) - 1ull;
+    u64 qk = SENT;    // QR: this lane's queue entry
+    u64 thr = SENT;   // worst key of a full queue, SENT while it has room
+    int cnt = 0;      // keys waiting in C
+
+    // merge the cnt keys waiting in C into the queue
+    auto flush = [&]() {
+        if (cnt == 0) return;
+        int P = 2;
+        while (P < cnt) P <<= 1;
+        if constexpr (QR) {
+            u64 ck = lane < cnt ? C[lane] : SENT;
+            ck = sort_lanes(ck, P, lane);
+            qk = merge_lanes(qk, ck, a.beam, lane);
+            thr = shfl64(qk, a.beam - 1);
+        } else {
+            for (int i = cnt + lane; i < P; i += 64) C[i] = SENT;
+            __syncthreads();
+            bitonic_sort(C, P, lane);
+            merge_queue(Q, a.QP, C, P, a.beam, lane);
+            thr = Q[a.beam - 1];
+        }
+        cnt = 0;
+        __syncthreads();
+    };
+    // ComputeDistance + UpdateQueue for the n slots in L
+    auto evaluate = [&](int n) {
+        const int sub = lane & 7;
+        for (int base = 0; base < n; base += 8 * R) {
+            if (QR && cnt + 8 * R > 64) flush();
+            float s[R];
+            uint32_t v[R];
+            bool act[R];
+            eval_batch<NCH>(a.X, qreg, qlds, L, base, n, lane, a.metric, s, v, act);
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                u64 key = make_key(s[r], v[r]);
+                bool keep = act[r] && sub == 0 && key < thr;
+                u64 m = __ballot(keep);
+                if (keep) C[cnt + __popcll(m & lt_mask)] = key;
+                cnt += __popcll(m);
+            }
+            __syncthreads();
+        }
+        flush();
+    };
 
     if (p.b1 < p.b0) {
         c_stop = 3;
@@ -256,16 +340,8 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
                 n_c += __popcll(m);
             }
             __syncthreads();
-            if (n_c > 0) {
-                c_vis += n_c; c_evals += n_c; c_seed += n_c;
-                eval_rows<NCH>(a.X, qreg, qlds, L, n_c, C, lane, a.metric);
-                int CP = 2;
-                while (CP < n_c) CP <<= 1;
-                for (int i = n_c + lane; i < CP; i += 64) C[i] = SENT;
-                __syncthreads();
-                bitonic_sort(C, CP, lane);
-                merge_queue(Q, a.QP, C, CP, a.beam, lane);
-            }
+            c_vis += n_c; c_evals += n_c; c_seed += n_c;
+            evaluate(n_c);
         }
         // ---- greedy expansion (Algorithm 2, the while loop)
         const uint32_t recipK = (65536u + (uint32_t)a.K - 1u) / (uint32_t)a.K;
@@ -273,20 +349,36 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
             if ((int)c_iters == a.max_iter) { c_stop = 1; break; }
             // PopUnvisited: first `width` queue entries not yet expanded
             int np = 0;
-            for (int c = 0; c < a.QP && np < a.width; c += 64) {
-                u64 key = Q[c + lane];
-                u64 m = __ballot(key != SENT && !(key & 1ull));
+            u64 chosen = 0;  // QR: lanes picked as parents
+            if constexpr (QR) {
+                u64 m = __ballot(qk != SENT && !(qk & 1ull));
                 while (m && np < a.width) {
                     int b = __ffsll((long long)m) - 1;
                     m &= m - 1;
-                    if (lane == b) { par[np] = key_slot(key); par[8 + np] = (uint32_t)(c + lane); }
+                    chosen |= 1ull << b;
+                    if (lane == b) par[np] = key_slot(qk);
                     ++np;
+                }
+            } else {
+                for (int c = 0; c < a.QP && np < a.width; c += 64) {
+                    u64 key = Q[c + lane];
+                    u64 m = __ballot(key != SENT && !(key & 1ull));
+                    while (m && np < a.width) {
+                        int b = __ffsll((long long)m) - 1;
+                        m &= m - 1;
+                        if (lane == b) { par[np] = key_slot(key); par[8 + np] = (uint32_t)(c + lane); }
+                        ++np;
+                    }
                 }
             }
             if (np == 0) break;
             if ((int)c_vis + np * a.K > a.visited_cap) { c_stop = 2; break; }
             __syncthreads();
-            if (lane < np) Q[par[8 + lane]] |= 1ull;
+            if constexpr (QR) {
+                if ((chosen >> lane) & 1ull) qk |= 1ull;
+            } else {
+                if (lane < np) Q[par[8 + lane]] |= 1ull;
+            }
             c_iters += 1; c_par += np;
             // GatherNeighbors + pre-check + visited test, all parents' rows at once
             const int total = np * a.K;
@@ -310,21 +402,14 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
                 n_c += __popcll(m);
             }
             __syncthreads();
-            if (n_c > 0) {
-                c_vis += n_c; c_evals += n_c;
-                eval_rows<NCH>(a.X, qreg, qlds, L, n_c, C, lane, a.metric);
-                int CP = 2;
-                while (CP < n_c) CP <<= 1;
-                for (int i = n_c + lane; i < CP; i += 64) C[i] = SENT;
-                __syncthreads();
-                bitonic_sort(C, CP, lane);
-                merge_queue(Q, a.QP, C, CP, a.beam, lane);   // UpdateQueue
-            }
+            c_vis += n_c; c_evals += n_c;
+            evaluate(n_c);
         }
     }
     // ---- Top-k from the queue
     for (int j = lane; j < a.k; j += 64) {
-        u64 key = Q[j];
+        u64 key;
+        if constexpr (QR) key = qk; else key = Q[j];
         uint32_t id = GRAB_EMPTY;
         float d = __builtin_inff();
         if (key != SENT) {
@@ -343,13 +428,18 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
 }
 
 template <int NCH>
-grab_status launch_beam_t(grab_index *ix, const BeamArgs &a, int64_t nq, size_t lds) {
+grab_status launch_beam_t(grab_index *ix, const BeamArgs &a, int64_t nq, int H) {
+    const bool qr = a.QP == 64;
+    size_t lds = (size_t)(qr ? 64 : a.QP + a.maxc) * 8 + (size_t)H * 4 + (size_t)a.maxc * 4 + 16 * 4;
+    if (!EvalShape<NCH>::QREG) lds += (size_t)ix->dim * 4;
+    const void *fn = qr ? reinterpret_cast<const void *>(&k_beam_search<NCH, true>)
+                        : reinterpret_cast<const void *>(&k_beam_search<NCH, false>);
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_search<NCH>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return grab_fail(ix, GRAB_EHIP, "LDS request of %zu bytes refused: %s", lds, hipGetErrorString(e));
     }
-    k_beam_search<NCH><<<dim3((unsigned)nq), dim3(64), lds, ix->stream>>>(a);
+    if (qr) k_beam_search<NCH, true><<<dim3((unsigned)nq), dim3(64), lds, ix->stream>>>(a);
+    else k_beam_search<NCH, false><<<dim3((unsigned)nq), dim3(64), lds, ix->stream>>>(a);
     GRAB_HIP(ix, hipGetLastError());
     return GRAB_OK;
 }
@@ -385,10 +475,8 @@ grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s) {
     a.maxc = pow2_at_least(s.width * a.K, 64);
     a.metric = ix->metric; a.out_slots = s.out_slots ? 1 : 0;
     const int nch = ix->dim / 32;
-    size_t lds = (size_t)a.QP * 8 + (size_t)a.maxc * 8 + (size_t)H * 4 + (size_t)a.maxc * 4 + 16 * 4;
-    if (nch > 8) lds += (size_t)ix->dim * 4;
     switch (nch) {
-#define GRAB_CASE(N) case N: return launch_beam_t<N>(ix, a, s.nq, lds);
+#define GRAB_CASE(N) case N: return launch_beam_t<N>(ix, a, s.nq, H);
         GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
         GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
 #undef GRAB_CASE
