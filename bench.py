@@ -139,7 +139,7 @@ def main():
         best = None
         for c in GRID:
             beam = set_cfg(c)
-            sec = timed(beam, 3)
+            sec = timed(beam, 20)
             rec = GT.recall(ids, gt)
             log(f"[bench] grid beam={c[0]} seeds={c[1]} width={c[2]} visited_cap={c[3]}: recall@10={rec:.4f} {nq / sec:,.0f} q/s")
             if rec >= 0.95 and (best is None or sec < best[0]):
@@ -186,10 +186,12 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic_beam_search_c2.json")
     if os.path.exists(tpath) and args.workload == "c2" and not args.scale:
         try:
-            traffic = json.load(open(tpath)).get("hbm_bytes_per_launch")
+            tj = json.load(open(tpath))
+            if list(tj.get("config", [])) == [chosen[0], chosen[1], chosen[2], max(chosen[3], chosen[1])]:
+                traffic = tj.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
-    roofline = {"bound": "hbm", "kernel": "k_beam_search<4>", "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+    roofline = {"bound": "hbm", "kernel": "k_beam_search<%d,%s>" % (cfg.dim // 32, "true" if chosen[0] <= 64 else "false"), "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": bytes_per_launch, "avg_kernel_ms": round(avg_beam_ms, 4),
                 "select_kernel_ms": round(float(np.mean(select_ms)), 4),
