@@ -29,9 +29,9 @@ METRIC = "filtered queries/sec at recall@10>=0.95 (1M x 128 fp32, 10% range), % 
 
 # (beam, n_seeds, search_width, visited_cap)
 GRID = [
-    (64, 64, 1, 2800), (64, 128, 1, 1400), (64, 256, 1, 1400), (64, 256, 2, 1400), (64, 256, 4, 1400),
-    (64, 512, 1, 1400), (64, 512, 2, 1400), (64, 512, 4, 1400), (32, 512, 2, 1400), (32, 512, 4, 1400),
-    (48, 384, 4, 1400), (64, 384, 4, 1400), (64, 1024, 4, 2800), (128, 256, 4, 2800),
+    (32, 256, 4, 1400), (32, 192, 4, 1400), (32, 256, 2, 1400), (32, 384, 2, 1400), (48, 128, 4, 1400),
+    (48, 192, 4, 1400), (48, 256, 4, 1400), (48, 384, 4, 1400), (64, 128, 4, 1400), (64, 256, 4, 1400),
+    (64, 128, 1, 1400), (64, 64, 1, 2800), (64, 512, 4, 1400), (128, 256, 4, 2800),
 ]
 
 
@@ -142,7 +142,7 @@ def main():
             sec = timed(beam, 20)
             rec = GT.recall(ids, gt)
             log(f"[bench] grid beam={c[0]} seeds={c[1]} width={c[2]} visited_cap={c[3]}: recall@10={rec:.4f} {nq / sec:,.0f} q/s")
-            if rec >= 0.95 and (best is None or sec < best[0]):
+            if rec >= 0.95 and (best is None or sec < 0.98 * best[0]):   # 2 % hysteresis: stable choice
                 best = (sec, c, rec)
         if best is None:
             log("[bench] no grid point reached recall 0.95; using the widest")

@@ -68,3 +68,121 @@ def test_full_size_matches_oracle(c2_full, sel, beam, seeds, width, vcap):
     assert agree >= 0.998, agree
     if (sel, beam) == (0.1, 32):
         assert rec >= 0.95, rec
+
+
+def _full_pair(name, n_queries=None):
+    import torch
+    from paper_2604_16402_amd import binding, groundtruth as GT
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS[name]
+    X, a = W.base_vectors(cfg), W.attributes(cfg)
+    q = W.query_vectors(cfg, n_queries)
+    ix = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
+    Xd, ad = torch.from_numpy(X).to(dev), torch.from_numpy(a).to(dev)
+    ix.build_buckets(Xd, ad, cfg.buckets)
+    ora = O.Index(X, a, cfg.buckets, metric=cfg.metric)
+    table, id2slot, slot2id = ix.get_layout()
+    assert np.array_equal(table, ora.table) and np.array_equal(id2slot, ora.id2slot[:cfg.n])
+    assert np.array_equal(slot2id, ora.slot2id)
+    la, ra = W.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, metric=cfg.metric,
+                           device="cuda:0", chunk=16384)
+    ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
+    ora.load_graph(la, ra)
+    return cfg, ix, ora, X, a, q, Xd, ad, dev, GT
+
+
+def _compare(cfg, ix, ora, q, lo, hi, beam, dev):
+    import torch
+    nq = len(q)
+    ids = torch.empty((nq, 10), dtype=torch.int32, device=dev)
+    dist = torch.empty((nq, 10), dtype=torch.float32, device=dev)
+    qd, lod, hid = torch.from_numpy(q).to(dev), torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)
+    ix.search_range(qd, lod, hid, 10, beam, ids, dist)
+    torch.cuda.synchronize()
+    w_ids, w_dist, w_ctr = ora.search(q, lo, hi, 10, beam, threads=O.max_threads())
+    assert np.array_equal(dist.cpu().numpy(), w_dist)
+    assert np.array_equal(ids.cpu().numpy().view(np.uint32), w_ids)
+    assert np.array_equal(ix.get_counters(nq), w_ctr)
+    return ids, qd, lod, hid
+
+
+def test_high_dimensional_config_matches_oracle():
+    # 1M x 960 fp32, degree 48+8, 10 % ranges, beam 128 (30 lines per row, query staged in LDS)
+    cfg, ix, ora, X, a, q, Xd, ad, dev, GT = _full_pair("c3")
+    lo, hi = W.ranges(cfg, 0.1)
+    for beam, seeds, width, vcap in [(128, 0, 1, 2800), (64, 256, 4, 1400)]:
+        ix.set_param("visited_cap", vcap); ix.set_param("n_seeds", seeds); ix.set_param("search_width", width)
+        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width)
+        ids, qd, lod, hid = _compare(cfg, ix, ora, q, lo, hi, beam, dev)
+    gt = GT.exact_filtered_knn(Xd, ad, qd, lod, hid, 10, cfg.metric, chunk=256)
+    assert GT.recall(ids, gt) > 0.95
+    ix.close()
+
+
+def test_ten_million_inner_product_zipf_config_matches_oracle():
+    # 10M x 96 unit vectors, inner product, Zipf(1.1) attributes in 256 buckets (long runs of equal
+    # attributes split across buckets), range widths log-uniform 0.1 %..100 %; a 20 % sample of the
+    # 100,000 queries is compared (the oracle and the index are at full size)
+    cfg, ix, ora, X, a, q, Xd, ad, dev, GT = _full_pair("c4", n_queries=20_000)
+    lo, hi = W.ranges(cfg, None, count=20_000)
+    for beam, seeds, width, vcap in [(128, 0, 1, 2800), (128, 1024, 4, 4000)]:
+        ix.set_param("visited_cap", vcap); ix.set_param("n_seeds", seeds); ix.set_param("search_width", width)
+        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width)
+        ids, qd, lod, hid = _compare(cfg, ix, ora, q, lo, hi, beam, dev)
+    got = ids.cpu().numpy().view(np.uint32)
+    live = got != 0xFFFFFFFF
+    sel_a = a[np.where(live, got, 0)]
+    assert ((sel_a >= lo[:, None]) & (sel_a <= hi[:, None]) | ~live).all()
+    # ranges that hold at most n_seeds objects are answered exactly (float64 exhaustive answer)
+    checked = 0
+    for i in range(400):
+        ok = np.nonzero((a >= lo[i]) & (a <= hi[i]))[0]
+        if len(ok) == 0 or len(ok) > 1024:
+            continue
+        d = -(X[ok].astype(np.float64) @ q[i].astype(np.float64))
+        want = ok[np.lexsort((ok, d))[:10]]
+        mine = got[i][got[i] != 0xFFFFFFFF]
+        assert len(mine) == len(want)
+        d_mine = -(X[mine].astype(np.float64) @ q[i].astype(np.float64))
+        assert np.allclose(np.sort(d_mine), np.sort(d[np.lexsort((ok, d))[:10]]), rtol=0, atol=1e-6)   # same distances up to fp32 ties
+        checked += 1
+    assert checked > 20
+    ix.close()
+
+
+def test_dynamic_config_matches_oracle_at_full_size():
+    # 1M x 128 base, an append of 100,000 objects (the dynamic workload's round) and one of 30,000, whole
+    # index compared after each append, then a 10,000-query batch at 10 % range
+    import torch
+    from paper_2604_16402_amd import binding
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS["c5"]
+    X, a = W.base_vectors(cfg), W.attributes(cfg)
+    n_cap = cfg.n + 3 * cfg.append_batch
+    ix = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
+    ix.build_buckets(torch.from_numpy(X).to(dev), torch.from_numpy(a).to(dev), cfg.buckets, n_cap)
+    ora = O.Index(X, a, cfg.buckets, n_cap=n_cap)
+    la, ra = W.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, device="cuda:0", chunk=16384)
+    ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
+    ora.load_graph(la, ra)
+    for r in range(2):
+        nx, na = W.append_vectors(cfg, r), W.append_attributes(cfg, r)
+        if r == 1:                                   # second batch smaller: lands on tails that already hold objects
+            nx, na = nx[:30_000], na[:30_000]
+        ix.append_batch(torch.from_numpy(nx).to(dev), torch.from_numpy(na).to(dev))
+        ora.append(nx, na, threads=O.max_threads())
+        table, id2slot, slot2id = ix.get_layout()
+        assert np.array_equal(table, ora.table) and np.array_equal(id2slot, ora.id2slot[:ora.n])
+        assert np.array_equal(slot2id, ora.slot2id)
+        assert np.array_equal(ix.get_graph(), ora.A)
+    xs, at = ix.get_rows()
+    live = ora.slot2id != O.EMPTY
+    assert np.array_equal(xs[live], ora.X[live]) and np.array_equal(at[live], ora.attr[live])
+    q = W.query_vectors(cfg)
+    lo, hi = W.ranges(cfg, 0.1)
+    for beam, seeds, width, vcap in [(64, 0, 1, 2800), (32, 256, 4, 1400)]:
+        ix.set_param("visited_cap", vcap); ix.set_param("n_seeds", seeds); ix.set_param("search_width", width)
+        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width)
+        _compare(cfg, ix, ora, q, lo, hi, beam, dev)
+    assert ix.get_counters(len(q))[:, 5].sum() > 0      # appended tails of edge buckets were pre-checked by attribute
+    ix.close()
