@@ -616,3 +616,174 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
     free(req); free(rows); free(rowd); free(bucket); free(slot); free(count);
     return 0;
 }
+
+/* ============================================================ graph construction (Section 4.3)
+ * The paper builds the index in two passes: (1) inside every bucket an exact brute-force k-NN
+ * graph, pruned, united with its reverse graph by an interleaved merge whose leading K_local
+ * entries are the necessary local edges; (2) remote edges chosen from a global candidate graph,
+ * split into proximal ones (neighbouring attribute ranges) and global ones, written into the
+ * remaining slots.  The global candidate graph of pass 2 is a third-party pipeline (Algorithm 1)
+ * and is not rebuilt here.  reading (normative for this build):
+ *
+ *  1. Candidates of node u: the `pool` nearest other nodes of its bucket, ordered by
+ *     (distance, slot).
+ *  2. Pruning (Eq. 2 used as a construction rule): scan the candidates in order, keep c iff
+ *     dist(u,c) < dist(c,n) for every n kept so far; forward list F(u) = kept ones, then the
+ *     rejected ones, each in candidate order.
+ *  3. Reverse list R(v): the sources u with v among the first K_local entries of F(u), ordered by
+ *     (dist(u,v), slot of u), at most K_local of them.
+ *  4. Interleaved merge: F0, R0, F1, R1, ... over the first K_local entries of each list; empty
+ *     entries and repeats are skipped; the first K_local survivors are the local part of the row.
+ *  5. Remote part: entry j is the node nearest to u in the j-th target bucket of u's bucket b.
+ *     Targets are b+1, b-1, b+2, b-2, b+4, b-4, ... (doubling: adjacent attribute intervals
+ *     first, then longer jumps), then the remaining offsets in order of size; targets outside
+ *     [0,B) are skipped; the first K_remote distinct ones count.  Fewer than K_remote targets
+ *     leave empty entries (the paper's fallback to redundant local edges is not used, so that
+ *     the remote part never holds an edge that stays inside the bucket).
+ */
+typedef struct {
+    uint32_t img, slot;
+    float dist;
+} knn_entry;
+
+static int knn_cmp(const void *a, const void *b) {
+    const knn_entry *x = (const knn_entry *)a, *y = (const knn_entry *)b;
+    if (x->img != y->img) return x->img < y->img ? -1 : 1;
+    if (x->slot != y->slot) return x->slot < y->slot ? -1 : 1;
+    return 0;
+}
+
+/* the P nearest occupied slots of `target_bucket` to the row at `slot` (itself excluded),
+ * ordered by (distance, slot); missing entries are (EMPTY, +inf) */
+void oracle_knn(const oracle_index *ix, uint32_t slot, int32_t target_bucket, int32_t P, uint32_t *out_slots,
+                float *out_dist) {
+    const int32_t *t = ix->table + 6 * target_bucket;
+    int64_t m = t[T_NTOT], n = 0;
+    knn_entry *e = (knn_entry *)malloc(sizeof(knn_entry) * (size_t)(m > 0 ? m : 1));
+    const float *q = ix->X + (size_t)slot * ix->dim;
+    for (int64_t j = 0; j < m; ++j) {
+        uint32_t s = (uint32_t)(t[T_BASE] + j);
+        if (s == slot) continue;
+        float d = oracle_distance(q, ix->X + (size_t)s * ix->dim, ix->dim, ix->metric);
+        e[n].img = dist_image(d); e[n].slot = s; e[n].dist = d;
+        n++;
+    }
+    qsort(e, (size_t)n, sizeof(knn_entry), knn_cmp);
+    for (int j = 0; j < P; ++j) {
+        out_slots[j] = j < n ? e[j].slot : EMPTY;
+        out_dist[j] = j < n ? e[j].dist : INFINITY;
+    }
+    free(e);
+}
+
+/* target buckets of bucket b for its remote entries; returns how many (<= k_remote) */
+int oracle_remote_targets(int32_t b, int32_t B, int32_t k_remote, int32_t *out) {
+    int n = 0;
+    for (int pass = 0; pass < 2 && n < k_remote; ++pass)
+        for (int o = 1; o < B && n < k_remote; o = pass == 0 ? o * 2 : o + 1) {
+            if (pass == 1 && (o & (o - 1)) == 0) continue;   /* powers of two were taken in pass 0 */
+            for (int sgn = 1; sgn >= -1 && n < k_remote; sgn -= 2) {
+                int t = b + sgn * o;
+                if (t < 0 || t >= B) continue;
+                out[n++] = t;
+            }
+        }
+    return n;
+}
+
+/* forward list of one node: F (slots) and Fd (distances to the node), `pool` entries */
+static void forward_list(const oracle_index *ix, uint32_t u, int32_t b, int32_t pool, uint32_t *F, float *Fd) {
+    uint32_t *cs = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)pool), *kept = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)pool);
+    float *cd = (float *)malloc(sizeof(float) * (size_t)pool);
+    uint8_t *is_kept = (uint8_t *)calloc((size_t)pool, 1);
+    oracle_knn(ix, u, b, pool, cs, cd);
+    int nk = 0;
+    for (int t = 0; t < pool && cs[t] != EMPTY; ++t) {
+        int ok = 1;
+        for (int j = 0; j < nk && ok; ++j) {
+            float dcn = oracle_distance(ix->X + (size_t)cs[t] * ix->dim, ix->X + (size_t)kept[j] * ix->dim, ix->dim, ix->metric);
+            if (!(cd[t] < dcn)) ok = 0;
+        }
+        if (ok) { kept[nk++] = cs[t]; is_kept[t] = 1; }
+    }
+    int w = 0;
+    for (int pass = 1; pass >= 0; --pass)
+        for (int t = 0; t < pool; ++t)
+            if (cs[t] != EMPTY && is_kept[t] == pass) { F[w] = cs[t]; Fd[w] = cd[t]; w++; }
+    for (; w < pool; ++w) { F[w] = EMPTY; Fd[w] = INFINITY; }
+    free(cs); free(kept); free(cd); free(is_kept);
+}
+
+typedef struct {
+    uint32_t v, img, u;
+} rev_edge;
+static int rev_cmp(const void *a, const void *b) {
+    const rev_edge *x = (const rev_edge *)a, *y = (const rev_edge *)b;
+    if (x->v != y->v) return x->v < y->v ? -1 : 1;
+    if (x->img != y->img) return x->img < y->img ? -1 : 1;
+    if (x->u != y->u) return x->u < y->u ? -1 : 1;
+    return 0;
+}
+
+/* Fills ix->A (all rows) for the objects currently in the index.  F_out/R_out (may be NULL)
+ * receive the forward lists [n_cap][pool] and reverse lists [n_cap][k_local] for inspection. */
+int oracle_build_graph(oracle_index *ix, int32_t pool, uint32_t *F_out, uint32_t *R_out, int32_t threads) {
+    const int kl = ix->k_local, kr = ix->k_remote, K = kl + kr, B = ix->n_buckets;
+    if (pool < kl || kl < 0 || kr < 0 || K < 1) return 1;
+    const int64_t N = ix->n_cap;
+    uint32_t *F = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * pool);
+    float *Fd = (float *)malloc(sizeof(float) * (size_t)N * pool);
+    uint32_t *R = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * (kl > 0 ? kl : 1));
+    for (int64_t i = 0; i < N * pool; ++i) F[i] = EMPTY;
+    for (int64_t i = 0; i < N * kl; ++i) R[i] = EMPTY;
+    for (int64_t i = 0; i < N * K; ++i) ix->A[i] = EMPTY;
+    if (threads < 1) threads = 1;
+    for (int b = 0; b < B; ++b) {
+        const int32_t *t = ix->table + 6 * b;
+        int32_t tg[64];
+        int nt = oracle_remote_targets(b, B, kr, tg);
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(threads)
+#endif
+        for (int64_t j = 0; j < t[T_NTOT]; ++j) {
+            uint32_t u = (uint32_t)(t[T_BASE] + j);
+            forward_list(ix, u, b, pool, F + (size_t)u * pool, Fd + (size_t)u * pool);
+            for (int r = 0; r < nt; ++r) {
+                float d;
+                oracle_knn(ix, u, tg[r], 1, ix->A + (size_t)u * K + kl + r, &d);
+            }
+        }
+    }
+    /* reverse lists */
+    int64_t ne = 0;
+    rev_edge *E = (rev_edge *)malloc(sizeof(rev_edge) * (size_t)(N * kl > 0 ? N * kl : 1));
+    for (int64_t u = 0; u < N; ++u)
+        for (int j = 0; j < kl; ++j) {
+            uint32_t v = F[(size_t)u * pool + j];
+            if (v == EMPTY) continue;
+            E[ne].v = v; E[ne].img = dist_image(Fd[(size_t)u * pool + j]); E[ne].u = (uint32_t)u;
+            ne++;
+        }
+    qsort(E, (size_t)ne, sizeof(rev_edge), rev_cmp);
+    for (int64_t p = 0, start = 0; p < ne; ++p) {
+        if (p > 0 && E[p].v != E[p - 1].v) start = p;
+        if (p - start < kl) R[(size_t)E[p].v * kl + (p - start)] = E[p].u;
+    }
+    /* interleaved merge */
+    for (int64_t u = 0; u < N; ++u) {
+        uint32_t *row = ix->A + (size_t)u * K;
+        int w = 0;
+        for (int j = 0; j < kl && w < kl; ++j)
+            for (int side = 0; side < 2 && w < kl; ++side) {
+                uint32_t c = side == 0 ? F[(size_t)u * pool + j] : R[(size_t)u * kl + j];
+                if (c == EMPTY) continue;
+                int dup = 0;
+                for (int x = 0; x < w; ++x) if (row[x] == c) dup = 1;
+                if (!dup) row[w++] = c;
+            }
+    }
+    if (F_out) memcpy(F_out, F, sizeof(uint32_t) * (size_t)N * pool);
+    if (R_out) memcpy(R_out, R, sizeof(uint32_t) * (size_t)N * kl);
+    free(F); free(Fd); free(R); free(E);
+    return 0;
+}

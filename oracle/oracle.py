@@ -201,6 +201,40 @@ class Index:
         return ids, dist, ctr
 
 
+    # -- Section 4.3: two-pass construction (see the reading in grab_oracle.c)
+    def knn(self, slot: int, target_bucket: int, P: int):
+        """(slots[P], dist[P]) of the P nearest objects of a bucket to the row at `slot`."""
+        out_s = np.full(P, EMPTY, dtype=np.uint32)
+        out_d = np.full(P, np.inf, dtype=np.float32)
+        ix = self._c_index()
+        _load().oracle_knn(ctypes.byref(ix), ctypes.c_uint32(slot), ctypes.c_int32(target_bucket), ctypes.c_int32(P),
+                           _ptr(out_s), _ptr(out_d))
+        return out_s, out_d
+
+    def remote_targets(self, b: int, k_remote: int):
+        out = np.zeros(max(k_remote, 1), dtype=np.int32)
+        f = _load().oracle_remote_targets
+        f.restype = ctypes.c_int
+        n = f(ctypes.c_int32(b), ctypes.c_int32(self.n_buckets), ctypes.c_int32(k_remote), _ptr(out))
+        return out[:n].tolist()
+
+    def build_graph(self, k_local: int, k_remote: int, pool: Optional[int] = None, threads: int = 1,
+                    want_lists: bool = False):
+        """Builds the adjacency in place.  Returns (F, R) when want_lists."""
+        pool = pool or 2 * k_local
+        self.k_local, self.k_remote = k_local, k_remote
+        self.A = np.full((self.n_cap, k_local + k_remote), EMPTY, dtype=np.uint32)
+        F = np.empty((self.n_cap, pool), dtype=np.uint32) if want_lists else None
+        R = np.empty((self.n_cap, k_local), dtype=np.uint32) if want_lists else None
+        ix = self._c_index()
+        f = _load().oracle_build_graph
+        f.restype = ctypes.c_int
+        rc = f(ctypes.byref(ix), ctypes.c_int32(pool), _ptr(F) if want_lists else None,
+               _ptr(R) if want_lists else None, ctypes.c_int32(threads))
+        if rc:
+            raise ValueError("oracle_build_graph rejected its arguments")
+        return (F, R) if want_lists else None
+
     def _resolved_append_params(self) -> _Params:
         return self._c_params(self.params["append_beam"])
 
