@@ -97,6 +97,23 @@ grab_status grab_build_buckets(grab_index *ix, const float *vectors, const int32
 grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k_local,
                             const uint32_t *remote_adj, int32_t k_remote);
 
+/* Two-pass index construction (Section 4.3) on the objects currently in the index, replacing any
+ * graph loaded or built before.  Pass 1 (local router): for every object the `pool` nearest
+ * objects of its bucket by exact brute force, pruned by the diversity rule (Eq. 2: a candidate is
+ * kept iff it is closer to the object than to every candidate kept before it; rejected ones
+ * follow the kept ones), united with the reverse graph by an interleaved merge (forward, reverse,
+ * forward, ...) whose first k_local distinct entries become the local part of the row.  Pass 2
+ * (remote edges): entry j of the remote part is the nearest object of the j-th target bucket;
+ * targets of bucket b are b+1, b-1, b+2, b-2, b+4, b-4, ... (adjacent attribute intervals first,
+ * then doubling jumps), then the remaining offsets by size, skipping buckets that do not exist.
+ * The paper draws remote candidates from a global graph built by a third-party pipeline
+ * (Algorithm 1); here they come from exact search in the target bucket.  Distances use the same
+ * fixed fp32 summation order as the search, ties go to the smaller slot.
+ * pool = 0 means min(2 * k_local, 64).  Requires k_local >= 1, k_local + k_remote <= 64,
+ * k_local <= pool <= 64.  Errors: GRAB_EINVAL, GRAB_ESTATE (no layout), GRAB_ENOMEM, GRAB_EHIP;
+ * on error the index is left without a graph. */
+grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, int32_t pool);
+
 /* Range-constrained search (Algorithm 2) for nq queries: queries[nq][dim], closed ranges
  * lo[i] <= attribute <= hi[i], k results per query from a candidate queue of `beam` entries
  * (the paper's itopk).  out_ids[nq][k] external ids and out_dist[nq][k] distances, ascending

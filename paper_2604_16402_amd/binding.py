@@ -24,7 +24,7 @@ PARAMS = dict(search_width=P_SEARCH_WIDTH, max_iter=P_MAX_ITER, n_seeds=P_N_SEED
 EMPTY = 0xFFFFFFFF
 
 EXPORTS = ["grab_create", "grab_destroy", "grab_last_error", "grab_build_buckets", "grab_load_graph",
-           "grab_search_range", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
+           "grab_build_graph", "grab_search_range", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
            "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing"]
 
 _lib = None
@@ -59,6 +59,7 @@ def load_library() -> ctypes.CDLL:
     lib.grab_last_error.restype = ctypes.c_char_p
     lib.grab_build_buckets.argtypes = [vp, vp, vp, i64, i32, i64]
     lib.grab_load_graph.argtypes = [vp, vp, i32, vp, i32]
+    lib.grab_build_graph.argtypes = [vp, i32, i32, i32]
     lib.grab_search_range.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp]
     lib.grab_append_batch.argtypes = [vp, vp, vp, i64]
     lib.grab_set_param.argtypes = [vp, i32, ctypes.c_double]
@@ -145,6 +146,9 @@ class Index:
             raise ValueError("adjacency must have one row per object in the index")
         self._check(self._lib.grab_load_graph(self._h, _ptr(local_adj, np.uint32, n * kl) if kl else None, kl,
                                               _ptr(remote_adj, np.uint32, n * kr) if kr else None, kr))
+
+    def build_graph(self, k_local: int, k_remote: int, pool: int = 0):
+        self._check(self._lib.grab_build_graph(self._h, k_local, k_remote, pool))
 
     def search_range(self, queries, lo, hi, k: int, beam: int, out_ids=None, out_dist=None):
         """Returns (ids[nq,k], dist[nq,k]); outputs are numpy unless device tensors are passed in."""

@@ -230,6 +230,27 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
     return GRAB_OK;
 }
 
+grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, int32_t pool) {
+    if (!ix) return GRAB_EINVAL;
+    if (!ix->X) return grab_fail(ix, GRAB_ESTATE, "build_buckets first");
+    if (k_local < 1 || k_remote < 0 || k_local + k_remote > 64) return grab_fail(ix, GRAB_EINVAL, "need k_local >= 1 and k_local + k_remote <= 64");
+    if (pool == 0) pool = 2 * k_local < 64 ? 2 * k_local : 64;
+    if (pool < k_local || pool > 64) return grab_fail(ix, GRAB_EINVAL, "pool must be k_local..64");
+    GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
+    ix->has_graph = false;
+    (void)hipFree(ix->A);
+    ix->A = nullptr;
+    GRAB_HIP(ix, hipMalloc((void **)&ix->A, (size_t)ix->n_slots * (k_local + k_remote) * 4));
+    grab_status st = grab_build_graph_device(ix, k_local, k_remote, pool);
+    if (st != GRAB_OK) {
+        (void)hipFree(ix->A);
+        ix->A = nullptr;
+        return st;
+    }
+    ix->kl = k_local; ix->kr = k_remote; ix->has_graph = true;
+    return GRAB_OK;
+}
+
 static grab_status resolve_search(grab_index *ix, int32_t k, int32_t beam, SearchLaunch &s) {
     const SearchParams &p = ix->prm;
     if (k < 1 || beam < k || beam > GRAB_MAX_BEAM) return grab_fail(ix, GRAB_EINVAL, "need 1 <= k <= beam <= %d", GRAB_MAX_BEAM);

@@ -121,5 +121,7 @@ grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s);
 grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s);
 // append: the whole insertion for m objects already on the device; `proto` carries the search
 // parameters resolved for beam = append_beam
+// construction: fills ix->A (already allocated for kl+kr entries per slot)
+grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int32_t pool);
 grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_t *d_attrs, int64_t m,
                                const SearchLaunch &proto);

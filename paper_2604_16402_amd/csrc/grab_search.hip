@@ -207,38 +207,6 @@ __device__ void merge_queue(u64 *Q, int QP, const u64 *C, int CP, int beam, int 
     }
 }
 
-// ---- a 64-entry queue held one key per lane, sorted and merged with lane exchanges ----------
-__device__ __forceinline__ u64 shfl64(u64 k, int src) {
-    return ((u64)(uint32_t)__shfl((int)(k >> 32), src) << 32) | (u64)(uint32_t)__shfl((int)(k & 0xFFFFFFFFull), src);
-}
-__device__ __forceinline__ u64 shfl_xor64(u64 k, int m) {
-    return ((u64)(uint32_t)__shfl_xor((int)(k >> 32), m) << 32) | (u64)(uint32_t)__shfl_xor((int)(k & 0xFFFFFFFFull), m);
-}
-// ascending bitonic sort of the keys of lanes [0,P); lanes beyond hold SENT and stay put
-__device__ __forceinline__ u64 sort_lanes(u64 key, int P, int lane) {
-    for (int k = 2; k <= P; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            u64 o = shfl_xor64(key, j);
-            bool take_min = ((lane & j) == 0) == ((lane & k) == 0);
-            bool less = key < o;
-            key = (less == take_min) ? key : o;
-        }
-    return key;
-}
-// queue (sorted, one key per lane) <- the 64 smallest of queue and ck (sorted), cut to beam
-__device__ __forceinline__ u64 merge_lanes(u64 qk, u64 ck, int beam, int lane) {
-    u64 r = shfl64(ck, 63 - lane);
-    u64 m = qk < r ? qk : r;
-#pragma unroll
-    for (int j = 32; j > 0; j >>= 1) {
-        u64 o = shfl_xor64(m, j);
-        bool take_min = (lane & j) == 0;
-        bool less = m < o;
-        m = (less == take_min) ? m : o;
-    }
-    return lane < beam ? m : SENT;
-}
-
 // One query per wavefront.  QR: the queue (beam <= 64) lives in registers, one key per lane,
 // and new keys are sorted/merged with lane exchanges in groups of at most 64; otherwise the
 // queue lives in LDS and is merged there.  In both variants a new key is dropped at once when
