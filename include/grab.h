@@ -92,7 +92,7 @@ grab_status grab_build_buckets(grab_index *ix, const float *vectors, const int32
  * (0xFFFFFFFF = no edge), one row per object currently in the index.  Ids are translated
  * to slots and each row is stored as [local | remote].  Checked on the device: ids < n,
  * local edges stay inside the node's bucket, remote edges leave it; a violation gives
- * GRAB_EINVAL and leaves the index without a graph.  k_local + k_remote must be 1..64;
+ * GRAB_EINVAL and leaves the index without a graph.  k_local + k_remote must be 1..128;
  * k_remote may be 0 (remote_adj then unused).  GRAB_ESTATE before grab_build_buckets. */
 grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k_local,
                             const uint32_t *remote_adj, int32_t k_remote);
@@ -109,7 +109,7 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
  * The paper draws remote candidates from a global graph built by a third-party pipeline
  * (Algorithm 1); here they come from exact search in the target bucket.  Distances use the same
  * fixed fp32 summation order as the search, ties go to the smaller slot.
- * pool = 0 means min(2 * k_local, 64).  Requires k_local >= 1, k_local + k_remote <= 64,
+ * pool = 0 means min(2 * k_local, 64).  Requires 1 <= k_local <= 64, 0 <= k_remote <= 64,
  * k_local <= pool <= 64.  Errors: GRAB_EINVAL, GRAB_ESTATE (no layout), GRAB_ENOMEM, GRAB_EHIP;
  * on error the index is left without a graph. */
 grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, int32_t pool);
@@ -131,6 +131,7 @@ grab_status grab_search_range(grab_index *ix, const float *queries, const int32_
  * globally, selects forward edges by the diversity rule (Eq. 2) and rewires reverse edges
  * with the freshness bias (Eq. 3).  New external ids are n_prev .. n_prev+m-1 in input
  * order.  GRAB_EFULL if any bucket would overflow its slab: nothing is written then.
+ * Needs k_local <= 64 and k_remote <= 64.
  * Errors: GRAB_EINVAL, GRAB_ESTATE (no graph), GRAB_EFULL, GRAB_ENOMEM, GRAB_EHIP. */
 grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_t *attrs, int64_t m);
 

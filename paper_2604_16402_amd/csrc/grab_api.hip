@@ -187,8 +187,8 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
                             int32_t k_remote) {
     if (!ix) return GRAB_EINVAL;
     if (!ix->X) return grab_fail(ix, GRAB_ESTATE, "build_buckets first");
-    if (k_local < 0 || k_remote < 0 || k_local + k_remote < 1 || k_local + k_remote > 64)
-        return grab_fail(ix, GRAB_EINVAL, "k_local + k_remote must be 1..64");
+    if (k_local < 0 || k_remote < 0 || k_local + k_remote < 1 || k_local + k_remote > 128)
+        return grab_fail(ix, GRAB_EINVAL, "k_local + k_remote must be 1..128");
     if ((k_local > 0 && !local_adj) || (k_remote > 0 && !remote_adj)) return grab_fail(ix, GRAB_EINVAL, "null adjacency");
     GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
     ix->has_graph = false;
@@ -233,7 +233,7 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
 grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, int32_t pool) {
     if (!ix) return GRAB_EINVAL;
     if (!ix->X) return grab_fail(ix, GRAB_ESTATE, "build_buckets first");
-    if (k_local < 1 || k_remote < 0 || k_local + k_remote > 64) return grab_fail(ix, GRAB_EINVAL, "need k_local >= 1 and k_local + k_remote <= 64");
+    if (k_local < 1 || k_local > 64 || k_remote < 0 || k_remote > 64) return grab_fail(ix, GRAB_EINVAL, "need 1 <= k_local <= 64 and 0 <= k_remote <= 64");
     if (pool == 0) pool = 2 * k_local < 64 ? 2 * k_local : 64;
     if (pool < k_local || pool > 64) return grab_fail(ix, GRAB_EINVAL, "pool must be k_local..64");
     GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
@@ -406,6 +406,7 @@ grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_
     if (m < 0) return grab_fail(ix, GRAB_EINVAL, "bad batch size");
     if (m == 0) return GRAB_OK;
     if (!vectors || !attrs) return grab_fail(ix, GRAB_EINVAL, "null argument");
+    if (ix->kl > 64 || ix->kr > 64) return grab_fail(ix, GRAB_EINVAL, "append needs k_local <= 64 and k_remote <= 64");
     if (ix->n + m > ix->n_slots)
         return grab_fail(ix, GRAB_EFULL, "%lld objects + %lld new exceed the %lld slots of the index", (long long)ix->n,
                          (long long)m, (long long)ix->n_slots);

@@ -175,6 +175,8 @@ def remote_targets(b: int, n_buckets: int, k_remote: int) -> list:
     (+-1, +-2: smooth transitions to adjacent attribute intervals), then doubling
     offsets (+-4, +-8, ...: long jumps), then whatever is left, skipping offsets that
     fall outside ``[0, n_buckets)``."""
+    if k_remote <= 0:
+        return []
     prefs = []
     o = 1
     while o < n_buckets:

@@ -69,7 +69,7 @@ def test_build_graph_rejects_bad_arguments():
         ix.build_graph(8, 2, 16)
     assert e.value.status == B.ESTATE
     ix.build_buckets(np.zeros((50, 32), np.float32), np.arange(50, dtype=np.int32), 2)
-    for kl, kr, pool in [(0, 2, 8), (40, 30, 64), (8, 2, 4), (8, 2, 100)]:
+    for kl, kr, pool in [(0, 2, 8), (70, 2, 64), (8, 70, 16), (8, 2, 4), (8, 2, 100)]:
         with pytest.raises(B.GrabError) as e:
             ix.build_graph(kl, kr, pool)
         assert e.value.status == B.EINVAL

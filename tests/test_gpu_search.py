@@ -227,3 +227,30 @@ def test_search_twice_gives_identical_bytes(c1_small, torch_dev):
     b = _search_gpu(ix, torch_dev, c["queries"], c["lo"], c["hi"], 10, 64)
     assert all(np.array_equal(x, y) for x, y in zip(a, b))
     ix.close()
+
+
+@pytest.mark.parametrize("dim,kl,kr,beam,width,seeds,vcap", [
+    (128, 64, 64, 512, 4, 512, 6000),     # degree 128 and a 512-entry queue (the paper's scalability setting)
+    (2048, 24, 8, 128, 4, 128, 2800),     # 2048-dimensional rows (64 lines per row)
+    (128, 100, 28, 256, 1, 0, 2800),      # unbalanced degree split, queue of 256
+])
+def test_wide_parameter_surface(torch_dev, dim, kl, kr, beam, width, seeds, vcap):
+    n, B = (3000, 4) if dim <= 128 else (1200, 3)
+    cfg = W.Config("wide", n, dim, 8, 0.4, n, B, min(kl, 64), min(kr, 64), 200, (0.3,), seed=dim + kl)
+    X, a, q = W.base_vectors(cfg), W.attributes(cfg), W.query_vectors(cfg)
+    ora = O.Index(X, a, B)
+    la, ra = W.build_graph(X, ora.bucket_of_ids(), B, min(kl, 64), kr, pool=min(2 * kl, 200))
+    if kl > 64:      # pad the local part with further in-bucket neighbours to reach the requested width
+        la2, _ = W.build_graph(X, ora.bucket_of_ids(), B, kl, 0, pool=kl + 20)
+        la = la2
+    ora.load_graph(la, ra)
+    c = dict(cfg=cfg, X=X, attrs=a, local=la, remote=ra)
+    ix = _gpu_index(c, torch_dev)
+    for name, val in [("visited_cap", vcap), ("n_seeds", seeds), ("search_width", width)]:
+        ix.set_param(name, val)
+    ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width)
+    lo, hi = W.ranges(cfg, 0.3)
+    ids, dist, ctr = _search_gpu(ix, torch_dev, q, lo, hi, 10, beam)
+    w = ora.search(q, lo, hi, 10, beam)
+    assert np.array_equal(dist, w[1]) and np.array_equal(ids, w[0]) and np.array_equal(ctr, w[2])
+    ix.close()
