@@ -168,50 +168,61 @@ __device__ __forceinline__ bool visited_insert(uint32_t *tab, uint32_t mask, int
     return false;
 }
 
-__device__ __forceinline__ void cmpx(u64 *a, int i, int l, bool up) {
-    u64 x = a[i], y = a[l];
-    if ((x > y) == up) { a[i] = y; a[l] = x; }
-}
+// The candidate queue: M keys per lane in registers, position p = 64*r + lane of register r,
+// sorted ascending over p.  Strides of 64 and more are compare-exchanges between registers of
+// the same lane; smaller strides are lane exchanges applied to every register.
+template <int M>
+struct LaneQueue {
+    u64 k[M];
 
-// ascending bitonic sort of a[0..n), n a power of two >= 2, by one wavefront
-__device__ void bitonic_sort(u64 *a, int n, int lane) {
-    for (int k = 2; k <= n; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int t = lane; t < (n >> 1); t += 64) {
-                int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-                cmpx(a, i, i | j, (i & k) == 0);
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int r = 0; r < M; ++r) k[r] = SENT;
+    }
+    // queue <- the 64*M smallest of queue and ck (sorted over the lanes, SENT-padded), cut to beam:
+    // min against the reversed newcomers turns the sorted queue into a bitonic sequence that holds
+    // exactly the survivors; a bitonic merge sorts it again
+    __device__ __forceinline__ void merge(u64 ck, int beam, int lane) {
+        const u64 rv = shfl64(ck, 63 - lane);
+        k[M - 1] = k[M - 1] < rv ? k[M - 1] : rv;
+#pragma unroll
+        for (int s = M / 2; s >= 1; s >>= 1)
+#pragma unroll
+            for (int r = 0; r < M; ++r)
+                if ((r & s) == 0) {
+                    const u64 x = k[r], y = k[r + s];
+                    k[r] = x < y ? x : y;
+                    k[r + s] = x < y ? y : x;
+                }
+#pragma unroll
+        for (int j = 32; j > 0; j >>= 1) {
+            const bool take_min = (lane & j) == 0;
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                const u64 o = shfl_xor64(k[r], j);
+                const bool less = k[r] < o;
+                k[r] = (less == take_min) ? k[r] : o;
             }
-            __syncthreads();
         }
-}
+#pragma unroll
+        for (int r = 0; r < M; ++r)
+            if (64 * r + lane >= beam) k[r] = SENT;
+    }
+    // key at position p (same p in every lane)
+    __device__ __forceinline__ u64 at(int p) const {
+        u64 t = SENT;
+#pragma unroll
+        for (int r = 0; r < M; ++r)
+            if ((p >> 6) == r) t = k[r];
+        return shfl64(t, p & 63);
+    }
+};
 
-// Q (sorted, QP entries) <- the QP smallest of Q and C (sorted, CP entries), sorted; then cut to beam
-__device__ void merge_queue(u64 *Q, int QP, const u64 *C, int CP, int beam, int lane) {
-    for (int i = lane; i < QP; i += 64) {
-        int r = QP - 1 - i;
-        u64 c = r < CP ? C[r] : SENT;
-        u64 q = Q[i];
-        Q[i] = q < c ? q : c;  // min against the reversed other list: bitonic, holds the QP smallest
-    }
-    __syncthreads();
-    for (int j = QP >> 1; j > 0; j >>= 1) {
-        for (int t = lane; t < (QP >> 1); t += 64) {
-            int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));
-            cmpx(Q, i, i | j, true);
-        }
-        __syncthreads();
-    }
-    if (beam < QP) {
-        for (int i = beam + lane; i < QP; i += 64) Q[i] = SENT;
-        __syncthreads();
-    }
-}
-
-// One query per wavefront.  QR: the queue (beam <= 64) lives in registers, one key per lane,
-// and new keys are sorted/merged with lane exchanges in groups of at most 64; otherwise the
-// queue lives in LDS and is merged there.  In both variants a new key is dropped at once when
-// it is not smaller than the current worst key of a full queue: it could never enter.
-template <int NCH, bool QR>
+// One query per wavefront; the queue of up to 64*M keys stays in registers for the whole search.
+// New keys wait in a 64-entry LDS buffer, are sorted with a lane-exchange bitonic network sized
+// to their number and merged into the queue.  A new key is dropped at once when it is not
+// smaller than the worst key of a full queue: it could never enter.
+template <int NCH, int M>
 __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int D = NCH * 32;
@@ -219,10 +230,8 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     const int lane = threadIdx.x;
     const int64_t q = blockIdx.x;
     const int H = 1 << a.hbits;
-    const int ccap = QR ? 64 : a.maxc;
-    u64 *Q = reinterpret_cast<u64 *>(smem);                 // LDS queue (unused when QR)
-    u64 *C = Q + (QR ? 0 : a.QP);                           // keys waiting to be merged
-    uint32_t *hash = reinterpret_cast<uint32_t *>(C + ccap);
+    u64 *C = reinterpret_cast<u64 *>(smem);                 // keys waiting to be merged
+    uint32_t *hash = reinterpret_cast<uint32_t *>(C + 64);
     uint32_t *L = hash + H;                                 // slots to evaluate
     uint32_t *par = L + a.maxc;                             // parent slots
     float *qlds = reinterpret_cast<float *>(par + 16);
@@ -235,14 +244,13 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
     load_query<NCH>(a.queries + q * D, qreg, qlds, lane);
     for (int i = lane; i < H / 4; i += 64) reinterpret_cast<uint4 *>(hash)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
-    if constexpr (!QR)
-        for (int i = lane; i < a.QP; i += 64) Q[i] = SENT;
     __syncthreads();
 
     const uint32_t hmask = (uint32_t)H - 1;
     const int hshift = 32 - a.hbits;
     const u64 lt_mask = (1ull << lane) - 1ull;
-    u64 qk = SENT;    // QR: this lane's queue entry
+    LaneQueue<M> Q;
+    Q.clear();
     u64 thr = SENT;   // worst key of a full queue, SENT while it has room
     int cnt = 0;      // keys waiting in C
 
@@ -251,18 +259,10 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
         if (cnt == 0) return;
         int P = 2;
         while (P < cnt) P <<= 1;
-        if constexpr (QR) {
-            u64 ck = lane < cnt ? C[lane] : SENT;
-            ck = sort_lanes(ck, P, lane);
-            qk = merge_lanes(qk, ck, a.beam, lane);
-            thr = shfl64(qk, a.beam - 1);
-        } else {
-            for (int i = cnt + lane; i < P; i += 64) C[i] = SENT;
-            __syncthreads();
-            bitonic_sort(C, P, lane);
-            merge_queue(Q, a.QP, C, P, a.beam, lane);
-            thr = Q[a.beam - 1];
-        }
+        u64 ck = lane < cnt ? C[lane] : SENT;
+        ck = sort_lanes(ck, P, lane);
+        Q.merge(ck, a.beam, lane);
+        thr = Q.at(a.beam - 1);
         cnt = 0;
         __syncthreads();
     };
@@ -270,7 +270,7 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     auto evaluate = [&](int n) {
         const int sub = lane & 7;
         for (int base = 0; base < n; base += 8 * R) {
-            if (QR && cnt + 8 * R > 64) flush();
+            if (cnt + 8 * R > 64) flush();
             float s[R];
             uint32_t v[R];
             bool act[R];
@@ -317,36 +317,25 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
             if ((int)c_iters == a.max_iter) { c_stop = 1; break; }
             // PopUnvisited: first `width` queue entries not yet expanded
             int np = 0;
-            u64 chosen = 0;  // QR: lanes picked as parents
-            if constexpr (QR) {
-                u64 m = __ballot(qk != SENT && !(qk & 1ull));
+            u64 chosen[M];
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                chosen[r] = 0;
+                u64 m = __ballot(Q.k[r] != SENT && !(Q.k[r] & 1ull));
                 while (m && np < a.width) {
                     int b = __ffsll((long long)m) - 1;
                     m &= m - 1;
-                    chosen |= 1ull << b;
-                    if (lane == b) par[np] = key_slot(qk);
+                    chosen[r] |= 1ull << b;
+                    if (lane == b) par[np] = key_slot(Q.k[r]);
                     ++np;
-                }
-            } else {
-                for (int c = 0; c < a.QP && np < a.width; c += 64) {
-                    u64 key = Q[c + lane];
-                    u64 m = __ballot(key != SENT && !(key & 1ull));
-                    while (m && np < a.width) {
-                        int b = __ffsll((long long)m) - 1;
-                        m &= m - 1;
-                        if (lane == b) { par[np] = key_slot(key); par[8 + np] = (uint32_t)(c + lane); }
-                        ++np;
-                    }
                 }
             }
             if (np == 0) break;
             if ((int)c_vis + np * a.K > a.visited_cap) { c_stop = 2; break; }
             __syncthreads();
-            if constexpr (QR) {
-                if ((chosen >> lane) & 1ull) qk |= 1ull;
-            } else {
-                if (lane < np) Q[par[8 + lane]] |= 1ull;
-            }
+#pragma unroll
+            for (int r = 0; r < M; ++r)
+                if ((chosen[r] >> lane) & 1ull) Q.k[r] |= 1ull;
             c_iters += 1; c_par += np;
             // GatherNeighbors + pre-check + visited test, all parents' rows at once
             const int total = np * a.K;
@@ -375,18 +364,21 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
         }
     }
     // ---- Top-k from the queue
-    for (int j = lane; j < a.k; j += 64) {
-        u64 key;
-        if constexpr (QR) key = qk; else key = Q[j];
-        uint32_t id = GRAB_EMPTY;
-        float d = __builtin_inff();
-        if (key != SENT) {
-            uint32_t slot = key_slot(key);
-            id = a.out_slots ? slot : a.slot2id[slot];
-            d = image_dist((uint32_t)(key >> 32));
+#pragma unroll
+    for (int r = 0; r < M; ++r) {
+        const int j = 64 * r + lane;
+        if (j < a.k) {
+            const u64 key = Q.k[r];
+            uint32_t id = GRAB_EMPTY;
+            float d = __builtin_inff();
+            if (key != SENT) {
+                uint32_t slot = key_slot(key);
+                id = a.out_slots ? slot : a.slot2id[slot];
+                d = image_dist((uint32_t)(key >> 32));
+            }
+            a.out_ids[q * a.k + j] = id;
+            a.out_dist[q * a.k + j] = d;
         }
-        a.out_ids[q * a.k + j] = id;
-        a.out_dist[q * a.k + j] = d;
     }
     if (lane < 8) {
         uint32_t val = lane == 0 ? c_iters : lane == 1 ? c_par : lane == 2 ? c_evals : lane == 3 ? c_seed
@@ -395,21 +387,28 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     }
 }
 
-template <int NCH>
-grab_status launch_beam_t(grab_index *ix, const BeamArgs &a, int64_t nq, int H) {
-    const bool qr = a.QP == 64;
-    size_t lds = (size_t)(qr ? 64 : a.QP + a.maxc) * 8 + (size_t)H * 4 + (size_t)a.maxc * 4 + 16 * 4;
-    if (!EvalShape<NCH>::QREG) lds += (size_t)ix->dim * 4;
-    const void *fn = qr ? reinterpret_cast<const void *>(&k_beam_search<NCH, true>)
-                        : reinterpret_cast<const void *>(&k_beam_search<NCH, false>);
+template <int NCH, int M>
+grab_status launch_beam_tm(grab_index *ix, const BeamArgs &a, int64_t nq, size_t lds) {
     if (lds > 64 * 1024) {
-        hipError_t e = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&k_beam_search<NCH, M>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e != hipSuccess) return grab_fail(ix, GRAB_EHIP, "LDS request of %zu bytes refused: %s", lds, hipGetErrorString(e));
     }
-    if (qr) k_beam_search<NCH, true><<<dim3((unsigned)nq), dim3(64), lds, ix->stream>>>(a);
-    else k_beam_search<NCH, false><<<dim3((unsigned)nq), dim3(64), lds, ix->stream>>>(a);
+    k_beam_search<NCH, M><<<dim3((unsigned)nq), dim3(64), lds, ix->stream>>>(a);
     GRAB_HIP(ix, hipGetLastError());
     return GRAB_OK;
+}
+
+template <int NCH>
+grab_status launch_beam_t(grab_index *ix, const BeamArgs &a, int64_t nq, int H) {
+    size_t lds = 64 * 8 + (size_t)H * 4 + (size_t)a.maxc * 4 + 16 * 4;
+    if (!EvalShape<NCH>::QREG) lds += (size_t)ix->dim * 4;
+    switch (a.QP / 64) {
+        case 1: return launch_beam_tm<NCH, 1>(ix, a, nq, lds);
+        case 2: return launch_beam_tm<NCH, 2>(ix, a, nq, lds);
+        case 4: return launch_beam_tm<NCH, 4>(ix, a, nq, lds);
+        default: return launch_beam_tm<NCH, 8>(ix, a, nq, lds);
+    }
 }
 
 inline int pow2_at_least(int x, int floor_) {
