@@ -31,8 +31,10 @@ METRIC = "filtered queries/sec at recall@10>=0.95 (1M x 128 fp32, 10% range), % 
 GRID = [
     (32, 256, 4, 1400), (32, 192, 4, 1400), (32, 256, 2, 1400), (32, 384, 2, 1400), (48, 128, 4, 1400),
     (48, 192, 4, 1400), (48, 256, 4, 1400), (48, 384, 4, 1400), (64, 128, 4, 1400), (64, 256, 4, 1400),
-    (64, 128, 1, 1400), (64, 64, 1, 2800), (64, 512, 4, 1400), (128, 256, 4, 2800),
-    (128, 1024, 4, 4000), (256, 2048, 4, 8000),
+    (64, 128, 1, 1400), (64, 64, 1, 2800), (64, 512, 4, 1400), (64, 128, 2, 2800), (64, 256, 4, 4000),
+    (96, 128, 2, 2800), (96, 256, 4, 4000), (128, 128, 2, 4000), (128, 256, 4, 2800), (128, 512, 4, 4000),
+    (64, 1024, 4, 2000), (96, 1024, 4, 2400), (128, 768, 4, 2400), (128, 1024, 4, 2400), (128, 1024, 4, 4000),
+    (256, 2048, 4, 8000),
 ]
 
 
@@ -208,7 +210,7 @@ def main():
                 traffic = tj.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
-    roofline = {"bound": "hbm", "kernel": "k_beam_search<%d,%s>" % (cfg.dim // 32, "true" if chosen[0] <= 64 else "false"), "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
+    roofline = {"bound": "hbm", "kernel": "k_beam_search<%d,%d>" % (cfg.dim // 32, 1 if chosen[0] <= 64 else 2 if chosen[0] <= 128 else 4 if chosen[0] <= 256 else 8), "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": bytes_per_launch, "avg_kernel_ms": round(avg_beam_ms, 4),
                 "select_kernel_ms": round(float(np.mean(select_ms)), 4),
@@ -245,8 +247,9 @@ def main():
         "value": round(qps, 1), "unit": "queries/s", "n_gpus": 1, "steps": args.steps,
         "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32, {cfg.components}-component Gaussian mixture, "
-                               f"uniform int attribute, {cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, "
+        "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32, {cfg.components}-component Gaussian mixture"
+                               f"{' (unit vectors, inner product)' if cfg.metric else ''}, "
+                               f"{'Zipf(1.1)' if cfg.attr_dist == 'zipf' else 'uniform'} int attribute, {cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, "
                                f"{nq} queries, {(format(args.selectivity, '.0%') if args.selectivity > 0 else 'log-uniform 0.1%..100%')} range, k={k}",
                    "beam": chosen[0], "n_seeds": chosen[1], "search_width": chosen[2], "visited_cap": max(chosen[3], chosen[1]),
                    "recall_at_10": round(chosen_recall, 4)},

@@ -137,7 +137,7 @@ struct BeamArgs {
     uint32_t *counters;
     uint32_t *out_ids;
     float *out_dist;
-    int32_t K, k, beam, QP, width, max_iter, S, visited_cap, hbits, maxc, metric, out_slots;
+    int32_t K, k, beam, QP, width, max_iter, S, visited_cap, hsize, maxc, metric, out_slots;
 };
 
 // scalar pre-check (Algorithm 2, the range test ahead of ComputeDistance) from slot
@@ -156,14 +156,15 @@ __device__ __forceinline__ bool precheck(const QueryPlan &p, uint32_t v, const i
     return false;
 }
 
-// exact visited set: open addressing, linear probing, one LDS compare-and-swap per probe
-__device__ __forceinline__ bool visited_insert(uint32_t *tab, uint32_t mask, int shift, uint32_t v) {
-    uint32_t h = (v * 0x9E3779B1u) >> shift;
-    for (uint32_t probe = 0; probe <= mask; ++probe) {
+// exact visited set: open addressing over H words (any multiple of 64, at most 80 % full when the
+// capacity rule stops the search), linear probing, one LDS compare-and-swap per probe
+__device__ __forceinline__ bool visited_insert(uint32_t *tab, uint32_t H, uint32_t v) {
+    uint32_t h = (uint32_t)(((u64)(v * 0x9E3779B1u) * (u64)H) >> 32);
+    for (uint32_t probe = 0; probe < H; ++probe) {
         uint32_t old = atomicCAS(&tab[h], GRAB_EMPTY, v);
         if (old == GRAB_EMPTY) return true;
         if (old == v) return false;
-        h = (h + 1) & mask;
+        h = h + 1 == H ? 0u : h + 1;
     }
     return false;
 }
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     constexpr int R = EvalShape<NCH>::R;
     const int lane = threadIdx.x;
     const int64_t q = blockIdx.x;
-    const int H = 1 << a.hbits;
+    const int H = a.hsize;
     u64 *C = reinterpret_cast<u64 *>(smem);                 // keys waiting to be merged
     uint32_t *hash = reinterpret_cast<uint32_t *>(C + 64);
     uint32_t *L = hash + H;                                 // slots to evaluate
@@ -246,8 +247,6 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     for (int i = lane; i < H / 4; i += 64) reinterpret_cast<uint4 *>(hash)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
     __syncthreads();
 
-    const uint32_t hmask = (uint32_t)H - 1;
-    const int hshift = 32 - a.hbits;
     const u64 lt_mask = (1ull << lane) - 1ull;
     LaneQueue<M> Q;
     Q.clear();
@@ -302,7 +301,7 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
                 bool tail = false, ok = false;
                 if (v != GRAB_EMPTY) ok = precheck(p, v, a.attr, lo, hi, tail);
                 c_tail += __popcll(__ballot(tail));
-                bool fresh = ok && visited_insert(hash, hmask, hshift, v);
+                bool fresh = ok && visited_insert(hash, (uint32_t)H, v);
                 u64 m = __ballot(fresh);
                 if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
                 n_c += __popcll(m);
@@ -353,7 +352,7 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
                 if (live) ok = precheck(p, v, a.attr, lo, hi, tail);
                 c_rej += __popcll(__ballot(live && !ok));
                 c_tail += __popcll(__ballot(tail));
-                bool fresh = ok && visited_insert(hash, hmask, hshift, v);
+                bool fresh = ok && visited_insert(hash, (uint32_t)H, v);
                 u64 m = __ballot(fresh);
                 if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
                 n_c += __popcll(m);
@@ -435,10 +434,11 @@ grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s) {
     a.counters = s.counters; a.out_ids = s.out_ids; a.out_dist = s.out_dist;
     a.K = ix->kl + ix->kr; a.k = s.k; a.beam = s.beam; a.QP = pow2_at_least(s.beam, 64);
     a.width = s.width; a.max_iter = s.max_iter; a.S = s.n_seeds; a.visited_cap = s.visited_cap;
-    // table at most 3/4 full when the capacity rule stops the search
-    int H = pow2_at_least((int)(((int64_t)s.visited_cap * 4 + 2) / 3) + 1, 256);
-    a.hbits = 0;
-    while ((1 << a.hbits) < H) ++a.hbits;
+    // visited table: the power of two above 4/3 of the capacity when that wastes little LDS (short
+    // probe runs), else 5/4 of the capacity rounded up to 64 words (80 % full at the very worst)
+    int H = pow2_at_least((int)(((int64_t)s.visited_cap * 4 + 2) / 3) + 1, 64);
+    if ((int64_t)H * 5 > (int64_t)s.visited_cap * 8) H = (int)((((int64_t)s.visited_cap * 5 + 3) / 4 + 63) / 64 * 64);
+    a.hsize = H;
     a.maxc = pow2_at_least(s.width * a.K, 64);
     a.metric = ix->metric; a.out_slots = s.out_slots ? 1 : 0;
     const int nch = ix->dim / 32;
