@@ -53,6 +53,8 @@ def main():
     ap.add_argument("--scale", type=int, default=0, help="shrink the workload to this many base vectors (debug)")
     ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap: skip the grid")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--alpha", type=float, default=0.6, help="dynamic workload: freshness bias of Eq. 3")
+    ap.add_argument("--append-beam", type=int, default=64, help="dynamic workload: queue size of append's searches")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy five times (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -269,6 +271,8 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
     k = cfg.k
     beam, S, w, vc = (int(x) for x in (args.config or "32,512,4,1400").split(","))
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
+    ix.set_param("alpha", args.alpha)
+    ix.set_param("append_beam", args.append_beam)
     rounds = []
     allX, alla = Xd, ad
     for r in range(cfg.append_rounds):
@@ -322,7 +326,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
            "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32 growing by {cfg.append_rounds} x {cfg.append_batch}, "
                                   f"{cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, 10000 queries per round, "
                                   f"{args.selectivity:.0%} range, k={k}",
-                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": 64, "alpha": 0.6},
+                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "alpha": args.alpha},
            "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
            "bulk_rebuilt_reference_final": rebuilt, "build": build}
     ix.close()
