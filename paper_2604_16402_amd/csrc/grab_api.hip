@@ -146,6 +146,7 @@ grab_status grab_build_buckets(grab_index *ix, const float *vectors, const int32
     if (!vectors || !attrs) return grab_fail(ix, GRAB_EINVAL, "null input");
     if (n_buckets < 1 || n_buckets > GRAB_MAX_BUCKETS) return grab_fail(ix, GRAB_EINVAL, "n_buckets must be 1..%d", GRAB_MAX_BUCKETS);
     if (n < n_buckets || n_cap < n || n_cap >= (1ll << 31)) return grab_fail(ix, GRAB_EINVAL, "need n_buckets <= n <= n_cap < 2^31");
+    if (n_cap * (int64_t)(ix->dim / 4) > (1ll << 38)) return grab_fail(ix, GRAB_EINVAL, "n_cap * dim exceeds 2^40 elements");
     GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
     drop_layout(ix);
     const int64_t slack = (n_cap - n) / n_buckets;
