@@ -54,7 +54,9 @@ def main():
     ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap: skip the grid")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--alpha", type=float, default=0.6, help="dynamic workload: freshness bias of Eq. 3")
-    ap.add_argument("--append-beam", type=int, default=64, help="dynamic workload: queue size of append's searches")
+    ap.add_argument("--append-beam", type=int, default=128, help="dynamic workload: queue size of append's searches")
+    ap.add_argument("--append-seeds", type=int, default=256, help="dynamic workload: seeds of append's candidate search")
+    ap.add_argument("--append-width", type=int, default=2, help="dynamic workload: search width of append's candidate search")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy five times (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -278,8 +280,8 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
     for r in range(cfg.append_rounds):
         nx = torch.from_numpy(W.append_vectors(cfg, r)).to(dev)
         na = torch.from_numpy(W.append_attributes(cfg, r)).to(dev)
-        # append's own searches use the library defaults (beam 64, 64 seeds, width 1)
-        ix.set_param("visited_cap", 2800); ix.set_param("n_seeds", 0); ix.set_param("search_width", 1)
+        # append's candidate search: beam append_beam, its own seeds and width
+        ix.set_param("visited_cap", 2800); ix.set_param("n_seeds", args.append_seeds); ix.set_param("search_width", args.append_width)
         torch.cuda.synchronize()
         t = time.perf_counter()
         ix.append_batch(nx, na)
@@ -326,7 +328,8 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
            "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32 growing by {cfg.append_rounds} x {cfg.append_batch}, "
                                   f"{cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, 10000 queries per round, "
                                   f"{args.selectivity:.0%} range, k={k}",
-                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "alpha": args.alpha},
+                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width,
+                      "alpha": args.alpha},
            "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
            "bulk_rebuilt_reference_final": rebuilt, "build": build}
     ix.close()

@@ -423,24 +423,40 @@ int oracle_max_threads(void) {
  *     stable counting sort in batch order.  If any bucket would pass its capacity the call
  *     fails (status 3) and nothing is written.  External id = n_prev + position in the batch.
  *     Existing slots never move.
- *  3. Candidates: two runs of the search above with the new vector as query and
- *     beam = append_beam: (L) restricted to the target bucket's slab, (G) over the whole
- *     attribute domain, keeping only results outside the target bucket.  The whole final
- *     queue is the candidate list, ordered by (distance, slot).
- *  4. Forward selection (Eq. 2): scan the list in order; keep c iff dist(q,c) < dist(c,n) for
- *     every n kept so far; stop when K_local (K_remote) are kept; then back-fill the row with
- *     the earliest rejected candidates; still short -> empty entries.  Row = [local | remote].
+ *  3. Local candidates: one run of the search above with the new vector as query, restricted to
+ *     the target bucket's slab, beam = append_beam.  The whole final queue is the candidate
+ *     list, ordered by (distance, slot).
+ *  4. Forward selection.  Local part (Eq. 2): scan the list in order; keep c iff
+ *     dist(q,c) < dist(c,n) for every n kept so far; stop when K_local are kept; then back-fill
+ *     with the earliest rejected candidates; still short -> empty entries.  Remote part: entry j
+ *     is the nearest to q (ties: smaller slot) among the j-th remote entries of the local
+ *     candidates, empty if they have none.  In a graph built by the two-pass construction the
+ *     j-th remote entry of every node of a bucket points into the same target bucket, so the new
+ *     row keeps that structure: it is the online form of the remote wiring (Section 4.3 pass 2,
+ *     "proximal" and "global" remote edges), found through graph locality instead of a scan.
+ *     (The paper searches remote candidates in the "global scope"; nearest-anywhere candidates
+ *     gave new nodes remote edges into arbitrary far buckets, which a range filter rejects, and
+ *     recall of the dynamic workload decayed with every batch.)
  *  5. Reverse requests: one per written edge q->v: (v, kind, dist(v,q), q).  Sorted by
- *     (v, kind, distance image, q's slot) and applied one after another per target.  With R the
- *     current local (or remote) part of v's row and a = alpha (squared for the squared-L2
- *     metric, so that the test is the paper's on true Euclidean distances):
+ *     (v, kind, distance image, q's slot) and applied one after another per target.  With
+ *     a = alpha (squared for the squared-L2 metric, so that the test is the paper's on true
+ *     Euclidean distances):
+ *     local kind, R = local part of v's row:
  *       pass  = a*dist(v,q) < dist(q,n) for every n in R           (Eq. 2 with Eq. 3's d_eff)
  *       if !pass: drop.  Else if R has an empty entry: fill the first one.  Else, among the
- *       entries n with dist(q,n) < dist(v,n) (v can still reach n through q), the one nearest
- *       to q (ties: smaller slot) is overwritten; if there is none the request is dropped.
- *       Evicting the farthest neighbour instead would keep only the closest ones, which the
- *       paper warns turns the graph into isolated cliques (Section 4.4, topology maintenance);
- *       on clustered data it removed exactly the long links and recall fell with every batch.
+ *       entries of R that q itself points to (anywhere in q's new row), the one nearest to q
+ *       (ties: smaller slot) is overwritten; if there is none the request is dropped.  The
+ *       overwritten neighbour n stays reachable from v through q, so "no pathway is lost"
+ *       (Section 4.4, topology maintenance) holds literally, and no node can lose its last
+ *       in-edge: an edge x->n only disappears while q->n exists.  Evicting the farthest neighbour
+ *       instead keeps only the closest ones, which the paper warns turns the graph into isolated
+ *       cliques; on clustered data it removed exactly the long links (recall fell with every
+ *       batch), and distance-only victim rules left thousands of strongly connected components.
+ *     remote kind, R = remote part of v's row: among the entries of R that lie in q's bucket take
+ *       the one farthest from v (ties: larger slot) and overwrite it iff a*dist(v,q) < its
+ *       distance to v: the entry for that bucket keeps pointing at (about) the nearest node of
+ *       the bucket, with the fresh node favoured by the bias.  If no entry lies in q's bucket, q
+ *       fills the first empty entry, if any.
  *     Fresh nodes already placed in R by this batch count as ordinary neighbours.
  *  6. Table: n_total grows by the bucket's batch count; min/max absorb the new attributes.
  */
@@ -535,24 +551,32 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         for (int64_t i = 0; i < m; ++i) {
             const float *q = vecs + (size_t)i * dim;
             uint32_t *row = rows + (size_t)i * K;
-            int kept[2];
-            for (int kind = 0; kind < 2; ++kind) {
-                int64_t nQ = kind == 0 ? search_one(ix, pr, q, 0, 0, bucket[i], append_beam, sc, NULL)
-                                       : search_one(ix, pr, q, INT32_MIN, INT32_MAX, -1, append_beam, sc, NULL);
-                int nc = 0;
-                for (int64_t j = 0; j < nQ; ++j) {
-                    if (kind == 1 && bucket_of_slot(ix, sc->Q[j].slot) == bucket[i]) continue;
-                    cs[nc] = sc->Q[j].slot; cd[nc] = sc->Q[j].dist; nc++;
+            int kept[2] = {0, 0};
+            /* local part: Eq. 2 selection over the candidates found in the target bucket */
+            int64_t nQ = search_one(ix, pr, q, 0, 0, bucket[i], append_beam, sc, NULL);
+            int nc = 0;
+            for (int64_t j = 0; j < nQ; ++j) { cs[nc] = sc->Q[j].slot; cd[nc] = sc->Q[j].dist; nc++; }
+            kept[0] = forward_select(ix, cs, cd, nc, kl, row);
+            for (int j = 0; j < kl; ++j) {
+                float d = 0.0f;
+                if (row[j] != EMPTY)
+                    for (int t = 0; t < nc; ++t) if (cs[t] == row[j]) d = cd[t];
+                rowd[(size_t)i * K + j] = d;
+            }
+            /* remote part: entry j is the nearest to q among the j-th remote entries of its local
+             * candidates (they all lie in the j-th target bucket when the graph was built that way) */
+            for (int j = 0; j < kr; ++j) {
+                uint32_t best = EMPTY, best_img = 0; float best_d = 0.0f;
+                for (int t = 0; t < nc; ++t) {
+                    uint32_t r = ix->A[(size_t)cs[t] * K + kl + j];
+                    if (r == EMPTY) continue;
+                    float d = oracle_distance(q, ix->X + (size_t)r * dim, dim, ix->metric);
+                    uint32_t im = dist_image(d);
+                    if (best == EMPTY || im < best_img || (im == best_img && r < best)) { best = r; best_img = im; best_d = d; }
                 }
-                uint32_t *part = row + (kind == 0 ? 0 : kl);
-                int cap = kind == 0 ? kl : kr;
-                kept[kind] = forward_select(ix, cs, cd, nc, cap, part);
-                for (int j = 0; j < cap; ++j) {
-                    float d = 0.0f;
-                    if (part[j] != EMPTY)
-                        for (int t = 0; t < nc; ++t) if (cs[t] == part[j]) d = cd[t];
-                    rowd[(size_t)i * K + (kind == 0 ? 0 : kl) + j] = d;
-                }
+                row[kl + j] = best;
+                rowd[(size_t)i * K + kl + j] = best_d;
+                if (best != EMPTY) kept[1]++;
             }
             if (kept_out) { kept_out[2 * i] = kept[0]; kept_out[2 * i + 1] = kept[1]; }
         }
@@ -586,6 +610,25 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         int len = req[r].kind == 0 ? kl : kr;
         const float *xq = ix->X + (size_t)req[r].q * dim, *xv = ix->X + (size_t)req[r].v * dim;
         float lhs = a * req[r].dist;
+        if (req[r].kind == 1) {
+            /* remote part of v: the entry that points into q's bucket keeps the nearest node of
+             * that bucket, the fresh node judged by its biased distance (Eq. 3) */
+            int bq = bucket_of_slot(ix, req[r].q);
+            int far = -1, empty_at = -1; uint32_t far_img = 0;
+            for (int j = 0; j < len; ++j) {
+                if (R[j] == EMPTY) { if (empty_at < 0) empty_at = j; continue; }
+                if (bucket_of_slot(ix, R[j]) != bq) continue;
+                uint32_t im = dist_image(oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric));
+                if (far < 0 || im > far_img || (im == far_img && R[j] > R[far])) { far = j; far_img = im; }
+            }
+            if (far >= 0) {
+                float dfar = oracle_distance(xv, ix->X + (size_t)R[far] * dim, dim, ix->metric);
+                if (lhs < dfar) R[far] = req[r].q;
+            } else if (empty_at >= 0) {
+                R[empty_at] = req[r].q;
+            }
+            continue;
+        }
         int pass = 1, empty_at = -1;
         for (int j = 0; j < len; ++j) {
             if (R[j] == EMPTY) { if (empty_at < 0) empty_at = j; continue; }
@@ -594,14 +637,15 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         }
         if (!pass) continue;
         if (empty_at >= 0) { R[empty_at] = req[r].q; continue; }
-        /* the newcomer takes the place of the neighbour whose pathway it covers best: among the
-         * entries n that are closer to q than to v, the one nearest to q (ties: smaller slot) */
+        /* the newcomer may only take the place of a neighbour it points to itself, so that the
+         * pathway v -> n survives as v -> q -> n; among those the one nearest to q (ties: smaller slot) */
         int victim = -1; uint32_t victim_img = 0;
+        const uint32_t *qrow = ix->A + (size_t)req[r].q * K;
         for (int j = 0; j < len; ++j) {
-            float dvn = oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric);
-            float dqn = oracle_distance(xq, ix->X + (size_t)R[j] * dim, dim, ix->metric);
-            if (!(dqn < dvn)) continue;
-            uint32_t im = dist_image(dqn);
+            int covered = 0;
+            for (int x = 0; x < K; ++x) if (qrow[x] == R[j]) covered = 1;
+            if (!covered) continue;
+            uint32_t im = dist_image(oracle_distance(xq, ix->X + (size_t)R[j] * dim, dim, ix->metric));
             if (victim < 0 || im < victim_img || (im == victim_img && R[j] < R[victim])) { victim = j; victim_img = im; }
         }
         if (victim >= 0) R[victim] = req[r].q;

@@ -115,19 +115,19 @@ __global__ void k_iota(uint32_t *__restrict__ a, int64_t n) {
 struct ForwardArgs {
     const float *X;
     uint32_t *A;
-    const int32_t *table;
-    const int32_t *bucket;
+    const float *vecs;          // the new vectors, batch order
     const uint32_t *slot;
-    const uint32_t *cand_s[2];  // [local search, global search] results: slots
-    const float *cand_d[2];     //                                          distances to the new vector
+    const uint32_t *cand_s;     // local candidate search results: slots [m][beam]
+    const float *cand_d;        //                                 distances to the new vector
     u64 *key1, *key2;           // request keys, one per row entry
     float *reqd;
     int32_t beam, kl, kr, metric;
 };
 
-// Forward edge selection for one new node per wavefront (Section 4.4 step 2, Eq. 2): scan the
+// Forward edges of one new node per wavefront (Section 4.4 step 2).  Local part (Eq. 2): scan the
 // candidates in (distance, slot) order, keep c iff dist(q,c) < dist(c,n) for every kept n, stop
-// at the part's width, back-fill with the earliest rejected ones.  Writes the new adjacency
+// at K_local, back-fill with the earliest rejected ones.  Remote part: entry j is the nearest to
+// the new vector among the j-th remote entries of its local candidates.  Writes the new adjacency
 // row [local | remote] and one reverse request per written edge.
 template <int NCH>
 __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
@@ -136,61 +136,98 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     const int lane = threadIdx.x;
     const int64_t i = blockIdx.x;
     const int K = a.kl + a.kr;
-    uint32_t *cs = reinterpret_cast<uint32_t *>(smem);
+    uint32_t *cs = reinterpret_cast<uint32_t *>(smem);          // local candidates
     float *cd = reinterpret_cast<float *>(cs + a.beam);
-    uint32_t *kept = reinterpret_cast<uint32_t *>(cd + a.beam);
+    uint32_t *rs = reinterpret_cast<uint32_t *>(cd + a.beam);   // remote candidates of one entry
+    float *rd = reinterpret_cast<float *>(rs + a.beam);
+    uint32_t *kept = reinterpret_cast<uint32_t *>(rd + a.beam);
     float *keptd = reinterpret_cast<float *>(kept + 64);
     uint32_t *rej = reinterpret_cast<uint32_t *>(keptd + 64);
     float *rejd = reinterpret_cast<float *>(rej + 64);
     float *dtmp = rejd + 64;
     float *qlds = dtmp + 64;
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
-    const int b = a.bucket[i];
-    const int slab_lo = a.table[T_COLS * b + T_BASE], slab_hi = slab_lo + a.table[T_COLS * b + T_CAP];
     const uint32_t self = a.slot[i];
     const u64 lt_mask = (1ull << lane) - 1ull;
-    for (int kind = 0; kind < 2; ++kind) {
-        const int cap = kind ? a.kr : a.kl, off = kind ? a.kl : 0;
-        const uint32_t *src_s = a.cand_s[kind] + i * a.beam;
-        const float *src_d = a.cand_d[kind] + i * a.beam;
-        int nc = 0;
-        for (int c0 = 0; c0 < a.beam; c0 += 64) {   // remote candidates: results outside the own slab
-            const int idx = c0 + lane;
-            uint32_t s = idx < a.beam ? src_s[idx] : GRAB_EMPTY;
-            bool ok = s != GRAB_EMPTY && (kind == 0 || !((int)s >= slab_lo && (int)s < slab_hi));
+    // ---- local part
+    int nc = 0;
+    for (int c0 = 0; c0 < a.beam; c0 += 64) {
+        const int idx = c0 + lane;
+        uint32_t s = idx < a.beam ? a.cand_s[i * a.beam + idx] : GRAB_EMPTY;
+        bool ok = s != GRAB_EMPTY;
+        u64 m = __ballot(ok);
+        if (ok) { int pos = nc + __popcll(m & lt_mask); cs[pos] = s; cd[pos] = a.cand_d[i * a.beam + idx]; }
+        nc += __popcll(m);
+    }
+    __syncthreads();
+    int nk = 0, nrej = 0;
+    for (int t = 0; t < nc && nk < a.kl; ++t) {
+        const uint32_t c = cs[t];
+        const float dqc = cd[t];
+        bool ok = true;
+        if (nk > 0) {
+            load_query<NCH>(a.X + (size_t)c * D, qreg, qlds, lane);
+            if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
+            eval_rows<NCH>(a.X, qreg, qlds, kept, nk, lane, a.metric, dtmp);
+            __syncthreads();
+            bool hidden = lane < nk && !(dqc < dtmp[lane]);
+            ok = __ballot(hidden) == 0;
+        }
+        if (lane == 0) {
+            if (ok) { kept[nk] = c; keptd[nk] = dqc; }
+            else if (nrej < 64) { rej[nrej] = c; rejd[nrej] = dqc; }
+        }
+        if (ok) ++nk; else if (nrej < 64) ++nrej;
+        __syncthreads();
+    }
+    for (int j = lane; j < a.kl; j += 64) {
+        uint32_t v = GRAB_EMPTY;
+        float d = 0.0f;
+        if (j < nk) { v = kept[j]; d = keptd[j]; }
+        else if (j - nk < nrej) { v = rej[j - nk]; d = rejd[j - nk]; }
+        a.A[(size_t)self * K + j] = v;
+        const int64_t r = i * K + j;
+        a.key1[r] = v == GRAB_EMPTY ? ~0ull : ((u64)v << 1);
+        a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
+        a.reqd[r] = d;
+    }
+    // ---- remote part
+    if (a.kr > 0) {
+        load_query<NCH>(a.vecs + (size_t)i * D, qreg, qlds, lane);
+        __syncthreads();
+    }
+    for (int j = 0; j < a.kr; ++j) {
+        int nr = 0;
+        for (int c0 = 0; c0 < nc; c0 += 64) {
+            const int t = c0 + lane;
+            uint32_t r = t < nc ? a.A[(size_t)cs[t] * K + a.kl + j] : GRAB_EMPTY;
+            bool ok = r != GRAB_EMPTY;
             u64 m = __ballot(ok);
-            if (ok) { int pos = nc + __popcll(m & lt_mask); cs[pos] = s; cd[pos] = src_d[idx]; }
-            nc += __popcll(m);
+            if (ok) rs[nr + __popcll(m & lt_mask)] = r;
+            nr += __popcll(m);
         }
         __syncthreads();
-        int nk = 0, nrej = 0;
-        for (int t = 0; t < nc && nk < cap; ++t) {
-            const uint32_t c = cs[t];
-            const float dqc = cd[t];
-            bool ok = true;
-            if (nk > 0) {
-                load_query<NCH>(a.X + (size_t)c * D, qreg, qlds, lane);
-                if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-                eval_rows<NCH>(a.X, qreg, qlds, kept, nk, lane, a.metric, dtmp);
-                __syncthreads();
-                bool hidden = lane < nk && !(dqc < dtmp[lane]);
-                ok = __ballot(hidden) == 0;
-            }
-            if (lane == 0) {
-                if (ok) { kept[nk] = c; keptd[nk] = dqc; }
-                else if (nrej < 64) { rej[nrej] = c; rejd[nrej] = dqc; }
-            }
-            if (ok) ++nk; else if (nrej < 64) ++nrej;
+        u64 best = ~0ull;
+        if (nr > 0) {
+            eval_rows<NCH>(a.X, qreg, qlds, rs, nr, lane, a.metric, rd);
             __syncthreads();
+            for (int t = lane; t < nr; t += 64) {
+                u64 k = ((u64)dist_image(rd[t]) << 32) | (u64)rs[t];
+                best = k < best ? k : best;
+            }
+#pragma unroll
+            for (int sft = 32; sft > 0; sft >>= 1) {
+                uint32_t hi = __shfl_xor((uint32_t)(best >> 32), sft), lo = __shfl_xor((uint32_t)best, sft);
+                u64 other = ((u64)hi << 32) | lo;
+                best = other < best ? other : best;
+            }
         }
-        for (int j = lane; j < cap; j += 64) {
-            uint32_t v = GRAB_EMPTY;
-            float d = 0.0f;
-            if (j < nk) { v = kept[j]; d = keptd[j]; }
-            else if (j - nk < nrej) { v = rej[j - nk]; d = rejd[j - nk]; }
-            a.A[(size_t)self * K + off + j] = v;
-            const int64_t r = i * K + off + j;
-            a.key1[r] = v == GRAB_EMPTY ? ~0ull : (((u64)v << 1) | (u64)kind);
+        if (lane == 0) {
+            const uint32_t v = best == ~0ull ? GRAB_EMPTY : (uint32_t)(best & 0xFFFFFFFFull);
+            const float d = best == ~0ull ? 0.0f : image_dist((uint32_t)(best >> 32));
+            a.A[(size_t)self * K + a.kl + j] = v;
+            const int64_t r = i * K + a.kl + j;
+            a.key1[r] = v == GRAB_EMPTY ? ~0ull : (((u64)v << 1) | 1ull);
             a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
             a.reqd[r] = d;
         }
@@ -201,17 +238,31 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
 struct RewireArgs {
     const float *X;
     uint32_t *A;
+    const int32_t *table;
     const u64 *key1s;       // sorted (target << 1 | kind); ~0 for "no request"
     const uint32_t *order;  // request index at each sorted position
     const u64 *key2;        // by request index: distance image << 32 | source slot
     const float *reqd;      // by request index: dist(target, source)
     int64_t nreq;
-    int32_t kl, kr, metric;
+    int32_t kl, kr, metric, B;
     float a;                // alpha, squared for the squared-L2 metric
 };
 
-// Reverse rewiring (Section 4.4 step 3, Eq. 2 with Eq. 3's effective distance): the wavefront
-// that sits on the first request of a (target, kind) group applies the whole group in order.
+__device__ __forceinline__ int bucket_of_slot_dev(const int32_t *__restrict__ table, int32_t B, uint32_t slot) {
+    int l = 0, r = B;  // last bucket whose base <= slot
+    while (r - l > 1) {
+        int m = (l + r) >> 1;
+        if ((uint32_t)table[T_COLS * m + T_BASE] <= slot) l = m; else r = m;
+    }
+    return l;
+}
+
+// Reverse rewiring (Section 4.4 step 3): the wavefront that sits on the first request of a
+// (target, kind) group applies the whole group in order.
+// Local kind: Eq. 2 with Eq. 3's effective distance decides whether the newcomer may enter; it
+// then fills an empty entry or overwrites, among the entries it points to itself, the one
+// nearest to it.  Remote kind: the entry of the target's remote part that lies in the newcomer's
+// bucket is overwritten iff the newcomer's biased distance to the target is smaller.
 template <int NCH>
 __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -226,56 +277,95 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
     const int K = a.kl + a.kr, off = kind ? a.kl : 0, len = kind ? a.kr : a.kl;
     uint32_t *R = reinterpret_cast<uint32_t *>(smem);   // current part of v's row
     uint32_t *Rl = R + 64;                                // same with empty entries pointing at row 0
-    float *dv = reinterpret_cast<float *>(Rl + 64);       // dist(v, R[j])
-    float *dq = dv + 64;                                  // dist(q, R[j])
-    float *qlds = dq + 64;
+    float *dq = reinterpret_cast<float *>(Rl + 64);       // local: dist(q, R[j]); remote: dist(v, R[j])
+    uint32_t *qrow = reinterpret_cast<uint32_t *>(dq + 64);  // the requesting node's own row
+    float *qlds = reinterpret_cast<float *>(qrow + 128);
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
     if (lane < len) {
         uint32_t e = a.A[(size_t)v * K + off + lane];
         R[lane] = e;
         Rl[lane] = e == GRAB_EMPTY ? 0u : e;
     }
-    load_query<NCH>(a.X + (size_t)v * D, qreg, qlds, lane);
-    __syncthreads();
-    eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dv);
     __syncthreads();
     bool changed = false;
-    for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
-        const uint32_t ridx = a.order[p];
-        const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
-        const float dvq = a.reqd[ridx];
-        const float lhs = a.a * dvq;
-        load_query<NCH>(a.X + (size_t)q * D, qreg, qlds, lane);
+    if (kind == 1) {
+        load_query<NCH>(a.X + (size_t)v * D, qreg, qlds, lane);
         if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-        eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);
+        eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);   // dist(v, R[j])
         __syncthreads();
-        const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
-        const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < dq[lane]);
-        if (__ballot(blocked) == 0) {
-            const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+        for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
+            const uint32_t ridx = a.order[p];
+            const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
+            const float dvq = a.reqd[ridx];
+            const float lhs = a.a * dvq;
+            const int bq = bucket_of_slot_dev(a.table, a.B, q);
+            const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
+            const bool inb = mine != GRAB_EMPTY && bucket_of_slot_dev(a.table, a.B, mine) == bq;
             int at = -1;
-            if (empties) {
-                at = __ffsll((long long)empties) - 1;
-            } else {
-                // victim: among the entries closer to q than to v, the one nearest to q
-                const bool covered = lane < len && dq[lane] < dv[lane];
-                u64 kf = covered ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : ~0ull;
-                u64 kmin = kf;
+            if (__ballot(inb)) {
+                u64 kf = inb ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : 0ull;
+                u64 kmax = kf;
 #pragma unroll
                 for (int s = 32; s > 0; s >>= 1) {
-                    uint32_t hi = __shfl_xor((uint32_t)(kmin >> 32), s), lo = __shfl_xor((uint32_t)kmin, s);
+                    uint32_t hi = __shfl_xor((uint32_t)(kmax >> 32), s), lo = __shfl_xor((uint32_t)kmax, s);
                     u64 other = ((u64)hi << 32) | lo;
-                    kmin = other < kmin ? other : kmin;
+                    kmax = other > kmax ? other : kmax;
                 }
-                if (kmin != ~0ull) at = __ffsll((long long)__ballot(covered && kf == kmin)) - 1;
+                const int far = __ffsll((long long)__ballot(inb && kf == kmax)) - 1;
+                if (lhs < dq[far]) at = far;
+            } else {
+                const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+                if (empties) at = __ffsll((long long)empties) - 1;
             }
             __syncthreads();
             if (at >= 0) {
-                if (lane == at) { R[at] = q; Rl[at] = q; dv[at] = dvq; }
+                if (lane == at) { R[at] = q; Rl[at] = q; dq[at] = dvq; }
                 changed = true;
             }
+            __syncthreads();
         }
-        __syncthreads();
+    } else {
+        for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
+            const uint32_t ridx = a.order[p];
+            const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
+            const float dvq = a.reqd[ridx];
+            const float lhs = a.a * dvq;
+            for (int x = lane; x < K; x += 64) qrow[x] = a.A[(size_t)q * K + x];
+            load_query<NCH>(a.X + (size_t)q * D, qreg, qlds, lane);
+            if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
+            eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);
+            __syncthreads();
+            const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
+            const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < dq[lane]);
+            if (__ballot(blocked) == 0) {
+                const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+                int at = -1;
+                if (empties) {
+                    at = __ffsll((long long)empties) - 1;
+                } else {
+                    // victim: among the entries q points to itself (v still reaches them through q),
+                    // the one nearest to q
+                    bool covered = false;
+                    if (lane < len)
+                        for (int x = 0; x < K; ++x) covered |= qrow[x] == mine;
+                    u64 kf = covered ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : ~0ull;
+                    u64 kmin = kf;
+#pragma unroll
+                    for (int s = 32; s > 0; s >>= 1) {
+                        uint32_t hi = __shfl_xor((uint32_t)(kmin >> 32), s), lo = __shfl_xor((uint32_t)kmin, s);
+                        u64 other = ((u64)hi << 32) | lo;
+                        kmin = other < kmin ? other : kmin;
+                    }
+                    if (kmin != ~0ull) at = __ffsll((long long)__ballot(covered && kf == kmin)) - 1;
+                }
+                __syncthreads();
+                if (at >= 0) {
+                    if (lane == at) { R[at] = q; Rl[at] = q; }
+                    changed = true;
+                }
+            }
+            __syncthreads();
+        }
     }
     if (changed && lane < len) a.A[(size_t)v * K + off + lane] = R[lane];
 }
@@ -284,10 +374,10 @@ template <int NCH>
 grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
     const size_t qbytes = EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4;
     if (phase == 0) {
-        size_t lds = (size_t)f.beam * 8 + 64 * 4 * 5 + qbytes;
+        size_t lds = (size_t)f.beam * 16 + 64 * 4 * 5 + qbytes;
         k_forward<NCH><<<dim3((unsigned)m), dim3(64), lds, ix->stream>>>(f);
     } else {
-        size_t lds = 64 * 4 * 4 + qbytes;
+        size_t lds = 64 * 4 * 3 + 128 * 4 + qbytes;
         k_rewire<NCH><<<dim3((unsigned)r.nreq), dim3(64), lds, ix->stream>>>(r);
     }
     GRAB_HIP(ix, hipGetLastError());
@@ -315,13 +405,12 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     const int64_t nreq = m * K;
     grab_status rc;
     // ---- arena
-    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_CG_S,
-           A_CG_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_N };
+    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_N };
     size_t need[A_N];
     for (size_t &x : need) x = 0;
     need[A_BUCKET] = need[A_KEYS] = need[A_IDX] = need[A_KEYS_S] = need[A_IDX_S] = need[A_SLOT] = need[A_LO] = need[A_HI] = (size_t)m * 4;
     need[A_STARTS] = need[A_COUNTS] = (size_t)B * 4;
-    need[A_CL_S] = need[A_CL_D] = need[A_CG_S] = need[A_CG_D] = (size_t)m * beam * 4;
+    need[A_CL_S] = need[A_CL_D] = (size_t)m * beam * 4;
     need[A_KEY1] = need[A_KEY2] = need[A_K2S] = need[A_K1G] = need[A_K1S] = (size_t)nreq * 8;
     need[A_REQD] = need[A_ORD0] = need[A_ORD1] = need[A_ORD2] = (size_t)nreq * 4;
     size_t tmp1 = 0, tmp2 = 0;
@@ -360,7 +449,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
             return grab_fail(ix, GRAB_EFULL, "bucket %d holds %d of %d slots and the batch adds %d", full,
                              ix->h_table[T_COLS * full + T_NTOT], ix->h_table[T_COLS * full + T_CAP], over);
     }
-    // ---- 3: candidate searches against the pre-batch index (new rows are not visible yet)
+    // ---- 3: local candidate search against the pre-batch index (new rows are not visible yet)
     k_fill_range<<<blocks_for(m), TPB, 0, st>>>((int32_t *)P(A_LO), (int32_t *)P(A_HI), m);
     if ((rc = grab_reserve(ix, ix->plans, m * sizeof(QueryPlan))) != GRAB_OK) return rc;
     if ((rc = grab_reserve(ix, ix->seeds, (size_t)m * proto.n_seeds * 4)) != GRAB_OK) return rc;
@@ -372,15 +461,11 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     s.only_bucket = bucket; s.out_ids = (uint32_t *)P(A_CL_S); s.out_dist = (float *)P(A_CL_D);
     if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
     if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
-    s.only_bucket = nullptr; s.out_ids = (uint32_t *)P(A_CG_S); s.out_dist = (float *)P(A_CG_D);
-    if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
-    if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
     ix->last_nq = 0;
     // ---- 4: forward selection, new adjacency rows, reverse requests
     ForwardArgs f;
-    f.X = ix->X; f.A = ix->A; f.table = ix->table; f.bucket = bucket; f.slot = slot;
-    f.cand_s[0] = (const uint32_t *)P(A_CL_S); f.cand_d[0] = (const float *)P(A_CL_D);
-    f.cand_s[1] = (const uint32_t *)P(A_CG_S); f.cand_d[1] = (const float *)P(A_CG_D);
+    f.X = ix->X; f.A = ix->A; f.vecs = d_vecs; f.slot = slot;
+    f.cand_s = (const uint32_t *)P(A_CL_S); f.cand_d = (const float *)P(A_CL_D);
     f.key1 = (u64 *)P(A_KEY1); f.key2 = (u64 *)P(A_KEY2); f.reqd = (float *)P(A_REQD);
     f.beam = beam; f.kl = kl; f.kr = kr; f.metric = ix->metric;
     RewireArgs r;
@@ -399,7 +484,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
                                            (uint32_t *)P(A_ORD2), (size_t)nreq, 0, 64, st));
     r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.order = (const uint32_t *)P(A_ORD2);
     r.key2 = (const u64 *)P(A_KEY2); r.reqd = (const float *)P(A_REQD); r.nreq = nreq;
-    r.kl = kl; r.kr = kr; r.metric = ix->metric;
+    r.kl = kl; r.kr = kr; r.metric = ix->metric; r.table = ix->table; r.B = B;
     r.a = ix->metric == GRAB_L2SQ ? ix->prm.alpha * ix->prm.alpha : ix->prm.alpha;
     if ((rc = launch_append(ix, f, r, m, 1)) != GRAB_OK) return rc;
     // ---- 6: table

@@ -11,6 +11,37 @@
 
 namespace {
 
+// integer finaliser used for the seed jitter (the public-domain MurmurHash3 finaliser)
+__device__ __forceinline__ uint32_t mix32(uint32_t x) {
+    x ^= x >> 16; x *= 0x85ebca6bu; x ^= x >> 13; x *= 0xc2b2ae35u; x ^= x >> 16;
+    return x;
+}
+
+// first index i in sorted a[0..n) with a[i] >= key (strict=false) or a[i] > key (strict=true):
+// a 64-way search, each step probing 64 evenly spaced positions with the whole wave
+__device__ int wave_bound(const int32_t *__restrict__ a, int n, int key, bool strict, int lane) {
+    int lo = 0, hi = n;
+    while (hi > lo) {
+        int chunk = (hi - lo + 63) >> 6;
+        int pos = lo + lane * chunk;
+        bool below = false;
+        if (pos < hi) {
+            int x = a[pos];
+            below = strict ? (x <= key) : (x < key);
+        }
+        int c = __popcll(__ballot(below));  // sorted input: the first c probes are below
+        if (c == 0) {
+            hi = lo;
+        } else {
+            int nlo = lo + (c - 1) * chunk + 1;
+            int nhi = lo + c * chunk;
+            hi = nhi < hi ? nhi : hi;
+            lo = nlo;
+        }
+    }
+    return lo;
+}
+
 // ----------------------------------------------------------------------------- select + seed
 // Algorithm 2 lines 1-2: the run of buckets whose [min,max] meets [lo,hi]; the valid part of
 // the sorted prefix of the two edge buckets by search; the seed population (valid sorted part
