@@ -127,9 +127,17 @@ grab_status grab_search_range(grab_index *ix, const float *queries, const int32_
                               uint32_t *out_ids, float *out_dist);
 
 /* Batched insertion (Section 4.4): appends m objects at the tails of their buckets without
- * moving any existing slot, searches candidate neighbours in the target bucket and
- * globally, selects forward edges by the diversity rule (Eq. 2) and rewires reverse edges
- * with the freshness bias (Eq. 3).  New external ids are n_prev .. n_prev+m-1 in input
+ * moving any existing slot (bucket = the one whose attribute interval holds the new value, else
+ * the first one above it; slot = stable order of arrival inside the bucket).  Decisions about
+ * existing nodes use the index as it was before the batch.  Per new object: candidate neighbours
+ * by a search restricted to its bucket (queue GRAB_P_APPEND_BEAM, the current seeds / width /
+ * visited-cap parameters); local forward edges by the diversity rule (Eq. 2) with back-fill;
+ * remote entry j = nearest among the j-th remote entries of the candidates; then one reverse
+ * request per written edge, applied per target in (kind, distance, source) order: a local request
+ * must pass Eq. 2 with the freshness-biased distance (Eq. 3) and then fills an empty entry or
+ * overwrites, among the target's neighbours that the new object points to itself, the one nearest
+ * to it; a remote request overwrites the target's remote entry that lies in the new object's
+ * bucket iff the biased distance is smaller.  New external ids are n_prev .. n_prev+m-1 in input
  * order.  GRAB_EFULL if any bucket would overflow its slab: nothing is written then.
  * Needs k_local <= 64 and k_remote <= 64.
  * Errors: GRAB_EINVAL, GRAB_ESTATE (no graph), GRAB_EFULL, GRAB_ENOMEM, GRAB_EHIP. */
