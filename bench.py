@@ -29,12 +29,11 @@ METRIC = "filtered queries/sec at recall@10>=0.95 (1M x 128 fp32, 10% range), % 
 
 # (beam, n_seeds, search_width, visited_cap)
 GRID = [
-    (32, 256, 4, 1400), (32, 192, 4, 1400), (32, 256, 2, 1400), (32, 384, 2, 1400), (48, 128, 4, 1400),
-    (48, 192, 4, 1400), (48, 256, 4, 1400), (48, 384, 4, 1400), (64, 128, 4, 1400), (64, 256, 4, 1400),
-    (64, 128, 1, 1400), (64, 64, 1, 2800), (64, 512, 4, 1400), (64, 128, 2, 2800), (64, 256, 4, 4000),
-    (96, 128, 2, 2800), (96, 256, 4, 4000), (128, 128, 2, 4000), (128, 256, 4, 2800), (128, 512, 4, 4000),
-    (64, 1024, 4, 2000), (96, 1024, 4, 2400), (128, 768, 4, 2400), (128, 1024, 4, 2400), (128, 1024, 4, 4000),
-    (256, 2048, 4, 8000),
+    (32, 64, 2, 1400), (32, 48, 1, 1400), (32, 128, 2, 1400), (32, 96, 4, 1400), (24, 128, 4, 1400), (24, 192, 4, 1400),
+    (32, 32, 1, 1400), (32, 256, 4, 1400), (48, 64, 2, 1400), (48, 128, 4, 1400), (64, 64, 2, 1400), (64, 128, 4, 1400),
+    (64, 64, 1, 2800), (64, 128, 2, 2800), (64, 256, 4, 4000), (96, 128, 2, 2800), (96, 256, 4, 4000), (128, 128, 2, 4000),
+    (128, 256, 4, 2800), (128, 512, 4, 4000), (64, 1024, 4, 2000), (96, 1024, 4, 2400), (128, 768, 4, 2400),
+    (128, 1024, 4, 2400), (128, 1024, 4, 4000), (256, 2048, 4, 8000),
 ]
 
 
@@ -98,7 +97,7 @@ def main():
     torch.cuda.synchronize()
     build["build_buckets_ms"] = round((time.perf_counter() - t) * 1e3, 2)
     t = time.perf_counter()
-    ix.build_graph(cfg.k_local, cfg.k_remote, 64)      # the library's own two-pass construction, timed only
+    ix.build_graph(cfg.k_local, cfg.k_remote, 0)       # the library's own two-pass construction (pool 128), timed only
     torch.cuda.synchronize()
     build["build_graph_ms"] = round((time.perf_counter() - t) * 1e3, 2)
     table, id2slot, _ = ix.get_layout()

@@ -109,8 +109,9 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
  * The paper draws remote candidates from a global graph built by a third-party pipeline
  * (Algorithm 1); here they come from exact search in the target bucket.  Distances use the same
  * fixed fp32 summation order as the search, ties go to the smaller slot.
- * pool = 0 means min(2 * k_local, 64).  Requires 1 <= k_local <= 64, 0 <= k_remote <= 64,
- * k_local <= pool <= 64.  Errors: GRAB_EINVAL, GRAB_ESTATE (no layout), GRAB_ENOMEM, GRAB_EHIP;
+ * pool = 0 means min(4 * k_local, 128): wide enough to reach past a node's own cluster, which is
+ * what gives the graph its long links.  Requires 1 <= k_local <= 64, 0 <= k_remote <= 64,
+ * k_local <= pool <= 128.  Errors: GRAB_EINVAL, GRAB_ESTATE (no layout), GRAB_ENOMEM, GRAB_EHIP;
  * on error the index is left without a graph. */
 grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, int32_t pool);
 

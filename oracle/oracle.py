@@ -221,7 +221,7 @@ class Index:
     def build_graph(self, k_local: int, k_remote: int, pool: Optional[int] = None, threads: int = 1,
                     want_lists: bool = False):
         """Builds the adjacency in place.  Returns (F, R) when want_lists."""
-        pool = pool or 2 * k_local
+        pool = pool or min(4 * k_local, 128)
         self.k_local, self.k_remote = k_local, k_remote
         self.A = np.full((self.n_cap, k_local + k_remote), EMPTY, dtype=np.uint32)
         F = np.empty((self.n_cap, pool), dtype=np.uint32) if want_lists else None

@@ -235,8 +235,8 @@ grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, 
     if (!ix) return GRAB_EINVAL;
     if (!ix->X) return grab_fail(ix, GRAB_ESTATE, "build_buckets first");
     if (k_local < 1 || k_local > 64 || k_remote < 0 || k_remote > 64) return grab_fail(ix, GRAB_EINVAL, "need 1 <= k_local <= 64 and 0 <= k_remote <= 64");
-    if (pool == 0) pool = 2 * k_local < 64 ? 2 * k_local : 64;
-    if (pool < k_local || pool > 64) return grab_fail(ix, GRAB_EINVAL, "pool must be k_local..64");
+    if (pool == 0) pool = 4 * k_local < 128 ? 4 * k_local : 128;
+    if (pool < k_local || pool > 128) return grab_fail(ix, GRAB_EINVAL, "pool must be k_local..128");
     GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
     ix->has_graph = false;
     (void)hipFree(ix->A);

@@ -59,6 +59,56 @@ __device__ __forceinline__ u64 merge_lanes(u64 qk, u64 ck, int beam, int lane) {
     return lane < beam ? m : SENT;
 }
 
+// The candidate queue: M keys per lane in registers, position p = 64*r + lane of register r,
+// sorted ascending over p.  Strides of 64 and more are compare-exchanges between registers of
+// the same lane; smaller strides are lane exchanges applied to every register.
+template <int M>
+struct LaneQueue {
+    u64 k[M];
+
+    __device__ __forceinline__ void clear() {
+#pragma unroll
+        for (int r = 0; r < M; ++r) k[r] = SENT;
+    }
+    // queue <- the 64*M smallest of queue and ck (sorted over the lanes, SENT-padded), cut to beam:
+    // min against the reversed newcomers turns the sorted queue into a bitonic sequence that holds
+    // exactly the survivors; a bitonic merge sorts it again
+    __device__ __forceinline__ void merge(u64 ck, int beam, int lane) {
+        const u64 rv = shfl64(ck, 63 - lane);
+        k[M - 1] = k[M - 1] < rv ? k[M - 1] : rv;
+#pragma unroll
+        for (int s = M / 2; s >= 1; s >>= 1)
+#pragma unroll
+            for (int r = 0; r < M; ++r)
+                if ((r & s) == 0) {
+                    const u64 x = k[r], y = k[r + s];
+                    k[r] = x < y ? x : y;
+                    k[r + s] = x < y ? y : x;
+                }
+#pragma unroll
+        for (int j = 32; j > 0; j >>= 1) {
+            const bool take_min = (lane & j) == 0;
+#pragma unroll
+            for (int r = 0; r < M; ++r) {
+                const u64 o = shfl_xor64(k[r], j);
+                const bool less = k[r] < o;
+                k[r] = (less == take_min) ? k[r] : o;
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < M; ++r)
+            if (64 * r + lane >= beam) k[r] = SENT;
+    }
+    // key at position p (same p in every lane)
+    __device__ __forceinline__ u64 at(int p) const {
+        u64 t = SENT;
+#pragma unroll
+        for (int r = 0; r < M; ++r)
+            if ((p >> 6) == r) t = k[r];
+        return shfl64(t, p & 63);
+    }
+};
+
 template <int NCH>
 struct EvalShape {
     // pieces of a row held in registers at once, and rows per lane group in flight

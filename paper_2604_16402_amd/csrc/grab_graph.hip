@@ -30,7 +30,7 @@ struct KnnArgs {
     int32_t P, metric, exclude_self;
 };
 
-template <int NCH>
+template <int NCH, int PM>
 __global__ __launch_bounds__(256) void k_knn(KnnArgs a) {
     constexpr int D4 = NCH * 8;
     __shared__ float Bt[32 * 65];             // target tile chunk, [float k][row], padded
@@ -54,16 +54,17 @@ __global__ __launch_bounds__(256) void k_knn(KnnArgs a) {
         for (int r = 0; r < 8; ++r) {
             if (!valid_i[r]) continue;
             if (a.P == 1) { if (lane == 0) a.out_s[(int64_t)slot_i[r] * a.out_stride + a.out_off] = GRAB_EMPTY; }
-            else if (lane < a.P) { a.out_s[(int64_t)slot_i[r] * a.P + lane] = GRAB_EMPTY; a.out_d[(int64_t)slot_i[r] * a.P + lane] = __builtin_inff(); }
+            else for (int pos = lane; pos < a.P; pos += 64) { a.out_s[(int64_t)slot_i[r] * a.P + pos] = GRAB_EMPTY; a.out_d[(int64_t)slot_i[r] * a.P + pos] = __builtin_inff(); }
         }
         return;
     }
     const int tb = a.table[T_COLS * t + T_BASE], tn = a.table[T_COLS * t + T_NTOT];
     const float4 *X4 = reinterpret_cast<const float4 *>(a.X);
     const u64 lt_mask = (1ull << lane) - 1ull;
-    u64 qk[8], thr[8];
+    LaneQueue<PM> qk[8];   // P > 1: the P best keys of each source row; P == 1: k[0] is a per-lane minimum
+    u64 thr[8];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) { qk[r] = SENT; thr[r] = SENT; }
+    for (int r = 0; r < 8; ++r) { qk[r].clear(); thr[r] = SENT; }
 
     for (int j0 = 0; j0 < tn; j0 += 64) {
         float acc[8][8];
@@ -122,7 +123,7 @@ __global__ __launch_bounds__(256) void k_knn(KnnArgs a) {
             const u64 key = make_key(s, slot_j);
             const bool keep = valid_j && valid_i[r] && !(a.exclude_self && slot_j == slot_i[r]) && key < thr[r];
             if (a.P == 1) {
-                if (keep && key < qk[r]) qk[r] = key;     // per-lane running minimum, reduced at the end
+                if (keep && key < qk[r].k[0]) qk[r].k[0] = key;     // per-lane running minimum, reduced at the end
             } else {
                 const u64 m = __ballot(keep);
                 if (m) {
@@ -134,8 +135,8 @@ __global__ __launch_bounds__(256) void k_knn(KnnArgs a) {
                     int Pc = 2;
                     while (Pc < cnt) Pc <<= 1;
                     ck = sort_lanes(ck, Pc, lane);
-                    qk[r] = merge_lanes(qk[r], ck, a.P, lane);
-                    thr[r] = shfl64(qk[r], a.P - 1);
+                    qk[r].merge(ck, a.P, lane);
+                    thr[r] = qk[r].at(a.P - 1);
                 }
             }
         }
@@ -143,7 +144,7 @@ __global__ __launch_bounds__(256) void k_knn(KnnArgs a) {
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         if (a.P == 1) {
-            u64 best = qk[r];
+            u64 best = qk[r].k[0];
 #pragma unroll
             for (int s = 32; s > 0; s >>= 1) {
                 u64 o = shfl_xor64(best, s);
@@ -151,10 +152,17 @@ __global__ __launch_bounds__(256) void k_knn(KnnArgs a) {
             }
             if (valid_i[r] && lane == 0)
                 a.out_s[(int64_t)slot_i[r] * a.out_stride + a.out_off] = best == SENT ? GRAB_EMPTY : key_slot(best);
-        } else if (valid_i[r] && lane < a.P) {
-            const bool has = qk[r] != SENT;
-            a.out_s[(int64_t)slot_i[r] * a.P + lane] = has ? key_slot(qk[r]) : GRAB_EMPTY;
-            a.out_d[(int64_t)slot_i[r] * a.P + lane] = has ? image_dist((uint32_t)(qk[r] >> 32)) : __builtin_inff();
+        } else if (valid_i[r]) {
+#pragma unroll
+            for (int m = 0; m < PM; ++m) {
+                const int pos = 64 * m + lane;
+                if (pos < a.P) {
+                    const u64 kk = qk[r].k[m];
+                    const bool has = kk != SENT;
+                    a.out_s[(int64_t)slot_i[r] * a.P + pos] = has ? key_slot(kk) : GRAB_EMPTY;
+                    a.out_d[(int64_t)slot_i[r] * a.P + pos] = has ? image_dist((uint32_t)(kk >> 32)) : __builtin_inff();
+                }
+            }
         }
     }
 }
@@ -171,6 +179,7 @@ struct PruneArgs {
 
 // Eq. 2 scan for one node per wavefront: candidate t is kept iff dist(u,c_t) < dist(c_t,n) for every
 // n kept before it; the kept rows are evaluated eight lanes per row against the candidate's row.
+// Up to 128 candidates: lane l holds candidates l and 64 + l.
 template <int NCH>
 __global__ __launch_bounds__(64) void k_prune(PruneArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -179,43 +188,55 @@ __global__ __launch_bounds__(64) void k_prune(PruneArgs a) {
     const int64_t u = blockIdx.x;
     if (a.slot2id[u] == GRAB_EMPTY) return;
     uint32_t *kept = reinterpret_cast<uint32_t *>(smem);
-    float *dtmp = reinterpret_cast<float *>(kept + 64);
-    float *qlds = dtmp + 64;
+    float *dtmp = reinterpret_cast<float *>(kept + 128);
+    float *qlds = dtmp + 128;
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
-    const uint32_t cs = lane < a.P ? a.cand_s[u * a.P + lane] : GRAB_EMPTY;
-    const float cd = lane < a.P ? a.cand_d[u * a.P + lane] : 0.0f;
-    const u64 validm = __ballot(cs != GRAB_EMPTY);
-    const int nc = __popcll(validm);
+    uint32_t cs[2];
+    float cd[2];
+    u64 validm[2], keptm[2] = {0, 0};
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = 64 * h + lane;
+        cs[h] = t < a.P ? a.cand_s[u * a.P + t] : GRAB_EMPTY;
+        cd[h] = t < a.P ? a.cand_d[u * a.P + t] : 0.0f;
+        validm[h] = __ballot(cs[h] != GRAB_EMPTY);
+    }
+    const int nc = __popcll(validm[0]) + __popcll(validm[1]);   // valid candidates form a prefix
     const u64 lt_mask = (1ull << lane) - 1ull;
-    u64 keptm = 0;
     int nk = 0;
     for (int t = 0; t < nc; ++t) {
-        const uint32_t c = (uint32_t)__shfl((int)cs, t);
-        const float dqc = __shfl(cd, t);
+        const uint32_t c = t < 64 ? (uint32_t)__shfl((int)cs[0], t) : (uint32_t)__shfl((int)cs[1], t - 64);
+        const float dqc = t < 64 ? __shfl(cd[0], t) : __shfl(cd[1], t - 64);
         bool ok = true;
         if (nk > 0) {
             load_query<NCH>(a.X + (size_t)c * D, qreg, qlds, lane);
             if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
             eval_rows<NCH>(a.X, qreg, qlds, kept, nk, lane, a.metric, dtmp);
             __syncthreads();
-            const bool hidden = lane < nk && !(dqc < dtmp[lane]);
+            const bool hidden = (lane < nk && !(dqc < dtmp[lane])) || (64 + lane < nk && !(dqc < dtmp[64 + lane]));
             ok = __ballot(hidden) == 0;
         }
         if (ok) {
             if (lane == 0) kept[nk] = c;
-            keptm |= 1ull << t;
+            keptm[t >> 6] |= 1ull << (t & 63);
             ++nk;
         }
         __syncthreads();
     }
-    if (lane < a.P) {
+    const int nk0 = __popcll(keptm[0]), nr0 = __popcll(~keptm[0] & validm[0]);
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const int t = 64 * h + lane;
+        if (t >= a.P) continue;
         uint32_t out = GRAB_EMPTY;
         float outd = __builtin_inff();
-        int pos = lane;
-        if (lane < nc) {
-            const bool mine = (keptm >> lane) & 1ull;
-            pos = mine ? __popcll(keptm & lt_mask) : nk + __popcll(~keptm & validm & lt_mask);
-            out = cs; outd = cd;
+        int pos = t;
+        if (t < nc) {
+            const bool mine = (keptm[h] >> lane) & 1ull;
+            const int kept_before = (h ? nk0 : 0) + __popcll(keptm[h] & lt_mask);
+            const int rej_before = (h ? nr0 : 0) + __popcll(~keptm[h] & validm[h] & lt_mask);
+            pos = mine ? kept_before : nk + rej_before;
+            out = cs[h]; outd = cd[h];
         }
         a.F[u * a.P + pos] = out;
         a.Fd[u * a.P + pos] = outd;
@@ -275,9 +296,10 @@ __global__ void k_interleave(const uint32_t *__restrict__ F, const uint32_t *__r
 template <int NCH>
 grab_status launch_graph_t(grab_index *ix, const KnnArgs *k, const PruneArgs *p, unsigned tiles) {
     if (k) {
-        k_knn<NCH><<<dim3(tiles, (unsigned)ix->B), dim3(256), 0, ix->stream>>>(*k);
+        if (k->P > 64) k_knn<NCH, 2><<<dim3(tiles, (unsigned)ix->B), dim3(256), 0, ix->stream>>>(*k);
+        else k_knn<NCH, 1><<<dim3(tiles, (unsigned)ix->B), dim3(256), 0, ix->stream>>>(*k);
     } else {
-        size_t lds = 64 * 4 * 2 + (EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4);
+        size_t lds = 128 * 4 * 2 + (EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4);
         k_prune<NCH><<<dim3((unsigned)ix->n_slots), dim3(64), lds, ix->stream>>>(*p);
     }
     GRAB_HIP(ix, hipGetLastError());

@@ -212,7 +212,7 @@ def build_graph(vectors: np.ndarray, bucket_of: np.ndarray, n_buckets: int, k_lo
     as uint32 external ids, ``EMPTY`` where no edge exists.
 
     Local rows (Section 4.3, first pass): exact k-NN inside the bucket over a pool of
-    candidates, greedy diversity selection (a candidate is kept when it is closer to the
+    candidates (4 x k_local by default: wide enough to reach past the node's own cluster), greedy diversity selection (a candidate is kept when it is closer to the
     node than to every candidate already kept, Eq. 2), back-filled with the nearest
     rejected candidates, then interleaved with the reverse edges and cut to ``k_local``.
     Remote rows (second pass): the nearest node in each bucket of ``remote_targets``.
@@ -221,7 +221,7 @@ def build_graph(vectors: np.ndarray, bucket_of: np.ndarray, n_buckets: int, k_lo
     """
     import torch
     n, _ = vectors.shape
-    pool = pool or max(2 * k_local, k_local + 16)
+    pool = pool or 4 * k_local
     local_adj = np.full((n, k_local), EMPTY, dtype=np.uint32)
     remote_adj = np.full((n, max(k_remote, 0)), EMPTY, dtype=np.uint32)
     order = np.argsort(bucket_of, kind="stable")

@@ -22,12 +22,14 @@ def _case(n, dim, B, metric, seed, n_cap=None):
     (1500, 960, 3, 8, 2, 24, W.L2SQ, None),
     (700, 32, 9, 33, 5, 64, W.L2SQ, None),      # buckets (~78 rows) barely larger than the pool
     (300, 32, 6, 32, 3, 64, W.L2SQ, None),      # buckets (50 rows) smaller than the pool: short lists
+    (4000, 128, 5, 32, 4, 128, W.L2SQ, None),   # 128 candidates: two per lane
+    (2600, 64, 4, 20, 3, 100, W.L2SQ, 3000),    # a pool that is not a power of two
 ])
 def test_build_graph_matches_oracle(n, dim, B, kl, kr, pool, metric, n_cap):
     from paper_2604_16402_amd import binding
     cfg, X, a = _case(n, dim, B, metric, seed=n + dim)
     ora = O.Index(X, a, B, n_cap=n_cap, metric=metric)
-    ora.build_graph(kl, kr, pool=pool or min(2 * kl, 64), threads=O.max_threads())
+    ora.build_graph(kl, kr, pool=pool or min(4 * kl, 128), threads=O.max_threads())
     ix = binding.Index(dim, metric)
     ix.build_buckets(X, a, B, n_cap)
     ix.build_graph(kl, kr, pool)
@@ -69,7 +71,7 @@ def test_build_graph_rejects_bad_arguments():
         ix.build_graph(8, 2, 16)
     assert e.value.status == B.ESTATE
     ix.build_buckets(np.zeros((50, 32), np.float32), np.arange(50, dtype=np.int32), 2)
-    for kl, kr, pool in [(0, 2, 8), (70, 2, 64), (8, 70, 16), (8, 2, 4), (8, 2, 100)]:
+    for kl, kr, pool in [(0, 2, 8), (70, 2, 64), (8, 70, 16), (8, 2, 4), (8, 2, 200)]:
         with pytest.raises(B.GrabError) as e:
             ix.build_graph(kl, kr, pool)
         assert e.value.status == B.EINVAL
@@ -85,7 +87,7 @@ def test_full_size_build_properties_and_recall():
     dev = torch.device("cuda:0")
     cfg = W.CONFIGS["c2"]
     X, a, q = W.base_vectors(cfg), W.attributes(cfg), W.query_vectors(cfg)
-    kl, kr, pool = cfg.k_local, cfg.k_remote, 64
+    kl, kr, pool = cfg.k_local, cfg.k_remote, 128
     ix = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
     Xd, ad = torch.from_numpy(X).to(dev), torch.from_numpy(a).to(dev)
     ix.build_buckets(Xd, ad, cfg.buckets)
@@ -126,7 +128,7 @@ def test_full_size_build_properties_and_recall():
     qd, lod, hid = torch.from_numpy(q).to(dev), torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)
     ids = torch.empty((len(q), 10), dtype=torch.int32, device=dev)
     dist = torch.empty((len(q), 10), dtype=torch.float32, device=dev)
-    ix.set_param("visited_cap", 1400); ix.set_param("n_seeds", 256); ix.set_param("search_width", 4)
+    ix.set_param("visited_cap", 1400); ix.set_param("n_seeds", 64); ix.set_param("search_width", 2)
     ix.search_range(qd, lod, hid, 10, 32, ids, dist)
     gt = GT.exact_filtered_knn(Xd, ad, qd, lod, hid, 10)
     rec = GT.recall(ids, gt)
