@@ -206,7 +206,7 @@ def main():
     achieved = bytes_per_launch / (avg_beam_ms * 1e-3) / 1e9
     traffic = None
     tpath = os.path.join(ROOT, "profiles", "traffic_beam_search_c2.json")
-    if os.path.exists(tpath) and args.workload == "c2" and not args.scale:
+    if os.path.exists(tpath) and args.workload == "c2" and not args.scale and abs(args.selectivity - 0.1) < 1e-9:
         try:
             tj = json.load(open(tpath))
             if list(tj.get("config", [])) == [chosen[0], chosen[1], chosen[2], max(chosen[3], chosen[1])]:
