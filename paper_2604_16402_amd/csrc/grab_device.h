@@ -27,36 +27,93 @@ __device__ __forceinline__ int wave_sum(int v) {
     return v;
 }
 
-// ---- a 64-entry queue held one key per lane, sorted and merged with lane exchanges ----------
-__device__ __forceinline__ u64 shfl64(u64 k, int src) {
-    return ((u64)(uint32_t)__shfl((int)(k >> 32), src) << 32) | (u64)(uint32_t)__shfl((int)(k & 0xFFFFFFFFull), src);
+// ---- lane exchanges that stay out of LDS ------------------------------------------------------
+// DPP moves cover the partners at distance 1, 2, 4 and 8 (quad permutes, the half-row mirror
+// followed by a quad reversal, a rotation by 8 inside a row of 16); the row and half-wave swaps
+// of gfx950 cover distance 16 and 32.  A dependent chain of these costs a few cycles per step
+// where a ds_bpermute round trip costs on the order of a hundred.
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
+}
+// value of lane (lane ^ J)
+template <int J>
+__device__ __forceinline__ uint32_t xchg32(uint32_t x, int lane) {
+    static_assert(J == 1 || J == 2 || J == 4 || J == 8 || J == 16 || J == 32, "partner distance");
+    if constexpr (J == 1) return dpp_u32<0xB1>(x);                    // quad_perm [1,0,3,2]
+    else if constexpr (J == 2) return dpp_u32<0x4E>(x);               // quad_perm [2,3,0,1]
+    else if constexpr (J == 4) return dpp_u32<0x1B>(dpp_u32<0x141>(x));  // i -> 7-i, then reverse the quad
+    else if constexpr (J == 8) return dpp_u32<0x128>(x);              // row_ror:8
+    else if constexpr (J == 16) {
+        auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);  // odd rows of [0] <-> even rows of [1]
+        return (lane & 16) ? r[0] : r[1];
+    } else {
+        auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);  // upper half of [0] <-> lower half of [1]
+        return (lane & 32) ? r[0] : r[1];
+    }
+}
+template <int J>
+__device__ __forceinline__ u64 xchg64(u64 k, int lane) {
+    return ((u64)xchg32<J>((uint32_t)(k >> 32), lane) << 32) | (u64)xchg32<J>((uint32_t)k, lane);
+}
+// value of lane src, the same src in every lane
+__device__ __forceinline__ u64 read_lane64(u64 k, int src) {
+    return ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(k >> 32), src) << 32) |
+           (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)k, src);
 }
 __device__ __forceinline__ u64 shfl_xor64(u64 k, int m) {
     return ((u64)(uint32_t)__shfl_xor((int)(k >> 32), m) << 32) | (u64)(uint32_t)__shfl_xor((int)(k & 0xFFFFFFFFull), m);
 }
-// ascending bitonic sort of the keys of lanes [0,P); lanes beyond hold SENT and stay put
-__device__ __forceinline__ u64 sort_lanes(u64 key, int P, int lane) {
-    for (int k = 2; k <= P; k <<= 1)
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            u64 o = shfl_xor64(key, j);
-            bool take_min = ((lane & j) == 0) == ((lane & k) == 0);
-            bool less = key < o;
-            key = (less == take_min) ? key : o;
-        }
+
+// value of lane (lane ^ (K-1)): the mirror image inside aligned blocks of K lanes
+template <int K>
+__device__ __forceinline__ uint32_t mirror32(uint32_t x, int lane) {
+    if constexpr (K == 2) return dpp_u32<0xB1>(x);
+    else if constexpr (K == 4) return dpp_u32<0x1B>(x);           // quad_perm [3,2,1,0]
+    else if constexpr (K == 8) return dpp_u32<0x141>(x);          // row_half_mirror
+    else if constexpr (K == 16) return dpp_u32<0x140>(x);         // row_mirror
+    else if constexpr (K == 32) return xchg32<16>(dpp_u32<0x140>(x), lane);
+    else return xchg32<32>(xchg32<16>(dpp_u32<0x140>(x), lane), lane);
+}
+template <int K>
+__device__ __forceinline__ u64 mirror64(u64 k, int lane) {
+    return ((u64)mirror32<K>((uint32_t)(k >> 32), lane) << 32) | (u64)mirror32<K>((uint32_t)k, lane);
+}
+__device__ __forceinline__ u64 reverse64(u64 k, int lane) { return mirror64<64>(k, lane); }
+
+// compare-exchange with the lane at distance J: the lower lane of a pair keeps the smaller key
+template <int J>
+__device__ __forceinline__ u64 cmpx(u64 key, int lane) {
+    const u64 o = xchg64<J>(key, lane);
+    return ((key < o) == ((lane & J) == 0)) ? key : o;
+}
+// the steps J, J/2, ..., 1 that sort a bitonic run of 2J lanes ascending
+template <int J>
+__device__ __forceinline__ u64 bitonic_merge(u64 key, int lane) {
+    key = cmpx<J>(key, lane);
+    if constexpr (J > 1) key = bitonic_merge<J / 2>(key, lane);
     return key;
 }
-// queue (sorted, one key per lane) <- the 64 smallest of queue and ck (sorted), cut to beam
-__device__ __forceinline__ u64 merge_lanes(u64 qk, u64 ck, int beam, int lane) {
-    u64 r = shfl64(ck, 63 - lane);
-    u64 m = qk < r ? qk : r;
-#pragma unroll
-    for (int j = 32; j > 0; j >>= 1) {
-        u64 o = shfl_xor64(m, j);
-        bool take_min = (lane & j) == 0;
-        bool less = m < o;
-        m = (less == take_min) ? m : o;
-    }
-    return lane < beam ? m : SENT;
+// two sorted runs of K/2 lanes -> one sorted run of K lanes.  The first step pairs each lane with
+// its mirror image in the block, so every step orders its pair the same way and the whole
+// network needs one lane mask per distance
+template <int K>
+__device__ __forceinline__ u64 merge_runs(u64 key, int lane) {
+    const u64 o = mirror64<K>(key, lane);
+    key = ((key < o) == ((lane & (K / 2)) == 0)) ? key : o;
+    if constexpr (K >= 4) key = bitonic_merge<K / 4>(key, lane);
+    return key;
+}
+// ascending sort of the keys of lanes [0,P), P a power of two (the same in every lane); lanes
+// beyond hold SENT and stay put
+__device__ __forceinline__ u64 sort_lanes(u64 key, int P, int lane) {
+    key = merge_runs<2>(key, lane);
+    if (P >= 4) key = merge_runs<4>(key, lane);
+    if (P >= 8) key = merge_runs<8>(key, lane);
+    if (P >= 16) key = merge_runs<16>(key, lane);
+    if (P >= 32) key = merge_runs<32>(key, lane);
+    if (P >= 64) key = merge_runs<64>(key, lane);
+    return key;
 }
 
 // The candidate queue: M keys per lane in registers, position p = 64*r + lane of register r,
@@ -74,7 +131,7 @@ struct LaneQueue {
     // min against the reversed newcomers turns the sorted queue into a bitonic sequence that holds
     // exactly the survivors; a bitonic merge sorts it again
     __device__ __forceinline__ void merge(u64 ck, int beam, int lane) {
-        const u64 rv = shfl64(ck, 63 - lane);
+        const u64 rv = reverse64(ck, lane);
         k[M - 1] = k[M - 1] < rv ? k[M - 1] : rv;
 #pragma unroll
         for (int s = M / 2; s >= 1; s >>= 1)
@@ -86,15 +143,7 @@ struct LaneQueue {
                     k[r + s] = x < y ? y : x;
                 }
 #pragma unroll
-        for (int j = 32; j > 0; j >>= 1) {
-            const bool take_min = (lane & j) == 0;
-#pragma unroll
-            for (int r = 0; r < M; ++r) {
-                const u64 o = shfl_xor64(k[r], j);
-                const bool less = k[r] < o;
-                k[r] = (less == take_min) ? k[r] : o;
-            }
-        }
+        for (int r = 0; r < M; ++r) k[r] = bitonic_merge<32>(k[r], lane);
 #pragma unroll
         for (int r = 0; r < M; ++r)
             if (64 * r + lane >= beam) k[r] = SENT;
@@ -105,7 +154,7 @@ struct LaneQueue {
 #pragma unroll
         for (int r = 0; r < M; ++r)
             if ((p >> 6) == r) t = k[r];
-        return shfl64(t, p & 63);
+        return read_lane64(t, p & 63);
     }
 };
 

@@ -204,8 +204,9 @@ __device__ __forceinline__ bool visited_insert(uint32_t *tab, uint32_t H, uint32
 // New keys wait in a 64-entry LDS buffer, are sorted with a lane-exchange bitonic network sized
 // to their number and merged into the queue.  A new key is dropped at once when it is not
 // smaller than the worst key of a full queue: it could never enter.
+// (four waves per SIMD wherever the registers of the gathered rows leave room for it)
 template <int NCH, int M>
-__global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
+__global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_search(BeamArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int D = NCH * 32;
     constexpr int R = EvalShape<NCH>::R;
@@ -235,7 +236,7 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
     int cnt = 0;      // keys waiting in C
 
     // merge the cnt keys waiting in C into the queue
-    auto flush = [&]() {
+    auto flush = [&]() __attribute__((always_inline)) {
         if (cnt == 0) return;
         int P = 2;
         while (P < cnt) P <<= 1;
@@ -247,7 +248,7 @@ __global__ __launch_bounds__(64) void k_beam_search(BeamArgs a) {
         __syncthreads();
     };
     // ComputeDistance + UpdateQueue for the n slots in L
-    auto evaluate = [&](int n) {
+    auto evaluate = [&](int n) __attribute__((always_inline)) {
         const int sub = lane & 7;
         for (int base = 0; base < n; base += 8 * R) {
             if (cnt + 8 * R > 64) flush();
