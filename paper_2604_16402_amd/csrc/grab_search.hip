@@ -210,6 +210,7 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int D = NCH * 32;
     constexpr int R = EvalShape<NCH>::R;
+    constexpr int NV = 4;
     const int lane = threadIdx.x;
     const int64_t q = blockIdx.x;
     const int H = a.hsize;
@@ -321,23 +322,32 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
             // GatherNeighbors + pre-check + visited test, all parents' rows at once
             const int total = np * a.K;
             int n_c = 0;
-            for (int e0 = 0; e0 < total; e0 += 64) {
-                const int e = e0 + lane;
-                uint32_t v = GRAB_EMPTY;
-                if (e < total) {
-                    uint32_t pi = ((uint32_t)e * recipK) >> 16;
-                    uint32_t j = (uint32_t)e - pi * (uint32_t)a.K;
-                    v = a.A[(size_t)par[pi] * a.K + j];
+            for (int e0 = 0; e0 < total; e0 += 64 * NV) {
+                uint32_t nv[NV];   // the adjacency loads of up to 64*NV entries are in flight together
+#pragma unroll
+                for (int u = 0; u < NV; ++u) {
+                    const int e = e0 + 64 * u + lane;
+                    nv[u] = GRAB_EMPTY;
+                    if (e < total) {
+                        uint32_t pi = ((uint32_t)e * recipK) >> 16;
+                        uint32_t j = (uint32_t)e - pi * (uint32_t)a.K;
+                        nv[u] = a.A[(size_t)par[pi] * a.K + j];
+                    }
                 }
-                bool tail = false, ok = false;
-                const bool live = v != GRAB_EMPTY;
-                if (live) ok = precheck(p, v, a.attr, lo, hi, tail);
-                c_rej += __popcll(__ballot(live && !ok));
-                c_tail += __popcll(__ballot(tail));
-                bool fresh = ok && visited_insert(hash, (uint32_t)H, v);
-                u64 m = __ballot(fresh);
-                if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
-                n_c += __popcll(m);
+#pragma unroll
+                for (int u = 0; u < NV; ++u) {
+                    if (e0 + 64 * u >= total) break;
+                    const uint32_t v = nv[u];
+                    bool tail = false, ok = false;
+                    const bool live = v != GRAB_EMPTY;
+                    if (live) ok = precheck(p, v, a.attr, lo, hi, tail);
+                    c_rej += __popcll(__ballot(live && !ok));
+                    c_tail += __popcll(__ballot(tail));
+                    bool fresh = ok && visited_insert(hash, (uint32_t)H, v);
+                    u64 m = __ballot(fresh);
+                    if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
+                    n_c += __popcll(m);
+                }
             }
             __syncthreads();
             c_vis += n_c; c_evals += n_c;
