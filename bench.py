@@ -29,7 +29,7 @@ METRIC = "filtered queries/sec at recall@10>=0.95 (1M x 128 fp32, 10% range), % 
 
 # (beam, n_seeds, search_width, visited_cap)
 GRID = [
-    (32, 64, 2, 1400), (32, 48, 1, 1400), (32, 128, 2, 1400), (32, 96, 4, 1400), (24, 128, 4, 1400), (24, 192, 4, 1400),
+    (32, 64, 2, 1400), (28, 96, 1, 1400), (28, 96, 3, 1400), (28, 128, 2, 1400), (32, 48, 1, 1400), (32, 128, 2, 1400), (32, 96, 4, 1400), (24, 128, 4, 1400), (24, 192, 4, 1400),
     (32, 32, 1, 1400), (32, 256, 4, 1400), (48, 64, 2, 1400), (48, 128, 4, 1400), (64, 64, 2, 1400), (64, 128, 4, 1400),
     (64, 64, 1, 2800), (64, 128, 2, 2800), (64, 256, 4, 4000), (96, 128, 2, 2800), (96, 256, 4, 4000), (128, 128, 2, 4000),
     (128, 256, 4, 2800), (128, 512, 4, 4000), (64, 1024, 4, 2000), (96, 1024, 4, 2400), (128, 768, 4, 2400),
