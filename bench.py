@@ -33,6 +33,7 @@ GRID = [
     (32, 32, 1, 1400), (32, 256, 4, 1400), (48, 64, 2, 1400), (48, 128, 4, 1400), (64, 64, 2, 1400), (64, 128, 4, 1400),
     (64, 64, 1, 2800), (64, 128, 2, 2800), (64, 256, 4, 4000), (96, 128, 2, 2800), (96, 256, 4, 4000), (128, 128, 2, 4000),
     (128, 256, 4, 2800), (128, 512, 4, 4000), (64, 1024, 4, 2000), (96, 1024, 4, 2400), (128, 768, 4, 2400),
+    (48, 1280, 4, 3200), (48, 1408, 4, 2800), (64, 1152, 4, 3200), (64, 1280, 4, 2400), (64, 1280, 4, 3200),
     (128, 1024, 4, 2400), (128, 1024, 4, 4000), (256, 2048, 4, 8000),
 ]
 

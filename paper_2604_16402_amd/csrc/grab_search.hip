@@ -187,17 +187,51 @@ __device__ __forceinline__ bool precheck(const QueryPlan &p, uint32_t v, const i
     return false;
 }
 
-// exact visited set: open addressing over H words (any multiple of 64, at most 80 % full when the
-// capacity rule stops the search), linear probing, one LDS compare-and-swap per probe
-__device__ __forceinline__ bool visited_insert(uint32_t *tab, uint32_t H, uint32_t v) {
-    uint32_t h = (uint32_t)(((u64)(v * 0x9E3779B1u) * (u64)H) >> 32);
-    for (uint32_t probe = 0; probe < H; ++probe) {
-        uint32_t old = atomicCAS(&tab[h], GRAB_EMPTY, v);
-        if (old == GRAB_EMPTY) return true;
-        if (old == v) return false;
-        h = h + 1 == H ? 0u : h + 1;
+// Pre-check and exact visited set for NV slots per lane at once.  The visited set is open
+// addressing over H words of LDS (any multiple of 64, at most 80 % full when the capacity rule
+// stops the search) with linear probing, one compare-and-swap per probe; the NV probe sequences
+// of a lane advance together, so a round costs one LDS round trip, not NV.  Slots that pass both
+// tests are appended to L (entry order, lanes ascending); returns the new length of L.
+// Which copy of a slot that occurs twice is the one admitted does not matter: queue keys are
+// unique per slot and the queue is a set.
+template <int NV>
+__device__ __forceinline__ int admit(const QueryPlan &p, const uint32_t (&v)[NV], const int32_t *__restrict__ attr,
+                                     int lo, int hi, uint32_t *tab, uint32_t H, uint32_t *L, int n_c, u64 lt_mask,
+                                     uint32_t &c_rej, uint32_t &c_tail) {
+    bool pend[NV], fresh[NV];
+    uint32_t h[NV];
+    bool any = false;
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        bool tail = false, ok = false;
+        const bool live = v[u] != GRAB_EMPTY;
+        if (live) ok = precheck(p, v[u], attr, lo, hi, tail);
+        c_rej += __popcll(__ballot(live && !ok));
+        c_tail += __popcll(__ballot(tail));
+        pend[u] = ok;
+        fresh[u] = false;
+        any |= ok;
+        h[u] = (uint32_t)(((u64)(v[u] * 0x9E3779B1u) * (u64)H) >> 32);
     }
-    return false;
+    for (uint32_t probe = 0; probe < H && __ballot(any) != 0; ++probe) {
+        any = false;
+#pragma unroll
+        for (int u = 0; u < NV; ++u)
+            if (pend[u]) {
+                const uint32_t old = atomicCAS(&tab[h[u]], GRAB_EMPTY, v[u]);
+                fresh[u] = old == GRAB_EMPTY;
+                pend[u] = old != GRAB_EMPTY && old != v[u];
+                h[u] = h[u] + 1 == H ? 0u : h[u] + 1;
+                any |= pend[u];
+            }
+    }
+#pragma unroll
+    for (int u = 0; u < NV; ++u) {
+        const u64 m = __ballot(fresh[u]);
+        if (fresh[u]) L[n_c + __popcll(m & lt_mask)] = v[u];
+        n_c += __popcll(m);
+    }
+    return n_c;
 }
 
 // One query per wavefront; the queue of up to 64*M keys stays in registers for the whole search.
@@ -278,16 +312,15 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
         for (int s0 = 0; s0 < p.n_seeds; s0 += a.maxc) {
             const int lim = min(p.n_seeds, s0 + a.maxc);
             int n_c = 0;
-            for (int e0 = s0; e0 < lim; e0 += 64) {
-                const int e = e0 + lane;
-                uint32_t v = e < lim ? sd[e] : GRAB_EMPTY;
-                bool tail = false, ok = false;
-                if (v != GRAB_EMPTY) ok = precheck(p, v, a.attr, lo, hi, tail);
-                c_tail += __popcll(__ballot(tail));
-                bool fresh = ok && visited_insert(hash, (uint32_t)H, v);
-                u64 m = __ballot(fresh);
-                if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
-                n_c += __popcll(m);
+            for (int e0 = s0; e0 < lim; e0 += 64 * NV) {
+                uint32_t sv[NV];
+#pragma unroll
+                for (int u = 0; u < NV; ++u) {
+                    const int e = e0 + 64 * u + lane;
+                    sv[u] = e < lim ? sd[e] : GRAB_EMPTY;
+                }
+                uint32_t unused = 0;
+                n_c = admit<NV>(p, sv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, unused, c_tail);
             }
             __syncthreads();
             c_vis += n_c; c_evals += n_c; c_seed += n_c;
@@ -334,20 +367,7 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
                         nv[u] = a.A[(size_t)par[pi] * a.K + j];
                     }
                 }
-#pragma unroll
-                for (int u = 0; u < NV; ++u) {
-                    if (e0 + 64 * u >= total) break;
-                    const uint32_t v = nv[u];
-                    bool tail = false, ok = false;
-                    const bool live = v != GRAB_EMPTY;
-                    if (live) ok = precheck(p, v, a.attr, lo, hi, tail);
-                    c_rej += __popcll(__ballot(live && !ok));
-                    c_tail += __popcll(__ballot(tail));
-                    bool fresh = ok && visited_insert(hash, (uint32_t)H, v);
-                    u64 m = __ballot(fresh);
-                    if (fresh) L[n_c + __popcll(m & lt_mask)] = v;
-                    n_c += __popcll(m);
-                }
+                n_c = admit<NV>(p, nv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, c_rej, c_tail);
             }
             __syncthreads();
             c_vis += n_c; c_evals += n_c;

@@ -11,6 +11,7 @@ def exact_filtered_knn(vectors, attrs, queries, lo, hi, k: int, metric: int = 0,
     Returns ids[nq,k] (int64, -1 where fewer than k objects satisfy the range)."""
     import torch
     n = vectors.shape[0]
+    chunk = max(1, min(chunk, (1 << 29) // max(1, n)))   # score blocks stay under 2 GiB
     out = torch.full((queries.shape[0], k), -1, dtype=torch.int64, device=vectors.device)
     vn = (vectors * vectors).sum(1) if metric == 0 else None
     for s in range(0, queries.shape[0], chunk):
