@@ -210,15 +210,20 @@ def main():
     if os.path.exists(tpath) and args.workload == "c2" and not args.scale and abs(args.selectivity - 0.1) < 1e-9:
         try:
             tj = json.load(open(tpath))
-            if list(tj.get("config", [])) == [chosen[0], chosen[1], chosen[2], max(chosen[3], chosen[1])]:
-                traffic = tj.get("hbm_bytes_per_launch")
+            for ent in tj.get("settings", []):
+                if list(ent.get("config", [])) == [chosen[0], chosen[1], chosen[2], chosen[3]]:
+                    traffic = ent.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
+    # what the device sustains for random whole rows of this index (no search logic at all)
+    g_ms, g_bytes = ix.probe_gather(65536, 40)
+    gather_gbs = g_bytes / (g_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_beam_search<%d,%d>" % (cfg.dim // 32, 1 if chosen[0] <= 64 else 2 if chosen[0] <= 128 else 4 if chosen[0] <= 256 else 8), "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
                 "bytes_per_launch": bytes_per_launch, "avg_kernel_ms": round(avg_beam_ms, 4),
                 "select_kernel_ms": round(float(np.mean(select_ms)), 4),
-                "evals_per_query": round(float(ctr[:, 2].mean()), 1), "parents_per_query": round(float(ctr[:, 1].mean()), 1)}
+                "evals_per_query": round(float(ctr[:, 2].mean()), 1), "parents_per_query": round(float(ctr[:, 1].mean()), 1),
+                "random_row_gather_gbs": round(gather_gbs, 1)}
 
     # ---- CPU baseline: the oracle as it stands, all host cores, same inputs and graph
     cpu = None

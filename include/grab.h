@@ -182,6 +182,17 @@ grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq);
  * finish.  GRAB_ESTATE if profiling was off. */
 grab_status grab_get_timing(grab_index *ix, float ms[2]);
 
+/* Measurement aid (no passage of the paper: it prices the memory system, not the method).
+ * `waves` wavefronts each read `batches` batches of whole vector rows of the index at
+ * pseudo-random slots, eight lanes per row as the distance evaluation of Algorithm 2 reads them,
+ * and do nothing else.  *ms (host) = duration of that launch measured with HIP events on the
+ * index's stream, *bytes (host) = rows read x row size.  bytes / ms is the rate the device
+ * sustains for random rows of this size over this index's footprint: the practical ceiling of
+ * the gathered distance evaluation, to be read beside the HBM peak.  Waits for the launch.
+ * Needs grab_build_buckets before it; invalidates grab_get_timing of an earlier search.
+ * waves in 1..2^24, batches in 1..65536, else GRAB_EINVAL. */
+grab_status grab_probe_gather(grab_index *ix, int64_t waves, int32_t batches, float *ms, double *bytes);
+
 #ifdef __cplusplus
 }
 #endif

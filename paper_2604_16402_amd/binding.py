@@ -25,7 +25,8 @@ EMPTY = 0xFFFFFFFF
 
 EXPORTS = ["grab_create", "grab_destroy", "grab_last_error", "grab_build_buckets", "grab_load_graph",
            "grab_build_graph", "grab_search_range", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
-           "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing"]
+           "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing",
+           "grab_probe_gather"]
 
 _lib = None
 
@@ -70,6 +71,7 @@ def load_library() -> ctypes.CDLL:
     lib.grab_select_range.argtypes = [vp, vp, vp, i64, i32, vp, vp]
     lib.grab_get_counters.argtypes = [vp, vp, i64]
     lib.grab_get_timing.argtypes = [vp, vp]
+    lib.grab_probe_gather.argtypes = [vp, i64, i32, vp, vp]
     for name in EXPORTS:
         if name not in ("grab_destroy", "grab_last_error"):
             getattr(lib, name).restype = ctypes.c_int
@@ -206,6 +208,13 @@ class Index:
         out = np.empty((nq, 8), dtype=np.uint32)
         self._check(self._lib.grab_get_counters(self._h, out.ctypes.data, nq))
         return out
+
+    def probe_gather(self, waves: int = 65536, batches: int = 40):
+        """(ms, bytes) of a launch that only reads random vector rows of the index."""
+        ms = np.zeros(1, dtype=np.float32)
+        nbytes = np.zeros(1, dtype=np.float64)
+        self._check(self._lib.grab_probe_gather(self._h, waves, batches, ms.ctypes.data, nbytes.ctypes.data))
+        return float(ms[0]), float(nbytes[0])
 
     def get_timing(self):
         """(select_ms, beam_ms) of the last search; needs set_param("profile", 1) before it."""

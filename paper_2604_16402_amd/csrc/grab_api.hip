@@ -401,6 +401,28 @@ grab_status grab_get_timing(grab_index *ix, float ms[2]) {
     return GRAB_OK;
 }
 
+grab_status grab_probe_gather(grab_index *ix, int64_t waves, int32_t batches, float *ms, double *bytes) {
+    if (!ix) return GRAB_EINVAL;
+    if (!ms || !bytes) return grab_fail(ix, GRAB_EINVAL, "null argument");
+    if (!ix->X || ix->n_slots <= 0) return grab_fail(ix, GRAB_ESTATE, "no vectors loaded");
+    if (waves < 1 || waves > (1 << 24) || batches < 1 || batches > (1 << 16))
+        return grab_fail(ix, GRAB_EINVAL, "waves must lie in 1..2^24 and batches in 1..2^16");
+    grab_status st = grab_reserve(ix, ix->flags, 256);
+    if (st != GRAB_OK) return st;
+    for (int i = 0; i < 2; ++i)
+        if (!ix->ev[i]) GRAB_HIP(ix, hipEventCreate(&ix->ev[i]));
+    double b = 0;
+    if ((st = grab_launch_gather_probe(ix, waves, 1, reinterpret_cast<float *>(ix->flags.p), &b)) != GRAB_OK) return st;   // warm-up
+    GRAB_HIP(ix, hipEventRecord(ix->ev[0], ix->stream));
+    if ((st = grab_launch_gather_probe(ix, waves, batches, reinterpret_cast<float *>(ix->flags.p), &b)) != GRAB_OK) return st;
+    GRAB_HIP(ix, hipEventRecord(ix->ev[1], ix->stream));
+    GRAB_HIP(ix, hipEventSynchronize(ix->ev[1]));
+    GRAB_HIP(ix, hipEventElapsedTime(ms, ix->ev[0], ix->ev[1]));
+    ix->timed = false;   // the search events were reused
+    *bytes = b;
+    return GRAB_OK;
+}
+
 grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_t *attrs, int64_t m) {
     if (!ix) return GRAB_EINVAL;
     if (!ix->has_graph) return grab_fail(ix, GRAB_ESTATE, "no graph loaded");

@@ -119,6 +119,8 @@ struct SearchLaunch {
 };
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s);
 grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s);
+// measurement aid: `waves` wavefronts each read `batches` batches of random rows; *bytes = rows read x row size
+grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batches, float *sink, double *bytes);
 // append: the whole insertion for m objects already on the device; `proto` carries the search
 // parameters resolved for beam = append_beam
 // construction: fills ix->A (already allocated for kl+kr entries per slot)

@@ -428,7 +428,61 @@ inline int pow2_at_least(int x, int floor_) {
     return p;
 }
 
+// Measurement aid: every group of eight lanes reads whole rows of the index at pseudo-random
+// slots, with the access shape of eval_batch and nothing else to do.  Its rate is what the memory
+// system delivers for random rows of this size over this footprint, the practical ceiling of the
+// gathered distance evaluation.
+template <int NCH>
+__global__ __launch_bounds__(64) void k_gather_probe(const float *__restrict__ X, uint32_t n_slots, int batches,
+                                                     float *sink) {
+    constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R, D4 = NCH * 8;
+    const int lane = threadIdx.x, sub = lane & 7, grp = lane >> 3;
+    float acc = 0.f;
+    for (int it = 0; it < batches; ++it) {
+        uint32_t v[R];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const uint32_t h = mix32((blockIdx.x * 0x9E3779B1u) ^ ((uint32_t)((it * R + r) * 8 + grp) * 0x85EBCA6Bu));
+            v[r] = (uint32_t)(((u64)h * n_slots) >> 32);
+        }
+#pragma unroll
+        for (int c0 = 0; c0 < NCH; c0 += CB) {
+            float4 buf[R][CB];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v[r] * D4 + sub;
+#pragma unroll
+                for (int cc = 0; cc < CB; ++cc) buf[r][cc] = row[(c0 + cc) * 8];
+            }
+#pragma unroll
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int cc = 0; cc < CB; ++cc) acc += (buf[r][cc].x + buf[r][cc].y) + (buf[r][cc].z + buf[r][cc].w);
+        }
+    }
+    if (acc == 1.2345678e-30f) sink[0] = acc;   // keeps the loads alive; practically never taken
+}
+
+template <int NCH>
+grab_status launch_probe_t(grab_index *ix, int64_t waves, int32_t batches, float *sink, double *bytes) {
+    k_gather_probe<NCH><<<dim3((unsigned)waves), dim3(64), 0, ix->stream>>>(ix->X, (uint32_t)ix->n_slots, batches, sink);
+    GRAB_HIP(ix, hipGetLastError());
+    *bytes = (double)waves * batches * 8 * EvalShape<NCH>::R * (double)ix->dim * 4.0;
+    return GRAB_OK;
+}
+
 }  // namespace
+
+grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batches, float *sink, double *bytes) {
+    switch (ix->dim / 32) {
+#define GRAB_CASE(N) case N: return launch_probe_t<N>(ix, waves, batches, sink, bytes);
+        GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
+        GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
+#undef GRAB_CASE
+        default:
+            return grab_fail(ix, GRAB_EINVAL, "dim %d has no search kernel", ix->dim);
+    }
+}
 
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
     if (s.nq == 0) return GRAB_OK;

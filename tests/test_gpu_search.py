@@ -254,3 +254,22 @@ def test_wide_parameter_surface(torch_dev, dim, kl, kr, beam, width, seeds, vcap
     w = ora.search(q, lo, hi, 10, beam)
     assert np.array_equal(dist, w[1]) and np.array_equal(ids, w[0]) and np.array_equal(ctr, w[2])
     ix.close()
+
+
+def test_gather_probe_reports_rows_read(c1_small, torch_dev):
+    from paper_2604_16402_amd import binding
+    ix = _gpu_index(c1_small, torch_dev)
+    ms, nbytes = ix.probe_gather(1024, 4)
+    # 128-d rows: 4 rows per lane group in flight, 8 groups per wavefront
+    assert nbytes == 1024 * 4 * 8 * 4 * 128 * 4
+    assert ms > 0.0
+    with pytest.raises(binding.GrabError):
+        ix.probe_gather(0, 4)
+    with pytest.raises(binding.GrabError):
+        ix.probe_gather(16, 1 << 20)
+    # a search after the probe still matches the oracle (the probe shares the timing events)
+    q, lo, hi = c1_small["queries"][:50], c1_small["lo"][:50], c1_small["hi"][:50]
+    ids, dist, _ = _search_gpu(ix, torch_dev, q, lo, hi, 10, 64)
+    want_ids, want_dist, _ = c1_small["oracle"].search(q, lo, hi, 10, 64)
+    assert np.array_equal(ids, want_ids) and np.array_equal(dist, want_dist)
+    ix.close()
