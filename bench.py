@@ -27,8 +27,12 @@ sys.path.insert(0, ROOT)
 PEAK_HBM_GBS = 8000.0
 METRIC = "filtered queries/sec at recall@10>=0.95 (1M x 128 fp32, 10% range), % peak HBM BW"
 
-# (beam, n_seeds, search_width, visited_cap)
+# (beam, n_seeds, search_width, visited_cap[, max_iter]); max_iter 0 or absent = 2 * beam
 GRID = [
+    (32, 96, 2, 1400, 20), (32, 64, 2, 1400, 21), (32, 128, 2, 1400, 20), (36, 64, 2, 1400, 21), (32, 96, 3, 1400, 14),
+    (36, 96, 2, 1400, 21), (32, 64, 2, 1400, 23),
+    (32, 256, 4, 1400, 12), (40, 192, 6, 1400, 11), (32, 64, 1, 1400, 39), (32, 48, 1, 1400, 41), (36, 64, 1, 1400, 39),
+    (96, 128, 3, 2800, 36), (96, 128, 3, 2800, 38), (48, 1280, 6, 3200, 10), (48, 1280, 4, 3200, 14),
     (32, 64, 2, 1400), (28, 96, 1, 1400), (28, 96, 3, 1400), (28, 128, 2, 1400), (32, 48, 1, 1400), (32, 128, 2, 1400), (32, 96, 4, 1400), (24, 128, 4, 1400), (24, 192, 4, 1400),
     (32, 32, 1, 1400), (32, 256, 4, 1400), (48, 64, 2, 1400), (48, 128, 4, 1400), (64, 64, 2, 1400), (64, 128, 4, 1400),
     (64, 64, 1, 2800), (64, 128, 2, 2800), (64, 256, 4, 4000), (96, 128, 2, 2800), (96, 256, 4, 4000), (128, 128, 2, 4000),
@@ -51,7 +55,7 @@ def main():
     ap.add_argument("--selectivity", type=float, default=0.1,
                     help="range width as a fraction of the attribute domain; <= 0: log-uniform 0.1 %%..100 %%")
     ap.add_argument("--scale", type=int, default=0, help="shrink the workload to this many base vectors (debug)")
-    ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap: skip the grid")
+    ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap[,max_iter]: skip the grid")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--alpha", type=float, default=0.95,
                     help="dynamic workload: freshness bias of Eq. 3 (the paper's 0.4..0.6 is for SIFT; in this synthetic "
@@ -135,7 +139,8 @@ def main():
     dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
 
     def set_cfg(c):
-        beam, S, w, vc = c
+        beam, S, w, vc = c[:4]
+        ix.set_param("max_iter", c[4] if len(c) > 4 else 0)
         ix.set_param("visited_cap", max(vc, S))
         ix.set_param("n_seeds", S)
         ix.set_param("search_width", w)
@@ -166,7 +171,7 @@ def main():
             beam = set_cfg(c)
             sec = timed(beam, 20)
             rec = GT.recall(ids, gt)
-            log(f"[bench] grid beam={c[0]} seeds={c[1]} width={c[2]} visited_cap={c[3]}: recall@10={rec:.4f} {nq / sec:,.0f} q/s")
+            log(f"[bench] grid beam={c[0]} seeds={c[1]} width={c[2]} visited_cap={c[3]} max_iter={c[4] if len(c) > 4 else 0}: recall@10={rec:.4f} {nq / sec:,.0f} q/s")
             if rec >= 0.95 and (best is None or sec < 0.98 * best[0]):   # 2 % hysteresis: stable choice
                 best = (sec, c, rec)
         if best is None:
@@ -213,7 +218,7 @@ def main():
         try:
             tj = json.load(open(tpath))
             for ent in tj.get("settings", []):
-                if list(ent.get("config", [])) == [chosen[0], chosen[1], chosen[2], chosen[3]]:
+                if list(ent.get("config", [])) == list(chosen) + [0] * (5 - len(chosen)):
                     traffic = ent.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
@@ -235,7 +240,8 @@ def main():
         t0 = time.time()
         ora = O.Index(X, attrs, cfg.buckets, metric=cfg.metric)
         ora.load_graph(la, ra)
-        ora.params.update(search_width=chosen[2], n_seeds=chosen[1], visited_cap=max(chosen[3], chosen[1]))
+        ora.params.update(search_width=chosen[2], n_seeds=chosen[1], visited_cap=max(chosen[3], chosen[1]),
+                          max_iter=(chosen[4] if len(chosen) > 4 and chosen[4] > 0 else None))
         cores = min(O.max_threads(), os.cpu_count() or 1)
         log(f"[bench] oracle index ready in {time.time() - t0:.1f}s; timing on {cores} threads")
         sample = nq
@@ -263,6 +269,7 @@ def main():
                                f"{'Zipf(1.1)' if cfg.attr_dist == 'zipf' else 'uniform'} int attribute, {cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, "
                                f"{nq} queries, {(format(args.selectivity, '.0%') if args.selectivity > 0 else 'log-uniform 0.1%..100%')} range, k={k}",
                    "beam": chosen[0], "n_seeds": chosen[1], "search_width": chosen[2], "visited_cap": max(chosen[3], chosen[1]),
+                   "max_iter": (chosen[4] if len(chosen) > 4 and chosen[4] > 0 else 2 * chosen[0]),
                    "recall_at_10": round(chosen_recall, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "parity_vs_oracle": parity, "build": build,
         "hbm_frac_of_peak": round(achieved / PEAK_HBM_GBS, 4),
@@ -278,7 +285,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
     import torch
     from paper_2604_16402_amd import groundtruth as GT, workloads as W
     k = cfg.k
-    beam, S, w, vc = (int(x) for x in (args.config or "32,512,4,1400").split(","))
+    beam, S, w, vc = [int(x) for x in (args.config or "32,512,4,1400").split(",")][:4]
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     ix.set_param("alpha", args.alpha)
     ix.set_param("append_beam", args.append_beam)
