@@ -434,7 +434,7 @@ int oracle_max_threads(void) {
  *     j-th remote entry of every node of a bucket points into the same target bucket, so the new
  *     row keeps that structure: it is the online form of the remote wiring (Section 4.3 pass 2,
  *     "proximal" and "global" remote edges), found through graph locality instead of a scan.
- *     (The paper searches remote candidates in the "global scope"; nearest-anywhere candidates
+ *     (Section 4.4 has the candidate search also look outside the target bucket; nearest-anywhere candidates
  *     gave new nodes remote edges into arbitrary far buckets, which a range filter rejects, and
  *     recall of the dynamic workload decayed with every batch.)
  *  5. Reverse requests: one per written edge q->v: (v, kind, dist(v,q), q).  Sorted by
