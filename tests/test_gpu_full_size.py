@@ -29,19 +29,22 @@ def c2_full():
     return dict(cfg=cfg, X=X, attrs=a, q=q, ix=ix, ora=ora, dev=dev, Xd=Xd, ad=ad, GT=GT)
 
 
-@pytest.mark.parametrize("sel,beam,seeds,width,vcap", [
-    (0.1, 32, 512, 4, 1400),     # the launch configuration bench.py times
-    (0.1, 64, 64, 1, 2800),      # library defaults
-    (0.01, 64, 512, 1, 1400),
-    (0.5, 128, 1024, 4, 4000),
+@pytest.mark.parametrize("sel,beam,seeds,width,vcap,max_iter", [
+    (0.1, 32, 96, 2, 1400, 20),      # the launch configuration bench.py times
+    (0.1, 28, 96, 3, 1400, 0),       # its best setting without an iteration cap
+    (0.1, 64, 64, 1, 2800, 0),       # library defaults
+    (0.01, 32, 256, 4, 1400, 12),
+    (0.5, 96, 128, 3, 2800, 36),
+    (0.5, 128, 1024, 4, 4000, 0),
 ])
-def test_full_size_matches_oracle(c2_full, sel, beam, seeds, width, vcap):
+def test_full_size_matches_oracle(c2_full, sel, beam, seeds, width, vcap, max_iter):
     import torch
     c = c2_full
     cfg, ix, ora, dev = c["cfg"], c["ix"], c["ora"], c["dev"]
     lo, hi = W.ranges(cfg, sel)
     ix.set_param("visited_cap", vcap); ix.set_param("n_seeds", seeds); ix.set_param("search_width", width)
-    ora.params.update(visited_cap=vcap, n_seeds=seeds, search_width=width)
+    ix.set_param("max_iter", max_iter)
+    ora.params.update(visited_cap=vcap, n_seeds=seeds, search_width=width, max_iter=max_iter or None)
     nq = len(c["q"])
     ids = torch.empty((nq, 10), dtype=torch.int32, device=dev)
     dist = torch.empty((nq, 10), dtype=torch.float32, device=dev)
@@ -66,7 +69,7 @@ def test_full_size_matches_oracle(c2_full, sel, beam, seeds, width, vcap):
     # the fp32 GPU ground truth agrees with the float64 exhaustive answer up to near-ties
     agree = np.mean([len(np.intersect1d(x, y)) / 10 for x, y in zip(gt.cpu().numpy()[sample], cpu_gt.astype(np.int64))])
     assert agree >= 0.998, agree
-    if (sel, beam) == (0.1, 32):
+    if (sel, beam) in ((0.1, 32), (0.1, 28)):
         assert rec >= 0.95, rec
 
 
@@ -110,9 +113,11 @@ def test_high_dimensional_config_matches_oracle():
     # 1M x 960 fp32, degree 48+8, 10 % ranges, beam 128 (30 lines per row, query staged in LDS)
     cfg, ix, ora, X, a, q, Xd, ad, dev, GT = _full_pair("c3")
     lo, hi = W.ranges(cfg, 0.1)
-    for beam, seeds, width, vcap in [(128, 0, 1, 2800), (64, 256, 4, 1400)]:
+    # the last setting is the one bench.py times on this workload
+    for beam, seeds, width, vcap, max_iter in [(128, 0, 1, 2800, 0), (64, 256, 4, 1400, 0), (32, 64, 1, 1400, 39)]:
         ix.set_param("visited_cap", vcap); ix.set_param("n_seeds", seeds); ix.set_param("search_width", width)
-        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width)
+        ix.set_param("max_iter", max_iter)
+        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width, max_iter=max_iter or None)
         ids, qd, lod, hid = _compare(cfg, ix, ora, q, lo, hi, beam, dev)
     gt = GT.exact_filtered_knn(Xd, ad, qd, lod, hid, 10, cfg.metric, chunk=256)
     assert GT.recall(ids, gt) > 0.95
@@ -125,9 +130,11 @@ def test_ten_million_inner_product_zipf_config_matches_oracle():
     # 100,000 queries is compared (the oracle and the index are at full size)
     cfg, ix, ora, X, a, q, Xd, ad, dev, GT = _full_pair("c4", n_queries=20_000)
     lo, hi = W.ranges(cfg, None, count=20_000)
-    for beam, seeds, width, vcap in [(128, 0, 1, 2800), (128, 1024, 4, 4000)]:
+    # the second setting is the one bench.py times on this workload
+    for beam, seeds, width, vcap, max_iter in [(128, 0, 1, 2800, 0), (48, 1280, 6, 3200, 10), (128, 1024, 4, 4000, 0)]:
         ix.set_param("visited_cap", vcap); ix.set_param("n_seeds", seeds); ix.set_param("search_width", width)
-        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width)
+        ix.set_param("max_iter", max_iter)
+        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width, max_iter=max_iter or None)
         ids, qd, lod, hid = _compare(cfg, ix, ora, q, lo, hi, beam, dev)
     got = ids.cpu().numpy().view(np.uint32)
     live = got != 0xFFFFFFFF
