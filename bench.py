@@ -160,6 +160,7 @@ def main():
 
     # ---- pick the fastest setting with Recall@10 >= 0.95 (Section 5.2 protocol)
     if args.config:
+        sweep = None
         chosen = tuple(int(x) for x in args.config.split(","))
         beam = set_cfg(chosen)
         run_once(beam)
@@ -167,11 +168,13 @@ def main():
         chosen_recall = GT.recall(ids, gt)
     else:
         best = None
+        sweep = []
         for c in GRID:
             beam = set_cfg(c)
             sec = timed(beam, 20)
             rec = GT.recall(ids, gt)
             log(f"[bench] grid beam={c[0]} seeds={c[1]} width={c[2]} visited_cap={c[3]} max_iter={c[4] if len(c) > 4 else 0}: recall@10={rec:.4f} {nq / sec:,.0f} q/s")
+            sweep.append([*c[:4], c[4] if len(c) > 4 else 0, round(rec, 4), round(nq / sec, 0)])
             if rec >= 0.95 and (best is None or sec < 0.98 * best[0]):   # 2 % hysteresis: stable choice
                 best = (sec, c, rec)
         if best is None:
@@ -272,6 +275,8 @@ def main():
                    "max_iter": (chosen[4] if len(chosen) > 4 and chosen[4] > 0 else 2 * chosen[0]),
                    "recall_at_10": round(chosen_recall, 4)},
         "roofline": roofline, "cpu_baseline": cpu, "parity_vs_oracle": parity, "build": build,
+        # every swept setting: [beam, n_seeds, search_width, visited_cap, max_iter (0 = 2 x beam), recall@10, queries/s]
+        "sweep": sweep,
         "hbm_frac_of_peak": round(achieved / PEAK_HBM_GBS, 4),
     }
     ix.close()
@@ -324,8 +329,11 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
     # connectivity of the grown graph (Section 5.4's diagnostic)
     from paper_2604_16402_amd import binding, diagnostics
     _, _, slot2id = ix.get_layout()
-    scc = diagnostics.strong_components(ix.get_graph(), slot2id != 0xFFFFFFFF)
-    log(f"[bench] strongly connected components after the appends: {scc}")
+    final_adj = ix.get_graph()
+    scc = diagnostics.strong_components(final_adj, slot2id != 0xFFFFFFFF)
+    n_orphans = diagnostics.orphans(final_adj, slot2id != 0xFFFFFFFF)
+    del final_adj
+    log(f"[bench] after the appends: {scc} strongly connected components, {n_orphans} objects without an in-edge")
     # context: the same final data set bulk-built by the harness, searched with the same setting
     ref = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
     ref.build_buckets(allX, alla, cfg.buckets)
@@ -349,7 +357,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
                       "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width,
                       "alpha": args.alpha},
            "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
-           "strong_components_final": scc, "bulk_rebuilt_reference_final": rebuilt, "build": build}
+           "strong_components_final": scc, "orphans_final": n_orphans, "bulk_rebuilt_reference_final": rebuilt, "build": build}
     ix.close()
     print(json.dumps(out), flush=True)
 

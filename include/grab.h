@@ -182,6 +182,35 @@ grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq);
  * finish.  GRAB_ESTATE if profiling was off. */
 grab_status grab_get_timing(grab_index *ix, float ms[2]);
 
+/* ---- float attributes ------------------------------------------------------------------------
+ * The filter of Section 3 is over a scalar attribute, and Section 5.1 draws it as a float in
+ * [0,1].  These calls take fp32 attributes and bounds.  Internally every float is replaced by
+ * its order-preserving int32 image (non-negative values: the IEEE-754 bit pattern; negative
+ * values: the bit pattern with its 31 magnitude bits flipped; -0 is stored as +0), so that
+ *     lo <= x <= hi   in float arithmetic   <=>   image(lo) <= image(x) <= image(hi),
+ * and everything else is the integer path: same layout, same results, same counters.  Read-back
+ * calls (grab_get_rows, the bucket table of grab_get_layout) report images; grab_attr_value turns
+ * an image back into the float.  An index is either integer- or float-keyed: use one family of
+ * calls throughout. */
+
+/* image of one float / float of one image; pure host functions */
+int32_t grab_attr_image(float x);
+float grab_attr_value(int32_t image);
+
+/* grab_build_buckets with attrs[n] fp32 (host or device).  GRAB_EINVAL if an attribute is NaN.
+ * Otherwise as grab_build_buckets on the images. */
+grab_status grab_build_buckets_f32(grab_index *ix, const float *vectors, const float *attrs, int64_t n,
+                                   int32_t n_buckets, int64_t n_cap);
+
+/* grab_search_range with closed ranges [lo[i], hi[i]] in fp32 (host or device).  A NaN bound makes
+ * that query's range empty (every result is padding).  Infinite bounds are allowed. */
+grab_status grab_search_range_f32(grab_index *ix, const float *queries, const float *lo, const float *hi, int64_t nq,
+                                  int32_t k, int32_t beam, uint32_t *out_ids, float *out_dist);
+
+/* grab_append_batch with attrs[m] fp32 (host or device).  GRAB_EINVAL, with nothing written, if an
+ * attribute is NaN. */
+grab_status grab_append_batch_f32(grab_index *ix, const float *vectors, const float *attrs, int64_t m);
+
 /* Measurement aid (no passage of the paper: it prices the memory system, not the method).
  * `waves` wavefronts each read `batches` batches of whole vector rows of the index at
  * pseudo-random slots, eight lanes per row as the distance evaluation of Algorithm 2 reads them,

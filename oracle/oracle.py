@@ -71,6 +71,35 @@ def distance(q: np.ndarray, v: np.ndarray, metric: int = L2SQ) -> np.float32:
 
 # ------------------------------------------------------------------------ bucketing (A1)
 
+def float_order_key(values) -> np.ndarray:
+    """int32 keys that order exactly like the fp32 values (the filter of Section 3 on a float
+    attribute, as in the experiments of Section 5.1, reduced to the integer case).
+
+    An IEEE-754 binary32 number is sign and magnitude: among non-negative numbers a larger
+    value has a larger bit pattern, among negative numbers a larger magnitude (a smaller
+    value) has a larger bit pattern.  So the key of x >= 0 is its bit pattern read as int32,
+    and the key of x < 0 is the bit pattern with the 31 magnitude bits inverted (still
+    negative, and now growing with x).  Both zeros get key 0.  NaN has no order: refused.
+    """
+    v = np.ascontiguousarray(values, dtype=np.float32)
+    if np.isnan(v).any():
+        raise ValueError("NaN has no place in an ordered attribute")
+    bits = v.view(np.int32).astype(np.int64)
+    key = np.where(bits >= 0, bits, bits ^ 0x7FFFFFFF)
+    key = np.where(v == 0.0, 0, key)
+    return key.astype(np.int32)
+
+
+def float_range_keys(lo, hi) -> Tuple[np.ndarray, np.ndarray]:
+    """Keys of closed float ranges; a range with a NaN bound holds nothing (keys 1 > 0)."""
+    lo = np.ascontiguousarray(lo, dtype=np.float32)
+    hi = np.ascontiguousarray(hi, dtype=np.float32)
+    bad = np.isnan(lo) | np.isnan(hi)
+    klo = float_order_key(np.where(bad, np.float32(0), lo))
+    khi = float_order_key(np.where(bad, np.float32(0), hi))
+    return np.where(bad, 1, klo).astype(np.int32), np.where(bad, 0, khi).astype(np.int32)
+
+
 def bucket_layout(attrs: np.ndarray, n_buckets: int, n_cap: int):
     """Section 4.2.1: partition into ``n_buckets`` disjoint ordered buckets by the scalar.
 

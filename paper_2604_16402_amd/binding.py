@@ -26,7 +26,8 @@ EMPTY = 0xFFFFFFFF
 EXPORTS = ["grab_create", "grab_destroy", "grab_last_error", "grab_build_buckets", "grab_load_graph",
            "grab_build_graph", "grab_search_range", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
            "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing",
-           "grab_probe_gather"]
+           "grab_probe_gather", "grab_attr_image", "grab_attr_value", "grab_build_buckets_f32", "grab_search_range_f32",
+           "grab_append_batch_f32"]
 
 _lib = None
 
@@ -72,11 +73,27 @@ def load_library() -> ctypes.CDLL:
     lib.grab_get_counters.argtypes = [vp, vp, i64]
     lib.grab_get_timing.argtypes = [vp, vp]
     lib.grab_probe_gather.argtypes = [vp, i64, i32, vp, vp]
+    lib.grab_attr_image.argtypes = [ctypes.c_float]
+    lib.grab_attr_value.argtypes = [i32]
+    lib.grab_build_buckets_f32.argtypes = [vp, vp, vp, i64, i32, i64]
+    lib.grab_search_range_f32.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp]
+    lib.grab_append_batch_f32.argtypes = [vp, vp, vp, i64]
     for name in EXPORTS:
-        if name not in ("grab_destroy", "grab_last_error"):
+        if name not in ("grab_destroy", "grab_last_error", "grab_attr_image", "grab_attr_value"):
             getattr(lib, name).restype = ctypes.c_int
+    lib.grab_attr_image.restype = i32
+    lib.grab_attr_value.restype = ctypes.c_float
     _lib = lib
     return lib
+
+
+def attr_image(x: float) -> int:
+    """Order-preserving int32 image the library stores for a float attribute."""
+    return int(load_library().grab_attr_image(ctypes.c_float(x)))
+
+
+def attr_value(image: int) -> float:
+    return float(load_library().grab_attr_value(int(image)))
 
 
 def _ptr(x, dtype, count: Optional[int] = None):
@@ -140,6 +157,13 @@ class Index:
         self._check(self._lib.grab_build_buckets(self._h, _ptr(vectors, np.float32, n * self.dim),
                                                  _ptr(attrs, np.int32, n), n, n_buckets, n if n_cap is None else n_cap))
 
+    def build_buckets_f32(self, vectors, attrs, n_buckets: int, n_cap: Optional[int] = None):
+        n = int(vectors.shape[0])
+        if int(vectors.shape[1]) != self.dim:
+            raise ValueError("vector dimension does not match the index")
+        self._check(self._lib.grab_build_buckets_f32(self._h, _ptr(vectors, np.float32, n * self.dim),
+                                                     _ptr(attrs, np.float32, n), n, n_buckets, n if n_cap is None else n_cap))
+
     def load_graph(self, local_adj, remote_adj):
         n = self.sizes()["n"]
         kl = int(local_adj.shape[1]) if local_adj is not None else 0
@@ -163,6 +187,23 @@ class Index:
                                                 _ptr(lo, np.int32, nq), _ptr(hi, np.int32, nq), nq, k, beam,
                                                 _ptr(out_ids, np.uint32, nq * k), _ptr(out_dist, np.float32, nq * k)))
         return out_ids, out_dist
+
+    def search_range_f32(self, queries, lo, hi, k: int, beam: int, out_ids=None, out_dist=None):
+        """search_range with fp32 range bounds."""
+        nq = int(queries.shape[0])
+        if out_ids is None:
+            out_ids = np.empty((nq, k), dtype=np.uint32)
+        if out_dist is None:
+            out_dist = np.empty((nq, k), dtype=np.float32)
+        self._check(self._lib.grab_search_range_f32(self._h, _ptr(queries, np.float32, nq * self.dim),
+                                                    _ptr(lo, np.float32, nq), _ptr(hi, np.float32, nq), nq, k, beam,
+                                                    _ptr(out_ids, np.uint32, nq * k), _ptr(out_dist, np.float32, nq * k)))
+        return out_ids, out_dist
+
+    def append_batch_f32(self, vectors, attrs):
+        m = int(vectors.shape[0])
+        self._check(self._lib.grab_append_batch_f32(self._h, _ptr(vectors, np.float32, m * self.dim),
+                                                    _ptr(attrs, np.float32, m), m))
 
     def append_batch(self, vectors, attrs):
         m = int(vectors.shape[0])

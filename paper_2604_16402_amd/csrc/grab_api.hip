@@ -94,7 +94,8 @@ void grab_destroy(grab_index *ix) {
     (void)hipStreamSynchronize(ix->stream);
     drop_layout(ix);
     DevBuf *bufs[] = {&ix->plans, &ix->seeds, &ix->counters, &ix->stage_q, &ix->stage_lo, &ix->stage_hi,
-                      &ix->stage_ids, &ix->stage_dist, &ix->stage_misc, &ix->flags};
+                      &ix->stage_ids, &ix->stage_dist, &ix->stage_misc, &ix->flags, &ix->stage_fa, &ix->stage_flo,
+                      &ix->stage_fhi, &ix->conv_a, &ix->conv_lo, &ix->conv_hi, &ix->attr_flag};
     for (DevBuf *b : bufs) free_buf(*b);
     for (DevBuf &b : ix->app) free_buf(b);
     for (hipEvent_t e : ix->ev)

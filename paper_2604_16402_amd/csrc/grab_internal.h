@@ -73,6 +73,8 @@ struct grab_index {
 
     // grow-only work buffers
     DevBuf plans, seeds, counters, stage_q, stage_lo, stage_hi, stage_ids, stage_dist, stage_misc, flags;
+    // float attributes: staged floats, their int32 images, the NaN flag
+    DevBuf stage_fa, stage_flo, stage_fhi, conv_a, conv_lo, conv_hi, attr_flag;
     int64_t last_nq = 0;
     std::vector<DevBuf> app;     // append's work arena
 

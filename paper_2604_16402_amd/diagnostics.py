@@ -18,3 +18,17 @@ def strong_components(adj_slots: np.ndarray, occupied: np.ndarray) -> int:
     g = csr_matrix((np.ones(int(keep.sum()), dtype=np.int8), (src[keep], dst[keep])), shape=(n, n))
     _, labels = connected_components(g, directed=True, connection="strong")
     return int(len(np.unique(labels[occupied])))
+
+
+def in_degrees(adj_slots: np.ndarray, occupied: np.ndarray) -> np.ndarray:
+    """In-degree of every slot (edges out of occupied slots only); 0 for an occupied slot means an
+    orphan: no search can reach it except as a seed (Section 5.3 tests that insertion leaves none)."""
+    n = adj_slots.shape[0]
+    rows = adj_slots[occupied]
+    dst = rows[rows != 0xFFFFFFFF].astype(np.int64)
+    return np.bincount(dst, minlength=n)
+
+
+def orphans(adj_slots: np.ndarray, occupied: np.ndarray) -> int:
+    """Occupied slots that no edge points to."""
+    return int(((in_degrees(adj_slots, occupied) == 0) & occupied).sum())

@@ -22,7 +22,7 @@ def lib():
 def test_every_declared_symbol_is_exported(lib):
     header = open(os.path.join(ROOT, "include", "grab.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(grab_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(grab_[a-z0-9_]+)\s*\(", header))
     assert {"grab_build_buckets", "grab_load_graph", "grab_search_range", "grab_append_batch"} <= declared
     for name in sorted(declared):
         assert hasattr(lib, name), f"{name} is declared in grab.h but not exported"
@@ -80,3 +80,19 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_attribute_image_is_the_oracle_order_key(lib):
+    # the two host functions need no device: compare them with the oracle's key on special values
+    # and random bit patterns, and check the round trip
+    from oracle import oracle as O
+    from paper_2604_16402_amd import binding as B
+    rng = np.random.default_rng(3)
+    v = np.concatenate([np.array([0.0, -0.0, 1e-45, -1e-45, 1.0, -1.0, 0.5, np.inf, -np.inf, 3.4028235e38, -3.4028235e38],
+                                 np.float32), rng.integers(-2**31, 2**31, 500).astype(np.int32).view(np.float32)])
+    v = v[~np.isnan(v)]
+    want = O.float_order_key(v)
+    for x, k in zip(v.tolist(), want.tolist()):
+        assert B.attr_image(x) == k, x
+        back = B.attr_value(k)
+        assert back == x and (x != 0.0 or np.signbit(np.float32(back)) == False)

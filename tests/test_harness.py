@@ -41,3 +41,7 @@ def test_strong_components_of_built_graphs():
     ring = np.array([[1], [2], [0], [0xFFFFFFFF]], np.uint32)
     assert diagnostics.strong_components(ring, np.array([True, True, True, True])) == 2
     assert diagnostics.strong_components(ring, np.array([True, True, True, False])) == 1
+    # nothing points to slot 3: one orphan while it is occupied
+    assert diagnostics.orphans(ring, np.array([True, True, True, True])) == 1
+    assert diagnostics.orphans(ring, np.array([True, True, True, False])) == 0
+    assert diagnostics.in_degrees(ring, np.array([True, True, True, True])).tolist()[3] == 0
