@@ -57,9 +57,7 @@ def main():
     ap.add_argument("--scale", type=int, default=0, help="shrink the workload to this many base vectors (debug)")
     ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap[,max_iter]: skip the grid")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
-    ap.add_argument("--alpha", type=float, default=0.95,
-                    help="dynamic workload: freshness bias of Eq. 3 (the paper's 0.4..0.6 is for SIFT; in this synthetic "
-                         "mixture neighbour distances concentrate and every value below 0.85 admits all newcomers)")
+    ap.add_argument("--alpha", type=float, default=0.6, help="dynamic workload: freshness bias of Eq. 3")
     ap.add_argument("--append-beam", type=int, default=128, help="dynamic workload: queue size of append's searches")
     ap.add_argument("--append-seeds", type=int, default=256, help="dynamic workload: seeds of append's candidate search")
     ap.add_argument("--append-width", type=int, default=2, help="dynamic workload: search width of append's candidate search")

@@ -136,8 +136,8 @@ grab_status grab_search_range(grab_index *ix, const float *queries, const int32_
  * remote entry j = nearest among the j-th remote entries of the candidates; then one reverse
  * request per written edge, applied per target in (kind, distance, source) order: a local request
  * must pass Eq. 2 with the freshness-biased distance (Eq. 3) and then fills an empty entry or
- * overwrites, among the target's neighbours that the new object points to itself, the one nearest
- * to it; a remote request overwrites the target's remote entry that lies in the new object's
+ * overwrites, among the target's neighbours that the new object points to itself, the one farthest
+ * from the target; a remote request overwrites the target's remote entry that lies in the new object's
  * bucket iff the biased distance is smaller.  New external ids are n_prev .. n_prev+m-1 in input
  * order.  GRAB_EFULL if any bucket would overflow its slab: nothing is written then.
  * Needs k_local <= 64 and k_remote <= 64.

@@ -261,7 +261,7 @@ __device__ __forceinline__ int bucket_of_slot_dev(const int32_t *__restrict__ ta
 // (target, kind) group applies the whole group in order.
 // Local kind: Eq. 2 with Eq. 3's effective distance decides whether the newcomer may enter; it
 // then fills an empty entry or overwrites, among the entries it points to itself, the one
-// nearest to it.  Remote kind: the entry of the target's remote part that lies in the newcomer's
+// farthest from the target (the target still reaches it through the newcomer).  Remote kind: the entry of the target's remote part that lies in the newcomer's
 // bucket is overwritten iff the newcomer's biased distance to the target is smaller.
 template <int NCH>
 __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
@@ -279,7 +279,8 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
     uint32_t *Rl = R + 64;                                // same with empty entries pointing at row 0
     float *dq = reinterpret_cast<float *>(Rl + 64);       // local: dist(q, R[j]); remote: dist(v, R[j])
     uint32_t *qrow = reinterpret_cast<uint32_t *>(dq + 64);  // the requesting node's own row
-    float *qlds = reinterpret_cast<float *>(qrow + 128);
+    float *dv = reinterpret_cast<float *>(qrow + 128);       // local: dist(v, R[j])
+    float *qlds = dv + 64;
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
     if (lane < len) {
         uint32_t e = a.A[(size_t)v * K + off + lane];
@@ -325,6 +326,10 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
             __syncthreads();
         }
     } else {
+        load_query<NCH>(a.X + (size_t)v * D, qreg, qlds, lane);
+        if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
+        eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dv);   // dist(v, R[j]), kept current below
+        __syncthreads();
         for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
             const uint32_t ridx = a.order[p];
             const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
@@ -344,11 +349,11 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
                     at = __ffsll((long long)empties) - 1;
                 } else {
                     // victim: among the entries q points to itself (v still reaches them through q),
-                    // the one nearest to q
+                    // the one farthest from v (ties: smaller slot)
                     bool covered = false;
                     if (lane < len)
                         for (int x = 0; x < K; ++x) covered |= qrow[x] == mine;
-                    u64 kf = covered ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : ~0ull;
+                    u64 kf = covered ? (((u64)(~dist_image(dv[lane])) << 32) | (u64)mine) : ~0ull;
                     u64 kmin = kf;
 #pragma unroll
                     for (int s = 32; s > 0; s >>= 1) {
@@ -360,7 +365,7 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
                 }
                 __syncthreads();
                 if (at >= 0) {
-                    if (lane == at) { R[at] = q; Rl[at] = q; }
+                    if (lane == at) { R[at] = q; Rl[at] = q; dv[at] = dvq; }
                     changed = true;
                 }
             }
@@ -377,7 +382,7 @@ grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireAr
         size_t lds = (size_t)f.beam * 16 + 64 * 4 * 5 + qbytes;
         k_forward<NCH><<<dim3((unsigned)m), dim3(64), lds, ix->stream>>>(f);
     } else {
-        size_t lds = 64 * 4 * 3 + 128 * 4 + qbytes;
+        size_t lds = 64 * 4 * 4 + 128 * 4 + qbytes;
         k_rewire<NCH><<<dim3((unsigned)r.nreq), dim3(64), lds, ix->stream>>>(r);
     }
     GRAB_HIP(ix, hipGetLastError());

@@ -50,6 +50,24 @@ def test_hand_worked_append_on_gpu(alpha):
     ix.close()
 
 
+def test_hand_worked_victim_choice_on_gpu():
+    from paper_2604_16402_amd import binding as B
+    g = json.load(open(os.path.join(GOLD, "append_victim_1d.json")))
+
+    def line(c):
+        out = np.zeros((len(c), 32), np.float32)
+        out[:, 0] = np.asarray(c, np.float32)
+        return out
+    ix = B.Index(32)
+    ix.build_buckets(line(g["coords"]), np.asarray(g["attrs"], np.int32), g["n_buckets"], g["n_cap"])
+    ix.load_graph(np.asarray(g["local"], np.uint32), None)
+    for k, v in [("n_seeds", g["n_seeds"]), ("append_beam", g["append_beam"]), ("alpha", g["alpha"])]:
+        ix.set_param(k, v)
+    ix.append_batch(line([g["new_coord"]]), np.asarray([g["new_attr"]], np.int32))
+    assert ix.get_graph().tolist() == g["adj_slots_after"]
+    ix.close()
+
+
 def _pair(n, dim, B, kl, kr, n_cap, seed, components=16, metric=W.L2SQ):
     import torch
     from paper_2604_16402_amd import binding

@@ -169,6 +169,22 @@ def test_new_nodes_are_reachable_and_found(grown):
         assert ((grown["attrs"][r] >= l) & (grown["attrs"][r] <= h)).all()
 
 
+def test_hand_worked_victim_choice():
+    # tests/golden/append_victim_1d.json: two targets where the covered neighbour farthest from the
+    # target and the covered neighbour nearest to the newcomer differ, and one refused request
+    g = json.load(open(os.path.join(GOLD, "append_victim_1d.json")))
+
+    def line(c):
+        out = np.zeros((len(c), 32), np.float32)
+        out[:, 0] = np.asarray(c, np.float32)
+        return out
+    ix = O.Index(line(g["coords"]), np.asarray(g["attrs"], np.int32), g["n_buckets"], n_cap=g["n_cap"])
+    ix.load_graph(np.asarray(g["local"], np.uint32), np.zeros((4, 0), np.uint32))
+    ix.params.update(n_seeds=g["n_seeds"], append_beam=g["append_beam"], alpha=g["alpha"])
+    ix.append(line([g["new_coord"]]), np.asarray([g["new_attr"]], np.int32))
+    assert ix.A.tolist() == g["adj_slots_after"]
+
+
 def _fresh(alpha, cap=8000):
     cfg = W.scaled(W.CONFIGS["c5"], 3000, n_queries=100, buckets=4, components=8, append_batch=400)
     X, a = W.base_vectors(cfg), W.attributes(cfg)
@@ -208,9 +224,9 @@ def test_bias_opens_rows_for_newcomers():
             part = pre[t][:kl]
             shared = [n for n in part if n == O.EMPTY or n in row]
             assert (s in ix.A[t]) == bool(shared)
-            if shared and O.EMPTY not in part:   # the overwritten neighbour is the shared one nearest to the newcomer
+            if shared and O.EMPTY not in part:   # the overwritten neighbour is the shared one farthest from the target
                 gone = [n for n in part if n not in ix.A[t]]
-                want = min(shared, key=lambda n: (float(O.distance(nx[0], ix.X[n])), int(n)))
+                want = min(shared, key=lambda n: (-float(O.distance(ix.X[t], ix.X[n])), int(n)))
                 assert gone == [want]
         else:           # remote rule: the entry that points into the newcomer's bucket, if any, gives way
             part = pre[t][kl:]
