@@ -109,7 +109,8 @@ def main():
     ends = table[:, 0].astype(np.int64) + table[:, 3]
     bucket_of = np.searchsorted(ends, id2slot.astype(np.int64), side="right")
     la, ra = W.build_graph(X, bucket_of, cfg.buckets, cfg.k_local, cfg.k_remote, metric=cfg.metric,
-                           device="cuda:0", chunk=16384)
+                           device="cuda:0", chunk=16384,
+                           progress=lambda b: log(f"[bench] harness graph: bucket {b + 1} of {cfg.buckets}") if (b + 1) % 16 == 0 else None)
     lad, rad = torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev)
     torch.cuda.synchronize()
     t = time.perf_counter()
