@@ -60,7 +60,8 @@ def main():
     ap.add_argument("--alpha", type=float, default=0.6, help="dynamic workload: freshness bias of Eq. 3")
     ap.add_argument("--append-beam", type=int, default=128, help="dynamic workload: queue size of append's searches")
     ap.add_argument("--append-seeds", type=int, default=256, help="dynamic workload: seeds of append's candidate search")
-    ap.add_argument("--append-width", type=int, default=2, help="dynamic workload: search width of append's candidate search")
+    ap.add_argument("--append-width", type=int, default=4, help="dynamic workload: search width of append's candidate search")
+    ap.add_argument("--append-max-iter", type=int, default=24, help="dynamic workload: iteration cap of append's candidate search")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy five times (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -300,6 +301,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
         na = torch.from_numpy(W.append_attributes(cfg, r)).to(dev)
         # append's candidate search: beam append_beam, its own seeds and width
         ix.set_param("visited_cap", 2800); ix.set_param("n_seeds", args.append_seeds); ix.set_param("search_width", args.append_width)
+        ix.set_param("max_iter", args.append_max_iter)
         torch.cuda.synchronize()
         t = time.perf_counter()
         ix.append_batch(nx, na)
@@ -307,6 +309,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
         t_app = time.perf_counter() - t
         allX, alla = torch.cat([allX, nx]), torch.cat([alla, na])
         ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
+        ix.set_param("max_iter", 0)
         q = torch.from_numpy(W.query_vectors(cfg, stream=100 + r)).to(dev)
         lo, hi = W.ranges(cfg, args.selectivity, stream=300 + r)
         lod, hid = torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)
@@ -353,7 +356,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
            "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32 growing by {cfg.append_rounds} x {cfg.append_batch}, "
                                   f"{cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, 10000 queries per round, "
                                   f"{args.selectivity:.0%} range, k={k}",
-                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width,
+                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width, "append_max_iter": args.append_max_iter,
                       "alpha": args.alpha},
            "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
            "strong_components_final": scc, "orphans_final": n_orphans, "bulk_rebuilt_reference_final": rebuilt, "build": build}

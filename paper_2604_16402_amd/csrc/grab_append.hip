@@ -112,6 +112,53 @@ __global__ void k_iota(uint32_t *__restrict__ a, int64_t n) {
     if (i < n) a[i] = (uint32_t)i;
 }
 
+// Distances from the row held by each group of eight lanes (mine: piece 8c+sub of that group's
+// row) to the rows rows[0..n), the same list for every group, in the summation order of
+// eval_batch with `mine` in the place of the query.  f(j, s) is called by every lane of a group
+// with the distance s between its row and rows[j].
+template <int NCH, typename F>
+__device__ __forceinline__ void group_vs_rows(const float *__restrict__ X, const float4 (&mine)[NCH], const uint32_t *rows,
+                                              int n, int lane, int metric, F &&f) {
+    constexpr int RR = NCH <= 2 ? 8 : (NCH <= 4 ? 4 : 2);   // rows in flight
+    constexpr int D4 = NCH * 8;
+    const int sub = lane & 7;
+    for (int j0 = 0; j0 < n; j0 += RR) {
+        float4 buf[RR][NCH];
+#pragma unroll
+        for (int r = 0; r < RR; ++r) {
+            const uint32_t v = j0 + r < n ? rows[j0 + r] : rows[j0];
+            const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v * D4 + sub;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) buf[r][c] = row[c * 8];
+        }
+#pragma unroll
+        for (int r = 0; r < RR; ++r) {
+            float acc = 0.0f;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                const float4 qv = mine[c], x = buf[r][c];
+                if (metric == GRAB_L2SQ) {
+                    const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+                    acc = __builtin_fmaf(dx, dx, acc);
+                    acc = __builtin_fmaf(dy, dy, acc);
+                    acc = __builtin_fmaf(dz, dz, acc);
+                    acc = __builtin_fmaf(dw, dw, acc);
+                } else {
+                    acc = __builtin_fmaf(qv.x, x.x, acc);
+                    acc = __builtin_fmaf(qv.y, x.y, acc);
+                    acc = __builtin_fmaf(qv.z, x.z, acc);
+                    acc = __builtin_fmaf(qv.w, x.w, acc);
+                }
+            }
+            float t = acc;
+            t += dpp_move<0xB1>(t);
+            t += dpp_move<0x4E>(t);
+            t += dpp_move<0x141>(t);
+            if (j0 + r < n) f(j0 + r, metric == GRAB_L2SQ ? t : -t);
+        }
+    }
+}
+
 struct ForwardArgs {
     const float *X;
     uint32_t *A;
@@ -145,7 +192,9 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     uint32_t *rej = reinterpret_cast<uint32_t *>(keptd + 64);
     float *rejd = reinterpret_cast<float *>(rej + 64);
     float *dtmp = rejd + 64;
-    float *qlds = dtmp + 64;
+    uint32_t *uniq = reinterpret_cast<uint32_t *>(dtmp + 64);   // set of distinct remote candidates
+    const int uniq_words = (2 * a.beam + 3) & ~3;    // keeps the query row behind it 16-byte aligned
+    float *qlds = reinterpret_cast<float *>(uniq + uniq_words);
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
     const uint32_t self = a.slot[i];
     const u64 lt_mask = (1ull << lane) - 1ull;
@@ -161,24 +210,60 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     }
     __syncthreads();
     int nk = 0, nrej = 0;
-    for (int t = 0; t < nc && nk < a.kl; ++t) {
-        const uint32_t c = cs[t];
-        const float dqc = cd[t];
-        bool ok = true;
-        if (nk > 0) {
-            load_query<NCH>(a.X + (size_t)c * D, qreg, qlds, lane);
-            if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-            eval_rows<NCH>(a.X, qreg, qlds, kept, nk, lane, a.metric, dtmp);
+    if constexpr (EvalShape<NCH>::QREG) {
+        // eight candidates at a time, one per lane group: their rows are loaded together, each is
+        // compared with every row kept so far and with the other seven, and the chunk is then
+        // resolved in candidate order exactly as a one-by-one scan would
+        const int sub = lane & 7, grp = lane >> 3;
+        for (int t0 = 0; t0 < nc && nk < a.kl; t0 += 8) {
+            const int G = min(8, nc - t0);
+            const int mt = t0 + grp < nc ? t0 + grp : t0;
+            const float mydq = cd[mt];
+            float4 mine[NCH];
+            {
+                const float4 *row = reinterpret_cast<const float4 *>(a.X) + (size_t)cs[mt] * (NCH * 8) + sub;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) mine[c] = row[c * 8];
+            }
+            bool hid = false;
+            group_vs_rows<NCH>(a.X, mine, kept, nk, lane, a.metric, [&](int, float s) { hid |= !(mydq < s); });
+            group_vs_rows<NCH>(a.X, mine, cs + t0, G, lane, a.metric, [&](int h, float s) { if (sub == 0) dtmp[grp * 8 + h] = s; });
+            const u64 hm = __ballot(hid);
             __syncthreads();
-            bool hidden = lane < nk && !(dqc < dtmp[lane]);
-            ok = __ballot(hidden) == 0;
+            uint32_t keptmask = 0;
+            for (int g = 0; g < G && nk < a.kl; ++g) {
+                const float dqc = cd[t0 + g];
+                bool ok = ((hm >> (8 * g)) & 1ull) == 0;
+                for (int h = 0; h < g; ++h)
+                    if ((keptmask >> h) & 1u) ok = ok && (dqc < dtmp[g * 8 + h]);
+                if (lane == 0) {
+                    if (ok) { kept[nk] = cs[t0 + g]; keptd[nk] = dqc; }
+                    else if (nrej < 64) { rej[nrej] = cs[t0 + g]; rejd[nrej] = dqc; }
+                }
+                if (ok) { ++nk; keptmask |= 1u << g; } else if (nrej < 64) ++nrej;
+            }
+            __syncthreads();
         }
-        if (lane == 0) {
-            if (ok) { kept[nk] = c; keptd[nk] = dqc; }
-            else if (nrej < 64) { rej[nrej] = c; rejd[nrej] = dqc; }
+    } else {
+        for (int t = 0; t < nc && nk < a.kl; ++t) {
+            const uint32_t c = cs[t];
+            const float dqc = cd[t];
+            bool ok = true;
+            if (nk > 0) {
+                load_query<NCH>(a.X + (size_t)c * D, qreg, qlds, lane);
+                __syncthreads();
+                eval_rows<NCH>(a.X, qreg, qlds, kept, nk, lane, a.metric, dtmp);
+                __syncthreads();
+                bool hidden = lane < nk && !(dqc < dtmp[lane]);
+                ok = __ballot(hidden) == 0;
+            }
+            if (lane == 0) {
+                if (ok) { kept[nk] = c; keptd[nk] = dqc; }
+                else if (nrej < 64) { rej[nrej] = c; rejd[nrej] = dqc; }
+            }
+            if (ok) ++nk; else if (nrej < 64) ++nrej;
+            __syncthreads();
         }
-        if (ok) ++nk; else if (nrej < 64) ++nrej;
-        __syncthreads();
     }
     for (int j = lane; j < a.kl; j += 64) {
         uint32_t v = GRAB_EMPTY;
@@ -197,11 +282,24 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         __syncthreads();
     }
     for (int j = 0; j < a.kr; ++j) {
+        // neighbouring candidates mostly share their j-th remote entry: each distinct slot is
+        // evaluated once (the minimum below does not depend on repeats)
+        for (int x = lane; x < uniq_words; x += 64) uniq[x] = GRAB_EMPTY;
+        __syncthreads();
         int nr = 0;
         for (int c0 = 0; c0 < nc; c0 += 64) {
             const int t = c0 + lane;
             uint32_t r = t < nc ? a.A[(size_t)cs[t] * K + a.kl + j] : GRAB_EMPTY;
-            bool ok = r != GRAB_EMPTY;
+            bool ok = false;
+            if (r != GRAB_EMPTY) {
+                uint32_t h = (uint32_t)(((u64)(r * 0x9E3779B1u) * (u64)uniq_words) >> 32);
+                for (int probe = 0; probe < uniq_words; ++probe) {
+                    const uint32_t old = atomicCAS(&uniq[h], GRAB_EMPTY, r);
+                    if (old == GRAB_EMPTY) { ok = true; break; }
+                    if (old == r) break;
+                    h = h + 1 == (uint32_t)uniq_words ? 0u : h + 1;
+                }
+            }
             u64 m = __ballot(ok);
             if (ok) rs[nr + __popcll(m & lt_mask)] = r;
             nr += __popcll(m);
@@ -379,7 +477,7 @@ template <int NCH>
 grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
     const size_t qbytes = EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4;
     if (phase == 0) {
-        size_t lds = (size_t)f.beam * 16 + 64 * 4 * 5 + qbytes;
+        size_t lds = (size_t)f.beam * 16 + 64 * 4 * 5 + (size_t)((2 * f.beam + 3) & ~3) * 4 + qbytes;
         k_forward<NCH><<<dim3((unsigned)m), dim3(64), lds, ix->stream>>>(f);
     } else {
         size_t lds = 64 * 4 * 4 + 128 * 4 + qbytes;
