@@ -294,6 +294,40 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     ix.set_param("alpha", args.alpha)
     ix.set_param("append_beam", args.append_beam)
+    DYN_GRID = [(32, 96, 2, 1400, 20), (36, 96, 2, 1400, 21), (40, 96, 2, 1400, 24), (40, 128, 3, 1400, 18), (48, 64, 2, 1400, 0),
+                (48, 96, 2, 1400, 28), (48, 128, 4, 1400, 0), (48, 128, 3, 1400, 20), (56, 128, 3, 1400, 24), (64, 64, 2, 1400, 0),
+                (64, 128, 4, 1400, 0), (64, 128, 3, 1400, 28), (64, 256, 4, 4000, 0), (96, 128, 3, 2800, 36), (96, 256, 4, 4000, 0),
+                (128, 256, 4, 2800, 0)]
+
+    def qps_at_recall(index, q, lod, hid, gt, ids, dist, target=0.95):
+        """Fastest setting of a small grid that reaches the recall target (Section 5.3 measures the
+        search rate at a fixed recall while the index grows)."""
+        best = None
+        for b_, s_, w_, v_, m_ in DYN_GRID:
+            index.set_param("visited_cap", v_); index.set_param("n_seeds", s_); index.set_param("search_width", w_)
+            index.set_param("max_iter", m_)
+            index.search_range(q, lod, hid, k, b_, ids, dist)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for _ in range(5):
+                index.search_range(q, lod, hid, k, b_, ids, dist)
+            torch.cuda.synchronize()
+            sec = (time.perf_counter() - t) / 5
+            rec = GT.recall(ids, gt)
+            if rec >= target and (best is None or sec < best[0]):
+                best = (sec, rec, [b_, s_, w_, v_, m_])
+        index.set_param("max_iter", 0)
+        if best is None:
+            return None
+        return {"queries_per_s": round(len(q) / best[0], 1), "recall_at_10": round(best[1], 4), "setting": best[2]}
+
+    q0 = torch.from_numpy(W.query_vectors(cfg, stream=100)).to(dev)
+    lo0, hi0 = W.ranges(cfg, args.selectivity, stream=300)
+    lo0d, hi0d = torch.from_numpy(lo0).to(dev), torch.from_numpy(hi0).to(dev)
+    ids0 = torch.empty((len(q0), k), dtype=torch.int32, device=dev)
+    dist0 = torch.empty((len(q0), k), dtype=torch.float32, device=dev)
+    at_recall = {"before_appends": qps_at_recall(ix, q0, lo0d, hi0d, GT.exact_filtered_knn(Xd, ad, q0, lo0d, hi0d, k, cfg.metric), ids0, dist0)}
+    ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     rounds = []
     allX, alla = Xd, ad
     for r in range(cfg.append_rounds):
@@ -328,6 +362,8 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
                        "append_ms": round(t_app * 1e3, 2), "search_qps": round(len(q) / t_s, 1),
                        "recall_at_10": round(GT.recall(ids, gt), 4), "results_from_appended": round(new_frac, 4)})
         log(f"[bench] round {r + 1}: {rounds[-1]}")
+    at_recall["after_appends"] = qps_at_recall(ix, q, lod, hid, gt, ids, dist)
+    ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     # connectivity of the grown graph (Section 5.4's diagnostic)
     from paper_2604_16402_amd import binding, diagnostics
     _, _, slot2id = ix.get_layout()
@@ -348,6 +384,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
     ref.search_range(q, lod, hid, k, beam, ids, dist)
     torch.cuda.synchronize()
     rebuilt = {"recall_at_10": round(GT.recall(ids, gt), 4)}
+    at_recall["bulk_rebuilt"] = qps_at_recall(ref, q, lod, hid, gt, ids, dist)
     ref.close()
     log(f"[bench] bulk-rebuilt reference on the final {ix.sizes()['n']} objects: {rebuilt}")
     out = {"metric": "dynamic workload: append vectors/s and filtered queries/s per round (1M -> 2M x 128 fp32, 10% range)",
@@ -359,7 +396,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
                       "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width, "append_max_iter": args.append_max_iter,
                       "alpha": args.alpha},
            "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
-           "strong_components_final": scc, "orphans_final": n_orphans, "bulk_rebuilt_reference_final": rebuilt, "build": build}
+           "search_rate_at_recall_0.95": at_recall, "strong_components_final": scc, "orphans_final": n_orphans, "bulk_rebuilt_reference_final": rebuilt, "build": build}
     ix.close()
     print(json.dumps(out), flush=True)
 
