@@ -3,10 +3,10 @@
 //
 // Data movement per query: the query row once, one 128-byte-aligned feature row per
 // distance evaluation (8 lanes x 16 B per 128-byte line, all lines of up to 8*R rows in
-// flight at once), one adjacency row per expanded parent.  The candidate queue, the new
-// candidates and the visited hash live in LDS.  The scalar pre-check is decided from slot
-// intervals prepared by the select kernel, so only slots in the appended tails of the two
-// edge buckets cost an attribute read.
+// flight at once), one adjacency row per expanded parent.  The candidate queue lives in
+// registers, the waiting new keys, the slot list and the visited set in LDS.  The scalar
+// pre-check is decided from slot intervals prepared by the select kernel, so only slots in
+// the appended tails of the two edge buckets cost an attribute read.
 #include "grab_device.h"
 
 namespace {
