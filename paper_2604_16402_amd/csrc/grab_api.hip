@@ -95,7 +95,8 @@ void grab_destroy(grab_index *ix) {
     drop_layout(ix);
     DevBuf *bufs[] = {&ix->plans, &ix->seeds, &ix->counters, &ix->stage_q, &ix->stage_lo, &ix->stage_hi,
                       &ix->stage_ids, &ix->stage_dist, &ix->stage_misc, &ix->flags, &ix->stage_fa, &ix->stage_flo,
-                      &ix->stage_fhi, &ix->conv_a, &ix->conv_lo, &ix->conv_hi, &ix->attr_flag};
+                      &ix->stage_fhi, &ix->conv_a, &ix->conv_lo, &ix->conv_hi, &ix->attr_flag, &ix->q_bin, &ix->q_rank,
+                      &ix->q_order, &ix->bin_count};
     for (DevBuf *b : bufs) free_buf(*b);
     for (DevBuf &b : ix->app) free_buf(b);
     for (hipEvent_t e : ix->ev)
@@ -294,6 +295,7 @@ grab_status grab_search_range(grab_index *ix, const float *queries, const int32_
     s.plans = (QueryPlan *)ix->plans.p; s.seeds = (uint32_t *)ix->seeds.p; s.counters = (uint32_t *)ix->counters.p;
     s.out_ids = ids_dev ? out_ids : (uint32_t *)ix->stage_ids.p;
     s.out_dist = dist_dev ? out_dist : (float *)ix->stage_dist.p;
+    if ((st = grab_plan_order(ix, s)) != GRAB_OK) return st;
     ix->timed = false;
     if (ix->profile) GRAB_HIP(ix, hipEventRecord(ix->ev[0], ix->stream));
     if ((st = grab_launch_select(ix, s)) != GRAB_OK) return st;

@@ -562,6 +562,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     s.plans = (QueryPlan *)ix->plans.p; s.seeds = (uint32_t *)ix->seeds.p; s.counters = (uint32_t *)ix->counters.p;
     s.out_slots = true;
     s.only_bucket = bucket; s.out_ids = (uint32_t *)P(A_CL_S); s.out_dist = (float *)P(A_CL_D);
+    if ((rc = grab_plan_order(ix, s)) != GRAB_OK) return rc;
     if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
     if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
     ix->last_nq = 0;

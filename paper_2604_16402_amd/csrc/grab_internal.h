@@ -75,6 +75,8 @@ struct grab_index {
     DevBuf plans, seeds, counters, stage_q, stage_lo, stage_hi, stage_ids, stage_dist, stage_misc, flags;
     // float attributes: staged floats, their int32 images, the NaN flag
     DevBuf stage_fa, stage_flo, stage_fhi, conv_a, conv_lo, conv_hi, attr_flag;
+    // launch order of the queries of a search (grab_plan_order)
+    DevBuf q_bin, q_rank, q_order, bin_count;
     int64_t last_nq = 0;
     std::vector<DevBuf> app;     // append's work arena
 
@@ -118,7 +120,15 @@ struct SearchLaunch {
     uint32_t *out_ids;  // device [nq][k] (external ids, or slots when out_slots)
     float *out_dist;    // device [nq][k]
     bool out_slots;
+    // launch order (all nullptr: query i runs in workgroup i): see grab_plan_order
+    int32_t *q_bin = nullptr, *q_rank = nullptr, *bin_count = nullptr;
+    uint32_t *order = nullptr;   // [order_len]: query of each workgroup, GRAB_EMPTY for none
+    int64_t order_len = 0;
 };
+// Reserves the buffers that let the search run its queries grouped by first selected bucket, one
+// contiguous run of that order per XCD (queries that read the same buckets then share L2 and the
+// Infinity Cache); fills the order fields of `s`, or leaves them null for small batches.
+grab_status grab_plan_order(grab_index *ix, SearchLaunch &s);
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s);
 grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s);
 // measurement aid: `waves` wavefronts each read `batches` batches of random rows; *bytes = rows read x row size

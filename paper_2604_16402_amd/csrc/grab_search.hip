@@ -155,6 +155,88 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
     }
 }
 
+// ------------------------------------------------------------------------------ launch order
+// Queries that select the same buckets read the same vectors.  The search therefore launches them
+// grouped by first selected bucket (a counting sort: k_order_bin counts and ranks, k_order
+// places), and gives each XCD one contiguous run of that order: workgroups go round the eight
+// XCDs, so workgroup w gets position (w % 8) * ceil(nq / 8) + w / 8.  Only the order in which
+// queries run changes; every query's result and counters are what they are in any order.
+__global__ void k_order_reset(int32_t *__restrict__ bin_count, int nbins, uint32_t *__restrict__ order, int64_t order_len) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < nbins) bin_count[i] = 0;
+    if (i < order_len) order[i] = GRAB_EMPTY;
+}
+
+// bin of a query = its first selected bucket (the bucket it is restricted to, for an append's
+// search); bin B = its range meets no bucket.  (Finer bins, by the position of lo inside the
+// bucket's interval, gained nothing.)  Rank inside the bin: LDS counts per workgroup, one global
+// atomic per workgroup and bin.
+__global__ __launch_bounds__(256) void k_order_bin(const int32_t *__restrict__ table, int32_t B,
+                                                   const int32_t *__restrict__ lo_, const int32_t *__restrict__ hi_,
+                                                   const int32_t *__restrict__ only_bucket, int64_t nq,
+                                                   int32_t *__restrict__ q_bin, int32_t *__restrict__ q_rank,
+                                                   int32_t *__restrict__ bin_count) {
+    __shared__ int32_t cnt[GRAB_MAX_BUCKETS + 1], base[GRAB_MAX_BUCKETS + 1];
+    const int last = B;
+    for (int i = threadIdx.x; i <= last; i += 256) cnt[i] = 0;
+    __syncthreads();
+    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    int bin = last, local = 0;
+    if (q < nq) {
+        if (only_bucket) {
+            bin = only_bucket[q];
+        } else {
+            const int lo = lo_[q], hi = hi_[q];
+            if (lo <= hi) {
+                int l = 0, r = B;    // first bucket whose max is not below lo (bucket intervals are ordered)
+                while (l < r) {
+                    const int m = (l + r) >> 1;
+                    if (table[T_COLS * m + T_MAX] < lo) l = m + 1; else r = m;
+                }
+                if (l < B && table[T_COLS * l + T_MIN] <= hi) bin = l;
+            }
+        }
+        if (bin < 0 || bin > last) bin = last;
+        local = atomicAdd(&cnt[bin], 1);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i <= last; i += 256)
+        if (cnt[i] > 0) base[i] = atomicAdd(&bin_count[i], cnt[i]);
+    __syncthreads();
+    if (q < nq) { q_bin[q] = bin; q_rank[q] = base[bin] + local; }
+}
+
+__global__ __launch_bounds__(64) void k_order(const int32_t *__restrict__ q_bin, const int32_t *__restrict__ q_rank,
+                                              const int32_t *__restrict__ bin_count, int nbins, int64_t nq,
+                                              uint32_t *__restrict__ order, int64_t order_len) {
+    __shared__ int32_t start[GRAB_MAX_BUCKETS + 2];
+    const int lane = threadIdx.x;
+    // exclusive prefix of the bin counts (every workgroup recomputes it: at most 1025 words)
+    int carry = 0;
+    for (int i0 = 0; i0 < nbins; i0 += 64) {
+        const int i = i0 + lane;
+        const int c = i < nbins ? bin_count[i] : 0;
+        int inc = c;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            int up = __shfl_up(inc, d);
+            if (lane >= d) inc += up;
+        }
+        if (i < nbins) start[i] = carry + inc - c;
+        carry += __shfl(inc, 63);
+    }
+    __syncthreads();
+    const int64_t q = (int64_t)blockIdx.x * 64 + lane;
+    if (q >= nq) return;
+    const int bin = q_bin[q];
+    if (bin < 0 || bin >= nbins) return;
+    const int64_t pos = (int64_t)start[bin] + q_rank[q];      // position in bucket order
+    const int64_t chunk = order_len / 8;
+    if (pos < 0 || pos >= nq || chunk == 0) return;
+    const int64_t w = (pos % chunk) * 8 + pos / chunk;          // workgroup that runs it
+    if (w < order_len) order[w] = (uint32_t)q;
+}
+
 // ------------------------------------------------------------------------------- beam search
 struct BeamArgs {
     const float *X;
@@ -168,6 +250,8 @@ struct BeamArgs {
     uint32_t *counters;
     uint32_t *out_ids;
     float *out_dist;
+    const uint32_t *order;   // query of each workgroup, or nullptr: workgroup i runs query i
+    int64_t nq;
     int32_t K, k, beam, QP, width, max_iter, S, visited_cap, hsize, maxc, metric, out_slots;
 };
 
@@ -246,7 +330,8 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
     constexpr int R = EvalShape<NCH>::R;
     constexpr int NV = 4;
     const int lane = threadIdx.x;
-    const int64_t q = blockIdx.x;
+    const int64_t q = a.order ? (int64_t)a.order[blockIdx.x] : (int64_t)blockIdx.x;
+    if (q >= a.nq) return;   // a hole of the launch order (GRAB_EMPTY)
     const int H = a.hsize;
     u64 *C = reinterpret_cast<u64 *>(smem);                 // keys waiting to be merged
     uint32_t *hash = reinterpret_cast<uint32_t *>(C + 64);
@@ -484,11 +569,42 @@ grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batc
     }
 }
 
+grab_status grab_plan_order(grab_index *ix, SearchLaunch &s) {
+    s.q_bin = s.q_rank = s.bin_count = nullptr;
+    s.order = nullptr;
+    s.order_len = 0;
+    if (s.nq < 2048) return GRAB_OK;   // a batch that does not even fill the device once gains nothing
+    const int64_t len = (s.nq + 7) / 8 * 8;
+    grab_status st;
+    if ((st = grab_reserve(ix, ix->q_bin, (size_t)s.nq * 4)) != GRAB_OK) return st;
+    if ((st = grab_reserve(ix, ix->q_rank, (size_t)s.nq * 4)) != GRAB_OK) return st;
+    if ((st = grab_reserve(ix, ix->q_order, (size_t)len * 4)) != GRAB_OK) return st;
+    if ((st = grab_reserve(ix, ix->bin_count, (size_t)(GRAB_MAX_BUCKETS + 1) * 4)) != GRAB_OK) return st;
+    s.q_bin = (int32_t *)ix->q_bin.p; s.q_rank = (int32_t *)ix->q_rank.p; s.bin_count = (int32_t *)ix->bin_count.p;
+    s.order = (uint32_t *)ix->q_order.p;
+    s.order_len = len;
+    return GRAB_OK;
+}
+
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
     if (s.nq == 0) return GRAB_OK;
+    const int nbins = ix->B + 1;   // the last bin takes the queries whose range meets no bucket
+    if (s.order) {
+        const int64_t n = s.order_len > nbins ? s.order_len : nbins;
+        k_order_reset<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ix->stream>>>(s.bin_count, nbins, s.order, s.order_len);
+        GRAB_HIP(ix, hipGetLastError());
+    }
     k_select_seed<<<dim3((unsigned)s.nq), dim3(64), 0, ix->stream>>>(ix->table, ix->B, ix->attr, s.lo, s.hi, s.only_bucket,
                                                                     s.n_seeds, s.salt, s.plans, s.seeds);
     GRAB_HIP(ix, hipGetLastError());
+    if (s.order) {
+        k_order_bin<<<dim3((unsigned)((s.nq + 255) / 256)), dim3(256), 0, ix->stream>>>(ix->table, ix->B, s.lo, s.hi, s.only_bucket,
+                                                                                     s.nq, s.q_bin, s.q_rank, s.bin_count);
+        GRAB_HIP(ix, hipGetLastError());
+        k_order<<<dim3((unsigned)((s.nq + 63) / 64)), dim3(64), 0, ix->stream>>>(s.q_bin, s.q_rank, s.bin_count, nbins, s.nq,
+                                                                              s.order, s.order_len);
+        GRAB_HIP(ix, hipGetLastError());
+    }
     return GRAB_OK;
 }
 
@@ -498,6 +614,7 @@ grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s) {
     a.X = ix->X; a.attr = ix->attr; a.A = ix->A; a.slot2id = ix->slot2id;
     a.queries = s.queries; a.lo = s.lo; a.hi = s.hi; a.plans = s.plans; a.seeds = s.seeds;
     a.counters = s.counters; a.out_ids = s.out_ids; a.out_dist = s.out_dist;
+    a.order = s.order; a.nq = s.nq;
     a.K = ix->kl + ix->kr; a.k = s.k; a.beam = s.beam; a.QP = pow2_at_least(s.beam, 64);
     a.width = s.width; a.max_iter = s.max_iter; a.S = s.n_seeds; a.visited_cap = s.visited_cap;
     // visited table: the power of two above 4/3 of the capacity when that wastes little LDS (short
@@ -509,7 +626,7 @@ grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s) {
     a.metric = ix->metric; a.out_slots = s.out_slots ? 1 : 0;
     const int nch = ix->dim / 32;
     switch (nch) {
-#define GRAB_CASE(N) case N: return launch_beam_t<N>(ix, a, s.nq, H);
+#define GRAB_CASE(N) case N: return launch_beam_t<N>(ix, a, s.order ? s.order_len : s.nq, H);
         GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
         GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
 #undef GRAB_CASE

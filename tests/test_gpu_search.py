@@ -273,3 +273,19 @@ def test_gather_probe_reports_rows_read(c1_small, torch_dev):
     want_ids, want_dist, _ = c1_small["oracle"].search(q, lo, hi, 10, 64)
     assert np.array_equal(ids, want_ids) and np.array_equal(dist, want_dist)
     ix.close()
+
+
+@pytest.mark.parametrize("nq", [2048, 2051, 4097])
+def test_batches_that_run_in_bucket_order_match_oracle(c1_small, torch_dev, nq):
+    # from 2,048 queries on the library launches the queries grouped by first selected bucket; the
+    # batch sizes leave zero, five and seven unused workgroups at the end of that order
+    ix = _gpu_index(c1_small, torch_dev)
+    rng = np.random.default_rng(nq)
+    pick = rng.integers(0, len(c1_small["queries"]), nq)
+    q = c1_small["queries"][pick]
+    lo = rng.integers(-200, 10100, nq).astype(np.int32)
+    hi = (lo + rng.integers(-3, 3000, nq)).astype(np.int32)          # some ranges are empty
+    ids, dist, ctr = _search_gpu(ix, torch_dev, q, lo, hi, 10, 32)
+    want_ids, want_dist, want_ctr = c1_small["oracle"].search(q, lo, hi, 10, 32, threads=O.max_threads())
+    assert np.array_equal(ids, want_ids) and np.array_equal(dist, want_dist) and np.array_equal(ctr, want_ctr)
+    ix.close()
