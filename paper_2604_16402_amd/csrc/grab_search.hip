@@ -156,11 +156,12 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
 }
 
 // ------------------------------------------------------------------------------ launch order
+#define GRAB_ORDER_RUN 256   // short run length, see k_order
 // Queries that select the same buckets read the same vectors.  The search therefore launches them
 // grouped by first selected bucket (a counting sort: k_order_bin counts and ranks, k_order
-// places), and gives each XCD one contiguous run of that order: workgroups go round the eight
-// XCDs, so workgroup w gets position (w % 8) * ceil(nq / 8) + w / 8.  Only the order in which
-// queries run changes; every query's result and counters are what they are in any order.
+// places), and gives each XCD contiguous runs of that order (workgroups go round the eight XCDs).
+// Only the order in which queries run changes; every query's result and counters are what they
+// are in any order.
 __global__ void k_order_reset(int32_t *__restrict__ bin_count, int nbins, uint32_t *__restrict__ order, int64_t order_len) {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < nbins) bin_count[i] = 0;
@@ -208,14 +209,15 @@ __global__ __launch_bounds__(256) void k_order_bin(const int32_t *__restrict__ t
 
 __global__ __launch_bounds__(64) void k_order(const int32_t *__restrict__ q_bin, const int32_t *__restrict__ q_rank,
                                               const int32_t *__restrict__ bin_count, int nbins, int64_t nq,
-                                              uint32_t *__restrict__ order, int64_t order_len) {
+                                              uint32_t *__restrict__ order, int64_t order_len, int runs_per_xcd) {
     __shared__ int32_t start[GRAB_MAX_BUCKETS + 2];
     const int lane = threadIdx.x;
     // exclusive prefix of the bin counts (every workgroup recomputes it: at most 1025 words)
-    int carry = 0;
+    int carry = 0, biggest = 0;
     for (int i0 = 0; i0 < nbins; i0 += 64) {
         const int i = i0 + lane;
         const int c = i < nbins ? bin_count[i] : 0;
+        biggest = max(biggest, c);
         int inc = c;
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) {
@@ -225,15 +227,24 @@ __global__ __launch_bounds__(64) void k_order(const int32_t *__restrict__ q_bin,
         if (i < nbins) start[i] = carry + inc - c;
         carry += __shfl(inc, 63);
     }
+#pragma unroll
+    for (int d = 32; d > 0; d >>= 1) biggest = max(biggest, __shfl_xor(biggest, d));   // all lanes still active
     __syncthreads();
     const int64_t q = (int64_t)blockIdx.x * 64 + lane;
     if (q >= nq) return;
     const int bin = q_bin[q];
     if (bin < 0 || bin >= nbins) return;
     const int64_t pos = (int64_t)start[bin] + q_rank[q];      // position in bucket order
-    const int64_t chunk = order_len / 8;
-    if (pos < 0 || pos >= nq || chunk == 0) return;
-    const int64_t w = (pos % chunk) * 8 + pos / chunk;          // workgroup that runs it
+    if (pos < 0 || pos >= nq) return;
+    // Runs of `run` consecutive positions go round the XCDs: the i-th workgroup of XCD c (w = 8 i + c)
+    // takes element i % run of run (i / run) * 8 + c.  Evenly filled bins: runs_per_xcd long runs per
+    // XCD (one gives the most sharing).  When one bin holds a large share of the batch, what a query
+    // costs follows its bin (a query that starts in the last bucket cannot be wide), and long runs
+    // would leave some XCDs with all the expensive queries: short runs then.
+    const int64_t parts = 8 * (int64_t)runs_per_xcd;
+    const int64_t run = (int64_t)biggest * 16 > nq ? GRAB_ORDER_RUN : (nq + parts - 1) / parts;
+    const int64_t g = pos / run, e = pos % run;
+    const int64_t w = ((g / 8) * run + e) * 8 + g % 8;
     if (w < order_len) order[w] = (uint32_t)q;
 }
 
@@ -574,7 +585,8 @@ grab_status grab_plan_order(grab_index *ix, SearchLaunch &s) {
     s.order = nullptr;
     s.order_len = 0;
     if (s.nq < 2048) return GRAB_OK;   // a batch that does not even fill the device once gains nothing
-    const int64_t len = (s.nq + 7) / 8 * 8;
+    // room for either run length k_order may choose: nq rounded up to eight short runs
+    const int64_t len = (s.nq + 8 * GRAB_ORDER_RUN - 1) / (8 * GRAB_ORDER_RUN) * (8 * GRAB_ORDER_RUN);
     grab_status st;
     if ((st = grab_reserve(ix, ix->q_bin, (size_t)s.nq * 4)) != GRAB_OK) return st;
     if ((st = grab_reserve(ix, ix->q_rank, (size_t)s.nq * 4)) != GRAB_OK) return st;
@@ -598,11 +610,15 @@ grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
                                                                     s.n_seeds, s.salt, s.plans, s.seeds);
     GRAB_HIP(ix, hipGetLastError());
     if (s.order) {
+        // measured: rows of 512 B (1M x 128) run fastest with one run per XCD (headline 481 us against
+        // 502 us with four and 516 us in input order); rows of 3,840 B (1M x 960) with four (3.82 ms
+        // against 4.06 ms with one and 4.19 ms in input order)
         k_order_bin<<<dim3((unsigned)((s.nq + 255) / 256)), dim3(256), 0, ix->stream>>>(ix->table, ix->B, s.lo, s.hi, s.only_bucket,
                                                                                      s.nq, s.q_bin, s.q_rank, s.bin_count);
         GRAB_HIP(ix, hipGetLastError());
         k_order<<<dim3((unsigned)((s.nq + 63) / 64)), dim3(64), 0, ix->stream>>>(s.q_bin, s.q_rank, s.bin_count, nbins, s.nq,
-                                                                              s.order, s.order_len);
+                                                                              s.order, s.order_len,
+                                                                              ix->dim >= 512 ? 4 : 1);
         GRAB_HIP(ix, hipGetLastError());
     }
     return GRAB_OK;
