@@ -168,6 +168,8 @@ struct ForwardArgs {
     const float *cand_d;        //                                 distances to the new vector
     u64 *key1, *key2;           // request keys, one per row entry
     float *reqd;
+    const uint32_t *by_bucket;  // batch positions in bucket order: the order the workgroups take them in
+    int64_t m;
     int32_t beam, kl, kr, metric;
 };
 
@@ -181,7 +183,12 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int D = NCH * 32;
     const int lane = threadIdx.x;
-    const int64_t i = blockIdx.x;
+    // new nodes of one bucket read the same candidate rows and the same remote target buckets: the
+    // workgroups take the batch in bucket order, one contiguous run of it per XCD
+    const int64_t chunk = (a.m + 7) / 8;
+    const int64_t pos = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+    if (pos >= a.m) return;
+    const int64_t i = a.by_bucket[pos];
     const int K = a.kl + a.kr;
     uint32_t *cs = reinterpret_cast<uint32_t *>(smem);          // local candidates
     float *cd = reinterpret_cast<float *>(cs + a.beam);
@@ -478,7 +485,7 @@ grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireAr
     const size_t qbytes = EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4;
     if (phase == 0) {
         size_t lds = (size_t)f.beam * 16 + 64 * 4 * 5 + (size_t)((2 * f.beam + 3) & ~3) * 4 + qbytes;
-        k_forward<NCH><<<dim3((unsigned)m), dim3(64), lds, ix->stream>>>(f);
+        k_forward<NCH><<<dim3((unsigned)((m + 7) / 8 * 8)), dim3(64), lds, ix->stream>>>(f);
     } else {
         size_t lds = 64 * 4 * 4 + 128 * 4 + qbytes;
         k_rewire<NCH><<<dim3((unsigned)r.nreq), dim3(64), lds, ix->stream>>>(r);
@@ -571,6 +578,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     f.X = ix->X; f.A = ix->A; f.vecs = d_vecs; f.slot = slot;
     f.cand_s = (const uint32_t *)P(A_CL_S); f.cand_d = (const float *)P(A_CL_D);
     f.key1 = (u64 *)P(A_KEY1); f.key2 = (u64 *)P(A_KEY2); f.reqd = (float *)P(A_REQD);
+    f.by_bucket = (const uint32_t *)P(A_IDX_S); f.m = m;
     f.beam = beam; f.kl = kl; f.kr = kr; f.metric = ix->metric;
     RewireArgs r;
     memset(&r, 0, sizeof(r));
