@@ -25,6 +25,8 @@
  *     physical row numbers of the bucket-major device arrays.
  *   - 0xFFFFFFFF marks an empty adjacency entry and a missing result.
  *   - dim must be a multiple of 32 (rows are whole 128-byte lines) and at most 2048.
+ *   - The queries of a batch are independent; the library runs them in an order of its own
+ *     (grouped by the buckets they select) and every result is what it would be in any order.
  *   - Not thread-safe per handle; different handles are independent.
  */
 #ifndef GRAB_H
