@@ -180,7 +180,8 @@ grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq);
 
 /* Kernel durations of the most recent grab_search_range, measured with HIP events on the
  * index's stream (needs GRAB_P_PROFILE = 1 before that search): ms[0] bucket-select + seeding
- * kernel, ms[1] beam-search kernel, in milliseconds (host array).  Waits for the search to
+ * kernel and, for batches of 2,048 queries and more, the three small kernels that fix the order
+ * in which the queries run; ms[1] beam-search kernel; in milliseconds (host array).  Waits for the search to
  * finish.  GRAB_ESTATE if profiling was off. */
 grab_status grab_get_timing(grab_index *ix, float ms[2]);
 
