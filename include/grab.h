@@ -129,6 +129,22 @@ grab_status grab_search_range(grab_index *ix, const float *queries, const int32_
                               const int32_t *hi, int64_t nq, int32_t k, int32_t beam,
                               uint32_t *out_ids, float *out_dist);
 
+/* grab_search_range for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same kernels, same results, same counters
+ * and timing read-backs as grab_search_range, but the per-batch work buffers (query plans, seed
+ * slots, counters, launch order) live in one static device array of about 18 MiB that every GPU
+ * the library runs on holds until the process ends; the call performs no hipMalloc, hipFree or
+ * other allocating call.  Limits: every pointer must be a device pointer (staging a host buffer
+ * would allocate); nq <= 16,384; nq * n_seeds <= 4,194,304 (n_seeds as grab_search_range
+ * resolves it).  Beyond either limit, or with a host pointer: GRAB_EINVAL, nothing launched.
+ * All calls on one GPU, from any handle, share that GPU's array: calls whose kernels could
+ * overlap on one GPU (different streams, different threads) race and must be serialised by the
+ * caller; the counters of a call stay readable until the next call on that GPU.
+ * Other errors: GRAB_ESTATE (no graph), GRAB_EHIP. */
+grab_status grab_search_range_noalloc(grab_index *ix, const float *queries, const int32_t *lo,
+                                      const int32_t *hi, int64_t nq, int32_t k, int32_t beam,
+                                      uint32_t *out_ids, float *out_dist);
+
 /* Batched insertion (Section 4.4): appends m objects at the tails of their buckets without
  * moving any existing slot (bucket = the one whose attribute interval holds the new value, else
  * the first one above it; slot = stable order of arrival inside the bucket).  Decisions about

@@ -24,7 +24,7 @@ PARAMS = dict(search_width=P_SEARCH_WIDTH, max_iter=P_MAX_ITER, n_seeds=P_N_SEED
 EMPTY = 0xFFFFFFFF
 
 EXPORTS = ["grab_create", "grab_destroy", "grab_last_error", "grab_build_buckets", "grab_load_graph",
-           "grab_build_graph", "grab_search_range", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
+           "grab_build_graph", "grab_search_range", "grab_search_range_noalloc", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
            "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing",
            "grab_probe_gather", "grab_attr_image", "grab_attr_value", "grab_build_buckets_f32", "grab_search_range_f32",
            "grab_append_batch_f32"]
@@ -63,6 +63,7 @@ def load_library() -> ctypes.CDLL:
     lib.grab_load_graph.argtypes = [vp, vp, i32, vp, i32]
     lib.grab_build_graph.argtypes = [vp, i32, i32, i32]
     lib.grab_search_range.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp]
+    lib.grab_search_range_noalloc.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp]
     lib.grab_append_batch.argtypes = [vp, vp, vp, i64]
     lib.grab_set_param.argtypes = [vp, i32, ctypes.c_double]
     lib.grab_get_sizes.argtypes = [vp, vp]
@@ -186,6 +187,14 @@ class Index:
         self._check(self._lib.grab_search_range(self._h, _ptr(queries, np.float32, nq * self.dim),
                                                 _ptr(lo, np.int32, nq), _ptr(hi, np.int32, nq), nq, k, beam,
                                                 _ptr(out_ids, np.uint32, nq * k), _ptr(out_dist, np.float32, nq * k)))
+        return out_ids, out_dist
+
+    def search_range_noalloc(self, queries, lo, hi, k: int, beam: int, out_ids, out_dist):
+        """search_range without any allocation inside the library: device tensors only."""
+        nq = int(queries.shape[0])
+        self._check(self._lib.grab_search_range_noalloc(self._h, _ptr(queries, np.float32, nq * self.dim),
+                                                        _ptr(lo, np.int32, nq), _ptr(hi, np.int32, nq), nq, k, beam,
+                                                        _ptr(out_ids, np.uint32, nq * k), _ptr(out_dist, np.float32, nq * k)))
         return out_ids, out_dist
 
     def search_range_f32(self, queries, lo, hi, k: int, beam: int, out_ids=None, out_dist=None):

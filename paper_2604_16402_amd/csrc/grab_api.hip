@@ -73,6 +73,22 @@ static void drop_layout(grab_index *ix) {
     ix->n = ix->n_slots = 0; ix->B = 0; ix->kl = ix->kr = 0; ix->has_graph = false;
 }
 
+grab_status grab_resolve_search(grab_index *ix, int32_t k, int32_t beam, SearchLaunch &s) {
+    const SearchParams &p = ix->prm;
+    if (k < 1 || beam < k || beam > GRAB_MAX_BEAM) return grab_fail(ix, GRAB_EINVAL, "need 1 <= k <= beam <= %d", GRAB_MAX_BEAM);
+    s.k = k; s.beam = beam;
+    s.width = p.search_width;
+    s.max_iter = p.max_iter > 0 ? p.max_iter : 2 * beam;
+    s.n_seeds = p.n_seeds > 0 ? p.n_seeds : (beam < 64 ? beam : 64);
+    s.visited_cap = p.visited_cap;
+    s.salt = p.seed_salt;
+    if (s.n_seeds > s.visited_cap) return grab_fail(ix, GRAB_EINVAL, "n_seeds %d exceeds visited_cap %d", s.n_seeds, s.visited_cap);
+    if (s.width * (ix->kl + ix->kr) > GRAB_MAX_CAND) return grab_fail(ix, GRAB_EINVAL, "search_width * degree exceeds %d", GRAB_MAX_CAND);
+    s.only_bucket = nullptr;
+    s.out_slots = false;
+    return GRAB_OK;
+}
+
 extern "C" {
 
 grab_status grab_create(grab_index **out, int32_t dim, int32_t metric, void *hip_stream) {
@@ -85,6 +101,14 @@ grab_status grab_create(grab_index **out, int32_t dim, int32_t metric, void *hip
     ix->dim = dim;
     ix->metric = metric;
     ix->stream = (hipStream_t)hip_stream;
+    // with a device present: look up, once per device, where grab_search_range_noalloc's static
+    // work array lives on it (a host without a GPU can still create and destroy handles)
+    int n_dev = 0;
+    if (hipGetDeviceCount(&n_dev) != hipSuccess) { (void)hipGetLastError(); n_dev = 0; }
+    if (n_dev > 0 && grab_scratch_init(ix, nullptr) != GRAB_OK) {
+        delete ix;
+        return GRAB_EHIP;
+    }
     *out = ix;
     return GRAB_OK;
 }
@@ -254,29 +278,13 @@ grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, 
     return GRAB_OK;
 }
 
-static grab_status resolve_search(grab_index *ix, int32_t k, int32_t beam, SearchLaunch &s) {
-    const SearchParams &p = ix->prm;
-    if (k < 1 || beam < k || beam > GRAB_MAX_BEAM) return grab_fail(ix, GRAB_EINVAL, "need 1 <= k <= beam <= %d", GRAB_MAX_BEAM);
-    s.k = k; s.beam = beam;
-    s.width = p.search_width;
-    s.max_iter = p.max_iter > 0 ? p.max_iter : 2 * beam;
-    s.n_seeds = p.n_seeds > 0 ? p.n_seeds : (beam < 64 ? beam : 64);
-    s.visited_cap = p.visited_cap;
-    s.salt = p.seed_salt;
-    if (s.n_seeds > s.visited_cap) return grab_fail(ix, GRAB_EINVAL, "n_seeds %d exceeds visited_cap %d", s.n_seeds, s.visited_cap);
-    if (s.width * (ix->kl + ix->kr) > GRAB_MAX_CAND) return grab_fail(ix, GRAB_EINVAL, "search_width * degree exceeds %d", GRAB_MAX_CAND);
-    s.only_bucket = nullptr;
-    s.out_slots = false;
-    return GRAB_OK;
-}
-
 grab_status grab_search_range(grab_index *ix, const float *queries, const int32_t *lo, const int32_t *hi, int64_t nq,
                               int32_t k, int32_t beam, uint32_t *out_ids, float *out_dist) {
     if (!ix) return GRAB_EINVAL;
     if (!ix->has_graph) return grab_fail(ix, GRAB_ESTATE, "no graph loaded");
     if (nq < 0 || nq > (1ll << 30)) return grab_fail(ix, GRAB_EINVAL, "bad query count");
     SearchLaunch s;
-    grab_status st = resolve_search(ix, k, beam, s);
+    grab_status st = grab_resolve_search(ix, k, beam, s);
     if (st != GRAB_OK) return st;
     if (nq == 0) { ix->last_nq = 0; return GRAB_OK; }
     if (!queries || !lo || !hi || !out_ids || !out_dist) return grab_fail(ix, GRAB_EINVAL, "null argument");
@@ -303,6 +311,7 @@ grab_status grab_search_range(grab_index *ix, const float *queries, const int32_
     if ((st = grab_launch_beam(ix, s)) != GRAB_OK) return st;
     if (ix->profile) { GRAB_HIP(ix, hipEventRecord(ix->ev[2], ix->stream)); ix->timed = true; }
     ix->last_nq = nq;
+    ix->last_counters = s.counters;
     if (!ids_dev) GRAB_HIP(ix, hipMemcpyAsync(out_ids, s.out_ids, (size_t)nq * k * 4, hipMemcpyDeviceToHost, ix->stream));
     if (!dist_dev) GRAB_HIP(ix, hipMemcpyAsync(out_dist, s.out_dist, (size_t)nq * k * 4, hipMemcpyDeviceToHost, ix->stream));
     if (!ids_dev || !dist_dev || dq != (const void *)queries || dlo != (const void *)lo || dhi != (const void *)hi)
@@ -316,7 +325,7 @@ grab_status grab_select_range(grab_index *ix, const int32_t *lo, const int32_t *
     if (!ix->X) return grab_fail(ix, GRAB_ESTATE, "build_buckets first");
     if (nq < 0) return grab_fail(ix, GRAB_EINVAL, "bad query count");
     SearchLaunch s;
-    grab_status st = resolve_search(ix, 1, beam, s);
+    grab_status st = grab_resolve_search(ix, 1, beam, s);
     if (st != GRAB_OK) return st;
     if (nq == 0) return GRAB_OK;
     if (!lo || !hi || !info) return grab_fail(ix, GRAB_EINVAL, "null argument");
@@ -390,7 +399,7 @@ grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq) {
     if (nq > ix->last_nq) return grab_fail(ix, GRAB_EINVAL, "last search had %lld queries", (long long)ix->last_nq);
     if (nq == 0) return GRAB_OK;
     GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
-    GRAB_HIP(ix, hipMemcpy(per_query, ix->counters.p, (size_t)nq * 8 * 4, hipMemcpyDefault));
+    GRAB_HIP(ix, hipMemcpy(per_query, ix->last_counters, (size_t)nq * 8 * 4, hipMemcpyDefault));
     return GRAB_OK;
 }
 
@@ -437,7 +446,7 @@ grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_
         return grab_fail(ix, GRAB_EFULL, "%lld objects + %lld new exceed the %lld slots of the index", (long long)ix->n,
                          (long long)m, (long long)ix->n_slots);
     SearchLaunch proto;
-    grab_status st = resolve_search(ix, ix->prm.append_beam, ix->prm.append_beam, proto);
+    grab_status st = grab_resolve_search(ix, ix->prm.append_beam, ix->prm.append_beam, proto);
     if (st != GRAB_OK) return st;
     const void *dv, *da;
     if ((st = grab_to_device(ix, vectors, (size_t)m * ix->dim * 4, ix->stage_q, &dv)) != GRAB_OK) return st;

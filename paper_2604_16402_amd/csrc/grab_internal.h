@@ -78,6 +78,7 @@ struct grab_index {
     // launch order of the queries of a search (grab_plan_order)
     DevBuf q_bin, q_rank, q_order, bin_count;
     int64_t last_nq = 0;
+    const uint32_t *last_counters = nullptr;   // where the most recent search wrote its counters
     std::vector<DevBuf> app;     // append's work arena
 
     bool profile = false;
@@ -129,6 +130,12 @@ struct SearchLaunch {
 // contiguous run of that order per XCD (queries that read the same buckets then share L2 and the
 // Infinity Cache); fills the order fields of `s`, or leaves them null for small batches.
 grab_status grab_plan_order(grab_index *ix, SearchLaunch &s);
+// entries of the launch-order array for a batch of nq queries (nq >= 2048)
+int64_t grab_order_len(int64_t nq);
+// fills the parameter fields of `s` from the index's tunables for (k, beam); validates them
+grab_status grab_resolve_search(grab_index *ix, int32_t k, int32_t beam, SearchLaunch &s);
+// device address, on the current device, of the static work array of grab_search_range_noalloc
+grab_status grab_scratch_init(grab_index *ix, unsigned char **out);
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s);
 grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s);
 // measurement aid: `waves` wavefronts each read `batches` batches of random rows; *bytes = rows read x row size

@@ -580,13 +580,15 @@ grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batc
     }
 }
 
+int64_t grab_order_len(int64_t nq) { return (nq + 8 * GRAB_ORDER_RUN - 1) / (8 * GRAB_ORDER_RUN) * (8 * GRAB_ORDER_RUN); }
+
 grab_status grab_plan_order(grab_index *ix, SearchLaunch &s) {
     s.q_bin = s.q_rank = s.bin_count = nullptr;
     s.order = nullptr;
     s.order_len = 0;
     if (s.nq < 2048) return GRAB_OK;   // a batch that does not even fill the device once gains nothing
     // room for either run length k_order may choose: nq rounded up to eight short runs
-    const int64_t len = (s.nq + 8 * GRAB_ORDER_RUN - 1) / (8 * GRAB_ORDER_RUN) * (8 * GRAB_ORDER_RUN);
+    const int64_t len = grab_order_len(s.nq);
     grab_status st;
     if ((st = grab_reserve(ix, ix->q_bin, (size_t)s.nq * 4)) != GRAB_OK) return st;
     if ((st = grab_reserve(ix, ix->q_rank, (size_t)s.nq * 4)) != GRAB_OK) return st;
