@@ -147,18 +147,22 @@ static uint32_t mix32(uint32_t x) {
     return x;
 }
 
+uint32_t oracle_mix32(uint32_t x) { return mix32(x); }   /* for the test that pins it on published values */
+
 /* ---------------------------------------------------------------- seeding (A3)
  * Algorithm 2 line 2 (SampleSeedsFrom(B_valid)).
  * reading: the seed population P is, over the selected buckets in order, the valid part
  * of the sorted prefix followed by the whole appended tail; V = |P|.  If V <= S every
  * member is a seed.  Otherwise seed j is P[floor(j*V/S) + mix32(j ^ salt) mod floor(V/S)]:
- * one seed per stratum with an integer jitter.  `only_bucket` >= 0 restricts P to that
- * bucket's whole slab contents (used by append).
+ * one seed per stratum with an integer jitter.  `scope` (see search_one) >= 0 restricts P to that
+ * bucket's whole contents; scope <= -2 makes P the whole contents of every bucket but one, in
+ * bucket order (both used by append and by the construction's second pass).
  * Writes seed slots to seeds[0..S) (EMPTY-padded); returns the count; *V_out = V;
  * span[0] = first valid sorted slot of b0, span[1] = end of valid sorted slots of b1. */
-static int64_t population_member(const oracle_index *ix, int b0, int b1, const int64_t *sa,
+static int64_t population_member(const oracle_index *ix, int b0, int b1, int skip, const int64_t *sa,
                                  const int64_t *se, int64_t i) {
     for (int b = b0; b <= b1; ++b) {
+        if (b == skip) continue;
         const int32_t *t = ix->table + 6 * b;
         int64_t ns = se[b - b0] - sa[b - b0];
         if (i < ns) return t[T_BASE] + sa[b - b0] + i;
@@ -170,7 +174,7 @@ static int64_t population_member(const oracle_index *ix, int b0, int b1, const i
     return -1;
 }
 
-static int64_t make_seeds(const oracle_index *ix, int32_t lo, int32_t hi, int only_bucket,
+static int64_t make_seeds(const oracle_index *ix, int32_t lo, int32_t hi, int scope,
                           const oracle_params *pr, uint32_t *seeds, int64_t *V_out,
                           int *b0_out, int *b1_out, int64_t span[2]) {
     int b0, b1;
@@ -178,8 +182,12 @@ static int64_t make_seeds(const oracle_index *ix, int32_t lo, int32_t hi, int on
     for (int64_t j = 0; j < S; ++j) seeds[j] = EMPTY;
     *V_out = 0;
     span[0] = span[1] = 0;
-    if (only_bucket >= 0) {
-        b0 = b1 = only_bucket;
+    const int skip = scope <= -2 ? -2 - scope : -1;
+    if (scope >= 0) {
+        b0 = b1 = scope;
+    } else if (skip >= 0) {
+        b0 = 0;
+        b1 = ix->n_buckets - 1;
     } else if (!select_buckets(ix, lo, hi, &b0, &b1)) {
         *b0_out = 0;
         *b1_out = -1;
@@ -192,25 +200,32 @@ static int64_t make_seeds(const oracle_index *ix, int32_t lo, int32_t hi, int on
     int64_t V = 0;
     for (int b = b0; b <= b1; ++b) {
         const int32_t *t = ix->table + 6 * b;
-        if (only_bucket >= 0) {
+        if (scope >= 0 || skip >= 0) {
             sa[b - b0] = 0;
             se[b - b0] = t[T_NSORT];
         } else {
             sorted_span(ix, b, lo, hi, &sa[b - b0], &se[b - b0]);
         }
-        V += (se[b - b0] - sa[b - b0]) + (t[T_NTOT] - t[T_NSORT]);
+        if (b != skip) V += (se[b - b0] - sa[b - b0]) + (t[T_NTOT] - t[T_NSORT]);
     }
     span[0] = ix->table[6 * b0 + T_BASE] + sa[0];
     span[1] = ix->table[6 * b1 + T_BASE] + se[nb - 1];
     *V_out = V;
+    if (V == 0 && skip >= 0) {   /* nothing outside the only bucket: an empty selection */
+        *b0_out = 0;
+        *b1_out = -1;
+        free(sa);
+        free(se);
+        return 0;
+    }
     int64_t count = 0;
     if (V <= S) {
-        for (int64_t i = 0; i < V; ++i) seeds[count++] = (uint32_t)population_member(ix, b0, b1, sa, se, i);
+        for (int64_t i = 0; i < V; ++i) seeds[count++] = (uint32_t)population_member(ix, b0, b1, skip, sa, se, i);
     } else {
         uint64_t stride = (uint64_t)(V / S);
         for (int64_t j = 0; j < S; ++j) {
             uint64_t pos = ((uint64_t)j * (uint64_t)V) / (uint64_t)S + (uint64_t)mix32((uint32_t)j ^ pr->seed_salt) % stride;
-            seeds[count++] = (uint32_t)population_member(ix, b0, b1, sa, se, (int64_t)pos);
+            seeds[count++] = (uint32_t)population_member(ix, b0, b1, skip, sa, se, (int64_t)pos);
         }
     }
     free(sa);
@@ -290,10 +305,12 @@ static int in_edge_tail(const oracle_index *ix, int b0, int b1, uint32_t v) {
  *  - a neighbour is pre-checked first, then looked up in the visited set, then evaluated;
  *    rejected neighbours are not recorded as visited;
  *  - the queue keeps the best `beam` entries ordered by (distance, slot).
- * `only_bucket` >= 0 (append's local candidate search) replaces the attribute test by
- * "slot lies in that bucket's slab".  Leaves the final queue in sc->Q, returns its length. */
+ * `scope` is the scope of the search: -1 = the attribute range [lo,hi]; b >= 0 (the local
+ * candidate search of an insertion) replaces the attribute test by "slot lies in bucket b's
+ * slab"; -2 - b (the global-scope candidate search) by "slot lies outside bucket b's slab".
+ * Leaves the final queue in sc->Q, returns its length. */
 static int64_t search_one(const oracle_index *ix, const oracle_params *pr, const float *q,
-                          int32_t lo, int32_t hi, int only_bucket, int32_t beam, scratch *sc,
+                          int32_t lo, int32_t hi, int scope, int32_t beam, scratch *sc,
                           uint32_t *ctr) {
     const int K = ix->k_local + ix->k_remote;
     const int w = pr->search_width;
@@ -301,14 +318,14 @@ static int64_t search_one(const oracle_index *ix, const oracle_params *pr, const
     int64_t V, span[2];
     uint32_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     scratch_fit(sc, (int64_t)pr->visited_cap + 1, (int64_t)beam + (int64_t)w * K + pr->n_seeds, pr->n_seeds);
-    int64_t ns = make_seeds(ix, lo, hi, only_bucket, pr, sc->seeds, &V, &b0, &b1, span);
+    int64_t ns = make_seeds(ix, lo, hi, scope, pr, sc->seeds, &V, &b0, &b1, span);
     entry *Q = sc->Q;
     int64_t nQ = 0;
     sc->n_touched = 0;
     if (b1 < b0) c[C_STOP] = 3;
     for (int64_t j = 0; j < ns; ++j) {
         uint32_t v = sc->seeds[j];
-        if (only_bucket < 0) {
+        if (scope == -1) {
             if (in_edge_tail(ix, b0, b1, v)) c[C_TAIL]++;
             if (ix->attr[v] < lo || ix->attr[v] > hi) continue;
         }
@@ -340,8 +357,10 @@ static int64_t search_one(const oracle_index *ix, const oracle_params *pr, const
             for (int j = 0; j < K; ++j) {
                 uint32_t v = ix->A[(size_t)pslot[i] * K + j];
                 if (v == EMPTY) continue;
-                if (only_bucket >= 0) {
-                    if (bucket_of_slot(ix, v) != only_bucket) { c[C_REJECTS]++; continue; }
+                if (scope >= 0) {
+                    if (bucket_of_slot(ix, v) != scope) { c[C_REJECTS]++; continue; }
+                } else if (scope <= -2) {
+                    if (bucket_of_slot(ix, v) == -2 - scope) { c[C_REJECTS]++; continue; }
                 } else {
                     if (in_edge_tail(ix, b0, b1, v)) c[C_TAIL]++;
                     if (ix->attr[v] < lo || ix->attr[v] > hi) { c[C_REJECTS]++; continue; }
@@ -399,6 +418,23 @@ int oracle_search(const oracle_index *ix, const oracle_params *pr, const float *
     return 0;
 }
 
+/* The candidate searches of insertion and construction, exposed for tests: query i runs with
+ * scope[i] (see search_one) and leaves its whole final queue, `beam` entries as slots and
+ * distances ordered by (distance, slot), padded with (0xFFFFFFFF, +inf). */
+int oracle_search_scoped(const oracle_index *ix, const oracle_params *pr, const float *queries, const int32_t *scope,
+                         int64_t nq, int32_t beam, uint32_t *out_slots, float *out_dist) {
+    scratch *sc = scratch_new(ix->n_cap);
+    for (int64_t qi = 0; qi < nq; ++qi) {
+        int64_t nQ = search_one(ix, pr, queries + (size_t)qi * ix->dim, 0, 0, scope[qi], beam, sc, NULL);
+        for (int j = 0; j < beam; ++j) {
+            out_slots[qi * beam + j] = j < nQ ? sc->Q[j].slot : EMPTY;
+            out_dist[qi * beam + j] = j < nQ ? sc->Q[j].dist : INFINITY;
+        }
+    }
+    scratch_free(sc);
+    return 0;
+}
+
 int oracle_max_threads(void) {
 #ifdef _OPENMP
     return omp_get_max_threads();
@@ -439,7 +475,7 @@ int oracle_max_threads(void) {
  *     recall of the dynamic workload decayed with every batch.)
  *  5. Reverse requests: one per written edge q->v: (v, kind, dist(v,q), q).  Sorted by
  *     (v, kind, distance image, q's slot) and applied one after another per target.  With
- *     a = alpha (squared for the squared-L2 metric, so that the test is the paper's on true
+ *     a = alpha squared (distances here are squared, so that the test is the paper's on true
  *     Euclidean distances):
  *     local kind, R = local part of v's row:
  *       pass  = a*dist(v,q) < dist(q,n) for every n in R           (Eq. 2 with Eq. 3's d_eff)
@@ -463,7 +499,66 @@ int oracle_max_threads(void) {
  *       fills the first empty entry, if any.
  *     Fresh nodes already placed in R by this batch count as ordinary neighbours.
  *  6. Table: n_total grows by the bucket's batch count; min/max absorb the new attributes.
+ *
+ * Steps 3-5 above wire the remote part by target bucket (remote_rule.mode 0).  The paper's own wording
+ * is the second reading kept here (remote_rule.mode 1; Section 4.4 "Parallel Candidate Search": candidates
+ * from the target bucket and from the global scope; Section 4.3 "Remote Edge Construction": the
+ * remote budget split into proximal and global candidates, redundant local edges kept where too
+ * few qualify).  It differs in the remote part only:
+ *  3'. A second run of the search with the new vector as query and the scope "every slot outside
+ *      the target bucket's slab" (same parameters, beam = append_beam): the global candidates,
+ *      ordered by (distance, slot).
+ *  4'. Remote part: scan the global candidates in order.  A candidate whose attribute differs from
+ *      the new object's by at most `window` is proximal, any other one global.  The first
+ *      n_proximal proximal ones fill remote positions 0.., the first K_remote - n_proximal global
+ *      ones the positions n_proximal..; no diversity test (Section 4.3 filters and ranks).  A
+ *      position left without a pick takes the nearest local candidate not yet in the row (the
+ *      redundant local edge that Section 4.3 keeps rather than leave an entry empty), else stays
+ *      empty.  Only picks that leave the bucket make a reverse request.
+ *  5'. Remote request at v: q is proximal to v iff |attr(q) - attr(v)| <= window, and competes
+ *      for the remote positions of its class only.  It takes the first of them that is empty or
+ *      holds a node of v's own bucket (a redundant local edge is there to be overwritten by a
+ *      remote one); if there is none, the entry of these positions farthest from v (ties: larger
+ *      slot) gives way iff a*dist(v,q) < its distance to v: each class keeps the nearest nodes it
+ *      has seen, the fresh one favoured by the bias (Eq. 3).
+ *
+ * Inner-product metric: Eq. 3 scales a distance, and minus the inner product is not one (it is
+ * negative for similar vectors, so scaling it by alpha < 1 would push a newcomer away).  Both
+ * sides of every biased comparison are therefore shifted first: s(d) = max(0, 1 + d), which for
+ * unit vectors is half the squared Euclidean distance, and the bias acts as alpha^2 on it, as on
+ * squared Euclidean distances.  The comparison "a*dist(x) < dist(y)" reads a*s(dist(x)) < s(dist(y)).
  */
+typedef struct {
+    int32_t mode;        /* 0: remote entry j belongs to the j-th target bucket; 1: proximal / global split */
+    int32_t n_proximal;  /* mode 1: remote positions reserved for proximal candidates (0..K_remote) */
+    int64_t window;      /* mode 1: largest attribute difference of a proximal candidate */
+} remote_rule;
+
+/* the quantity the freshness bias scales (see above): the distance itself for squared L2 */
+static float bias_base(const oracle_index *ix, float d) {
+    if (ix->metric == 0) return d;
+    float s = 1.0f + d;
+    return s > 0.0f ? s : 0.0f;
+}
+
+/* Section 4.3, remote edge selection over candidates ordered by (distance, slot): picks[0..kp) the
+ * nearest proximal ones, picks[kp..kr) the nearest global ones, EMPTY where the class runs out */
+static void select_remote(const oracle_index *ix, int32_t attr_u, const uint32_t *gs, const float *gd, int ng,
+                          const remote_rule *rr, uint32_t *picks, float *pickd) {
+    const int kr = ix->k_remote, kp = rr->n_proximal;
+    int np = 0, ngl = 0;
+    for (int j = 0; j < kr; ++j) { picks[j] = EMPTY; pickd[j] = 0.0f; }
+    for (int t = 0; t < ng; ++t) {
+        int64_t diff = (int64_t)ix->attr[gs[t]] - (int64_t)attr_u;
+        if (diff < 0) diff = -diff;
+        if (diff <= rr->window) {
+            if (np < kp) { picks[np] = gs[t]; pickd[np] = gd[t]; np++; }
+        } else if (ngl < kr - kp) {
+            picks[kp + ngl] = gs[t]; pickd[kp + ngl] = gd[t]; ngl++;
+        }
+    }
+}
+
 typedef struct {
     uint32_t v;      /* target (existing node) slot */
     uint32_t kind;   /* 0 local, 1 remote */
@@ -507,8 +602,10 @@ static int forward_select(const oracle_index *ix, const uint32_t *cs, const floa
  * kept_out (may be NULL): per new node {entries kept by Eq. 2 in the local part, in the remote part}. */
 int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_t append_beam,
                   const float *vecs, const int32_t *attrs, int64_t m, int64_t n_prev, uint32_t *id2slot,
-                  int32_t *kept_out, int32_t threads) {
+                  int32_t *kept_out, int32_t threads, const remote_rule *rr) {
     const int B = ix->n_buckets, kl = ix->k_local, kr = ix->k_remote, K = kl + kr, dim = ix->dim;
+    const int mode = rr ? rr->mode : 0;
+    if (mode != 0 && (mode != 1 || rr->n_proximal < 0 || rr->n_proximal > kr || rr->window < 0)) return 1;
     int32_t *bucket = (int32_t *)malloc(sizeof(int32_t) * (size_t)m);
     uint32_t *slot = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)m);
     int64_t *count = (int64_t *)calloc((size_t)B, sizeof(int64_t));
@@ -541,6 +638,7 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
     /* 3 + 4 on the snapshot */
     uint32_t *rows = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)m * K);
     float *rowd = (float *)malloc(sizeof(float) * (size_t)m * K);   /* dist(q, row entry) */
+    uint8_t *rowk = (uint8_t *)malloc((size_t)m * K);               /* request kind: 0 local, 1 remote, 2 none */
 #ifdef _OPENMP
     if (threads < 1) threads = 1;
 #pragma omp parallel num_threads(threads)
@@ -549,6 +647,8 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         scratch *sc = scratch_new(ix->n_cap);
         uint32_t *cs = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)append_beam);
         float *cd = (float *)malloc(sizeof(float) * (size_t)append_beam);
+        uint32_t *gs = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)append_beam);
+        float *gd = (float *)malloc(sizeof(float) * (size_t)append_beam);
 #ifdef _OPENMP
 #pragma omp for schedule(static)
 #endif
@@ -566,7 +666,9 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
                 if (row[j] != EMPTY)
                     for (int t = 0; t < nc; ++t) if (cs[t] == row[j]) d = cd[t];
                 rowd[(size_t)i * K + j] = d;
+                rowk[(size_t)i * K + j] = 0;
             }
+            if (mode == 0) {
             /* remote part: entry j is the nearest to q among the j-th remote entries of its local
              * candidates (they all lie in the j-th target bucket when the graph was built that way) */
             for (int j = 0; j < kr; ++j) {
@@ -580,11 +682,31 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
                 }
                 row[kl + j] = best;
                 rowd[(size_t)i * K + kl + j] = best_d;
+                rowk[(size_t)i * K + kl + j] = 1;
                 if (best != EMPTY) kept[1]++;
+            }
+            } else {
+            /* 3', 4': global-scope candidates, proximal / global picks, redundant local edges elsewhere */
+            int64_t nG = search_one(ix, pr, q, 0, 0, -2 - bucket[i], append_beam, sc, NULL);
+            int ng = 0;
+            for (int64_t j = 0; j < nG; ++j) { gs[ng] = sc->Q[j].slot; gd[ng] = sc->Q[j].dist; ng++; }
+            select_remote(ix, attrs[i], gs, gd, ng, rr, row + kl, rowd + (size_t)i * K + kl);
+            int next_local = 0;
+            for (int j = 0; j < kr; ++j) {
+                rowk[(size_t)i * K + kl + j] = 1;
+                if (row[kl + j] != EMPTY) { kept[1]++; continue; }
+                rowk[(size_t)i * K + kl + j] = 2;      /* no reverse request for a fallback entry */
+                for (; next_local < nc; ++next_local) {
+                    int used = 0;
+                    for (int x = 0; x < kl; ++x) if (row[x] == cs[next_local]) used = 1;
+                    if (!used) break;
+                }
+                if (next_local < nc) row[kl + j] = cs[next_local++];
+            }
             }
             if (kept_out) { kept_out[2 * i] = kept[0]; kept_out[2 * i + 1] = kept[1]; }
         }
-        free(cs); free(cd);
+        free(cs); free(cd); free(gs); free(gd);
         scratch_free(sc);
     }
     /* write the new nodes */
@@ -599,22 +721,32 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         memcpy(ix->A + (size_t)s * K, rows + (size_t)i * K, sizeof(uint32_t) * (size_t)K);
         for (int j = 0; j < K; ++j) {
             uint32_t v = rows[(size_t)i * K + j];
-            if (v == EMPTY) continue;
+            if (v == EMPTY || rowk[(size_t)i * K + j] == 2) continue;
             float d = rowd[(size_t)i * K + j];
-            req[nreq].v = v; req[nreq].kind = j < kl ? 0u : 1u; req[nreq].img = dist_image(d);
+            req[nreq].v = v; req[nreq].kind = rowk[(size_t)i * K + j]; req[nreq].img = dist_image(d);
             req[nreq].q = s; req[nreq].dist = d;
             nreq++;
         }
     }
-    /* 5 */
+    /* 5: requests of one target are applied in order; different targets touch different rows, so
+     * the targets may be worked on in parallel without changing any result */
     qsort(req, (size_t)nreq, sizeof(request), request_cmp);
-    const float a = ix->metric == 0 ? alpha * alpha : alpha;
-    for (int64_t r = 0; r < nreq; ++r) {
+    const float a = alpha * alpha;
+    int64_t ngroups = 0;
+    int64_t *gstart = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nreq + 1));
+    for (int64_t r = 0; r < nreq; ++r)
+        if (r == 0 || req[r].v != req[r - 1].v) gstart[ngroups++] = r;
+    gstart[ngroups] = nreq;
+#ifdef _OPENMP
+#pragma omp parallel for schedule(dynamic, 64) num_threads(threads)
+#endif
+    for (int64_t g = 0; g < ngroups; ++g)
+    for (int64_t r = gstart[g]; r < gstart[g + 1]; ++r) {
         uint32_t *R = ix->A + (size_t)req[r].v * K + (req[r].kind == 0 ? 0 : kl);
         int len = req[r].kind == 0 ? kl : kr;
         const float *xq = ix->X + (size_t)req[r].q * dim, *xv = ix->X + (size_t)req[r].v * dim;
-        float lhs = a * req[r].dist;
-        if (req[r].kind == 1) {
+        float lhs = a * bias_base(ix, req[r].dist);
+        if (req[r].kind == 1 && mode == 0) {
             /* remote part of v: the entry that points into q's bucket keeps the nearest node of
              * that bucket, the fresh node judged by its biased distance (Eq. 3) */
             int bq = bucket_of_slot(ix, req[r].q);
@@ -627,9 +759,29 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             }
             if (far >= 0) {
                 float dfar = oracle_distance(xv, ix->X + (size_t)R[far] * dim, dim, ix->metric);
-                if (lhs < dfar) R[far] = req[r].q;
+                if (lhs < bias_base(ix, dfar)) R[far] = req[r].q;
             } else if (empty_at >= 0) {
                 R[empty_at] = req[r].q;
+            }
+            continue;
+        }
+        if (req[r].kind == 1) {
+            /* 5': q competes for the remote positions of its class (proximal or global relative to v) */
+            int64_t diff = (int64_t)ix->attr[req[r].q] - (int64_t)ix->attr[req[r].v];
+            if (diff < 0) diff = -diff;
+            const int j0 = diff <= rr->window ? 0 : rr->n_proximal, j1 = diff <= rr->window ? rr->n_proximal : kr;
+            const int bv = bucket_of_slot(ix, req[r].v);
+            int take = -1, far = -1; uint32_t far_img = 0;
+            for (int j = j0; j < j1 && take < 0; ++j)
+                if (R[j] == EMPTY || bucket_of_slot(ix, R[j]) == bv) take = j;
+            if (take >= 0) { R[take] = req[r].q; continue; }
+            for (int j = j0; j < j1; ++j) {
+                uint32_t im = dist_image(oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric));
+                if (far < 0 || im > far_img || (im == far_img && R[j] > R[far])) { far = j; far_img = im; }
+            }
+            if (far >= 0) {
+                float dfar = oracle_distance(xv, ix->X + (size_t)R[far] * dim, dim, ix->metric);
+                if (lhs < bias_base(ix, dfar)) R[far] = req[r].q;
             }
             continue;
         }
@@ -637,7 +789,7 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         for (int j = 0; j < len; ++j) {
             if (R[j] == EMPTY) { if (empty_at < 0) empty_at = j; continue; }
             float dqn = oracle_distance(xq, ix->X + (size_t)R[j] * dim, dim, ix->metric);
-            if (!(lhs < dqn)) pass = 0;
+            if (!(lhs < bias_base(ix, dqn))) pass = 0;
         }
         if (!pass) continue;
         if (empty_at >= 0) { R[empty_at] = req[r].q; continue; }
@@ -654,6 +806,7 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         }
         if (victim >= 0) R[victim] = req[r].q;
     }
+    free(gstart);
     /* 6 */
     for (int64_t i = 0; i < m; ++i) {
         int32_t *t = ix->table + 6 * bucket[i];
@@ -661,7 +814,7 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         if (attrs[i] > t[T_MAX]) t[T_MAX] = attrs[i];
     }
     for (int b = 0; b < B; ++b) ix->table[6 * b + T_NTOT] += (int32_t)count[b];
-    free(req); free(rows); free(rowd); free(bucket); free(slot); free(count);
+    free(req); free(rows); free(rowd); free(rowk); free(bucket); free(slot); free(count);
     return 0;
 }
 
@@ -688,6 +841,20 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
  *     [0,B) are skipped; the first K_remote distinct ones count.  Fewer than K_remote targets
  *     leave empty entries (the paper's fallback to redundant local edges is not used, so that
  *     the remote part never holds an edge that stays inside the bucket).
+ *
+ * Step 5 is the remote wiring by target bucket (remote_rule.mode 0).  The second reading
+ * (remote_rule.mode 1) follows Section 4.3's own words, with the library's search in the place of
+ * the third-party global graph as the source of cross-bucket candidates:
+ *  4'. The interleaved merge goes on past K_local: after F and R are exhausted up to K_local it
+ *      continues with the rest of F; the first K_local survivors are the necessary local edges,
+ *      the next K_remote the redundant ones, stored in the remote part of the row.
+ *  5'. For every node u, against the graph as step 4' left it (all nodes are processed against
+ *      that same graph): global candidates = one run of the search (Algorithm 2) with u's vector
+ *      as query and the scope "every slot outside u's bucket", beam entries, ordered by
+ *      (distance, slot).  A candidate whose attribute differs from u's by at most `window` is
+ *      proximal, any other global.  The first n_proximal proximal ones overwrite remote positions
+ *      0.., the first K_remote - n_proximal global ones the positions n_proximal..; a position
+ *      without a pick keeps its redundant local edge.
  */
 typedef struct {
     uint32_t img, slot;
@@ -773,10 +940,72 @@ static int rev_cmp(const void *a, const void *b) {
     return 0;
 }
 
+/* Pass 2 alone (step 5 or 5'), on whatever graph the index holds: rewrites the remote part of
+ * every row.  mode 0 needs no search parameters (pr may be NULL). */
+int oracle_build_remote(oracle_index *ix, const remote_rule *rr, const oracle_params *pr, int32_t beam, int32_t threads) {
+    const int kl = ix->k_local, kr = ix->k_remote, K = kl + kr, B = ix->n_buckets;
+    const int mode = rr ? rr->mode : 0;
+    if (threads < 1) threads = 1;
+    if (kr == 0) return 0;
+    if (mode == 0) {
+        for (int b = 0; b < B; ++b) {
+            const int32_t *t = ix->table + 6 * b;
+            int32_t tg[64];
+            int nt = oracle_remote_targets(b, B, kr, tg);
+#ifdef _OPENMP
+#pragma omp parallel for schedule(static) num_threads(threads)
+#endif
+            for (int64_t j = 0; j < t[T_NTOT]; ++j) {
+                uint32_t u = (uint32_t)(t[T_BASE] + j);
+                for (int r = 0; r < kr; ++r) ix->A[(size_t)u * K + kl + r] = EMPTY;
+                for (int r = 0; r < nt; ++r) {
+                    float d;
+                    oracle_knn(ix, u, tg[r], 1, ix->A + (size_t)u * K + kl + r, &d);
+                }
+            }
+        }
+        return 0;
+    }
+    if (mode != 1 || !pr || rr->n_proximal < 0 || rr->n_proximal > kr || rr->window < 0 || beam < 1) return 1;
+    /* every search runs against the graph as it is now, not against rows already rewritten */
+    oracle_index snap = *ix;
+    snap.A = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)ix->n_cap * K);
+    memcpy(snap.A, ix->A, sizeof(uint32_t) * (size_t)ix->n_cap * K);
+#ifdef _OPENMP
+#pragma omp parallel num_threads(threads)
+#endif
+    {
+        scratch *sc = scratch_new(ix->n_cap);
+        uint32_t *gs = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)beam), *picks = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)kr);
+        float *gd = (float *)malloc(sizeof(float) * (size_t)beam), *pickd = (float *)malloc(sizeof(float) * (size_t)kr);
+        for (int b = 0; b < B; ++b) {
+            const int32_t *t = ix->table + 6 * b;
+#ifdef _OPENMP
+#pragma omp for schedule(dynamic, 16)
+#endif
+            for (int64_t j = 0; j < t[T_NTOT]; ++j) {
+                uint32_t u = (uint32_t)(t[T_BASE] + j);
+                int64_t nG = search_one(&snap, pr, ix->X + (size_t)u * ix->dim, 0, 0, -2 - b, beam, sc, NULL);
+                int ng = 0;
+                for (int64_t x = 0; x < nG; ++x) { gs[ng] = sc->Q[x].slot; gd[ng] = sc->Q[x].dist; ng++; }
+                select_remote(ix, ix->attr[u], gs, gd, ng, rr, picks, pickd);
+                for (int r = 0; r < kr; ++r)
+                    if (picks[r] != EMPTY) ix->A[(size_t)u * K + kl + r] = picks[r];
+            }
+        }
+        free(gs); free(gd); free(picks); free(pickd);
+        scratch_free(sc);
+    }
+    free(snap.A);
+    return 0;
+}
+
 /* Fills ix->A (all rows) for the objects currently in the index.  F_out/R_out (may be NULL)
  * receive the forward lists [n_cap][pool] and reverse lists [n_cap][k_local] for inspection. */
-int oracle_build_graph(oracle_index *ix, int32_t pool, uint32_t *F_out, uint32_t *R_out, int32_t threads) {
+int oracle_build_graph(oracle_index *ix, int32_t pool, uint32_t *F_out, uint32_t *R_out, int32_t threads,
+                       const remote_rule *rr, const oracle_params *pr, int32_t beam) {
     const int kl = ix->k_local, kr = ix->k_remote, K = kl + kr, B = ix->n_buckets;
+    const int mode = rr ? rr->mode : 0;
     if (pool < kl || kl < 0 || kr < 0 || K < 1) return 1;
     const int64_t N = ix->n_cap;
     uint32_t *F = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)N * pool);
@@ -788,18 +1017,12 @@ int oracle_build_graph(oracle_index *ix, int32_t pool, uint32_t *F_out, uint32_t
     if (threads < 1) threads = 1;
     for (int b = 0; b < B; ++b) {
         const int32_t *t = ix->table + 6 * b;
-        int32_t tg[64];
-        int nt = oracle_remote_targets(b, B, kr, tg);
 #ifdef _OPENMP
 #pragma omp parallel for schedule(static) num_threads(threads)
 #endif
         for (int64_t j = 0; j < t[T_NTOT]; ++j) {
             uint32_t u = (uint32_t)(t[T_BASE] + j);
             forward_list(ix, u, b, pool, F + (size_t)u * pool, Fd + (size_t)u * pool);
-            for (int r = 0; r < nt; ++r) {
-                float d;
-                oracle_knn(ix, u, tg[r], 1, ix->A + (size_t)u * K + kl + r, &d);
-            }
         }
     }
     /* reverse lists */
@@ -817,12 +1040,14 @@ int oracle_build_graph(oracle_index *ix, int32_t pool, uint32_t *F_out, uint32_t
         if (p > 0 && E[p].v != E[p - 1].v) start = p;
         if (p - start < kl) R[(size_t)E[p].v * kl + (p - start)] = E[p].u;
     }
-    /* interleaved merge */
+    /* interleaved merge: `want` entries per row (mode 1 also fills the redundant positions) */
+    const int want = mode == 1 ? K : kl;
     for (int64_t u = 0; u < N; ++u) {
         uint32_t *row = ix->A + (size_t)u * K;
         int w = 0;
-        for (int j = 0; j < kl && w < kl; ++j)
-            for (int side = 0; side < 2 && w < kl; ++side) {
+        for (int j = 0; j < pool && w < want; ++j)
+            for (int side = 0; side < 2 && w < want; ++side) {
+                if (side == 1 && j >= kl) continue;      /* the reverse list has K_local entries */
                 uint32_t c = side == 0 ? F[(size_t)u * pool + j] : R[(size_t)u * kl + j];
                 if (c == EMPTY) continue;
                 int dup = 0;
@@ -833,5 +1058,5 @@ int oracle_build_graph(oracle_index *ix, int32_t pool, uint32_t *F_out, uint32_t
     if (F_out) memcpy(F_out, F, sizeof(uint32_t) * (size_t)N * pool);
     if (R_out) memcpy(R_out, R, sizeof(uint32_t) * (size_t)N * kl);
     free(F); free(Fd); free(R); free(E);
-    return 0;
+    return oracle_build_remote(ix, rr, pr, beam, threads);
 }

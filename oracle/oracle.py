@@ -42,8 +42,8 @@ class _Params(ctypes.Structure):
                 ("seed_salt", ctypes.c_uint32)]
 
 
-class _AppendParams(ctypes.Structure):
-    _fields_ = [("alpha", ctypes.c_float), ("append_beam", ctypes.c_int32)]
+class _RemoteRule(ctypes.Structure):
+    _fields_ = [("mode", ctypes.c_int32), ("n_proximal", ctypes.c_int32), ("window", ctypes.c_int64)]
 
 
 def _load():
@@ -153,8 +153,11 @@ class Index:
         self.attr[live] = attrs[self.slot2id[live]]
         self.k_local = self.k_remote = 0
         self.A = None
+        # remote_mode 0: remote entry j belongs to the j-th target bucket; 1: proximal / global split
+        # (n_proximal None = ceil(k_remote / 2); remote_window = fraction of the attribute span)
         self.params = dict(search_width=1, max_iter=None, n_seeds=None, visited_cap=2800,
-                           seed_salt=0, alpha=0.6, append_beam=64)
+                           seed_salt=0, alpha=0.6, append_beam=64, remote_mode=0, n_proximal=None,
+                           remote_window=0.2)
 
     # -- M_I2B: bucket of every external id
     def bucket_of_ids(self) -> np.ndarray:
@@ -180,8 +183,8 @@ class Index:
         nb = np.where(live, self.bucket_of_slots(np.where(live, slots, 0)), -1)
         if ((nb[:, :kl] != own) & live[:, :kl]).any():
             raise ValueError("a local edge leaves its bucket")
-        if ((nb[:, kl:] == own) & live[:, kl:]).any():
-            raise ValueError("a remote edge stays in its bucket")
+        if self.params["remote_mode"] == 0 and ((nb[:, kl:] == own) & live[:, kl:]).any():
+            raise ValueError("a remote edge stays in its bucket")   # mode 1 keeps redundant local edges there
         self.k_local, self.k_remote = kl, kr
         self.A = np.full((self.n_cap, kl + kr), EMPTY, dtype=np.uint32)
         self.A[self.id2slot[:n]] = slots
@@ -198,6 +201,27 @@ class Index:
         max_iter = p["max_iter"] if p["max_iter"] is not None else 2 * beam
         n_seeds = p["n_seeds"] if p["n_seeds"] is not None else min(beam, 64)
         return _Params(p["search_width"], max_iter, n_seeds, p["visited_cap"], p["seed_salt"])
+
+    def _c_remote_rule(self) -> _RemoteRule:
+        """The remote wiring in force.  The proximal window is `remote_window` times the span of
+        the attributes in the index now (largest minus smallest), rounded down."""
+        p = self.params
+        kp = p["n_proximal"] if p["n_proximal"] is not None else (self.k_remote + 1) // 2
+        span = int(self.table[-1, 5]) - int(self.table[0, 4])
+        return _RemoteRule(p["remote_mode"], kp, int(np.floor(float(p["remote_window"]) * float(span))))
+
+    def search_scoped(self, queries: np.ndarray, scope: np.ndarray, beam: int):
+        """Candidate search of insertion / construction: scope b >= 0 = inside bucket b,
+        -2 - b = outside bucket b.  Returns the whole final queues (slots[nq,beam], dist[nq,beam])."""
+        queries = np.ascontiguousarray(queries, dtype=np.float32)
+        scope = np.ascontiguousarray(scope, dtype=np.int32)
+        nq = len(scope)
+        slots = np.empty((nq, beam), dtype=np.uint32)
+        dist = np.empty((nq, beam), dtype=np.float32)
+        ix, pr = self._c_index(), self._c_params(beam)
+        _load().oracle_search_scoped(ctypes.byref(ix), ctypes.byref(pr), _ptr(queries), _ptr(scope),
+                                     ctypes.c_int64(nq), ctypes.c_int32(beam), _ptr(slots), _ptr(dist))
+        return slots, dist
 
     def select(self, lo: int, hi: int, beam: int = 64):
         """(info[6], seeds): bucket run, population size, valid sorted span ends, seed slots."""
@@ -256,13 +280,29 @@ class Index:
         F = np.empty((self.n_cap, pool), dtype=np.uint32) if want_lists else None
         R = np.empty((self.n_cap, k_local), dtype=np.uint32) if want_lists else None
         ix = self._c_index()
+        rr, pr = self._c_remote_rule(), self._resolved_append_params()
         f = _load().oracle_build_graph
         f.restype = ctypes.c_int
         rc = f(ctypes.byref(ix), ctypes.c_int32(pool), _ptr(F) if want_lists else None,
-               _ptr(R) if want_lists else None, ctypes.c_int32(threads))
+               _ptr(R) if want_lists else None, ctypes.c_int32(threads), ctypes.byref(rr), ctypes.byref(pr),
+               ctypes.c_int32(self.params["append_beam"]))
         if rc:
             raise ValueError("oracle_build_graph rejected its arguments")
         return (F, R) if want_lists else None
+
+    def build_remote(self, threads: int = 1):
+        """Pass 2 of the construction alone: rewrites the remote part of every row of the graph
+        the index holds (see the reading in grab_oracle.c)."""
+        if self.A is None:
+            raise RuntimeError("load_graph first")
+        ix = self._c_index()
+        rr, pr = self._c_remote_rule(), self._resolved_append_params()
+        f = _load().oracle_build_remote
+        f.restype = ctypes.c_int
+        rc = f(ctypes.byref(ix), ctypes.byref(rr), ctypes.byref(pr), ctypes.c_int32(self.params["append_beam"]),
+               ctypes.c_int32(threads))
+        if rc:
+            raise ValueError("oracle_build_remote rejected its arguments")
 
     def _resolved_append_params(self) -> _Params:
         return self._c_params(self.params["append_beam"])
@@ -281,18 +321,24 @@ class Index:
         if self.n + m > len(self.id2slot):
             raise OverflowError("more objects than slots")
         kept = np.zeros((m, 2), dtype=np.int32)
-        ix, pr = self._c_index(), self._resolved_append_params()
+        ix, pr, rr = self._c_index(), self._resolved_append_params(), self._c_remote_rule()
         f = _load().oracle_append
         f.restype = ctypes.c_int
         rc = f(ctypes.byref(ix), ctypes.byref(pr), ctypes.c_float(self.params["alpha"]),
                ctypes.c_int32(self.params["append_beam"]), _ptr(vectors), _ptr(attrs), ctypes.c_int64(m),
-               ctypes.c_int64(self.n), _ptr(self.id2slot), _ptr(kept), ctypes.c_int32(threads))
+               ctypes.c_int64(self.n), _ptr(self.id2slot), _ptr(kept), ctypes.c_int32(threads), ctypes.byref(rr))
         if rc == 3:
             raise OverflowError("a bucket is out of tail room")
         if rc:
             raise ValueError("oracle_append rejected its arguments")
         self.n += m
         return kept
+
+
+def mix32(x: int) -> int:
+    f = _load().oracle_mix32
+    f.restype = ctypes.c_uint32
+    return int(f(ctypes.c_uint32(x)))
 
 
 def max_threads() -> int:
