@@ -63,9 +63,21 @@ typedef enum {
                                 default 2800, at most 24000                                */
     GRAB_P_SEED_SALT = 4,    /* moves the seed jitter; default 0                           */
     GRAB_P_ALPHA = 5,        /* freshness bias of Eq. 3, in (0, 1]; default 0.6            */
-    GRAB_P_APPEND_BEAM = 6,  /* candidate queue size of append's searches; default 64      */
-    GRAB_P_PROFILE = 7       /* 1: bracket the search kernels with HIP events on the index's
+    GRAB_P_APPEND_BEAM = 6,  /* candidate queue size of the candidate searches of
+                                grab_append_batch and grab_build_remote; default 64        */
+    GRAB_P_PROFILE = 7,      /* 1: bracket the search kernels with HIP events on the index's
                                 stream so that grab_get_timing can report them; default 0  */
+    GRAB_P_REMOTE_MODE = 8,  /* how grab_build_graph, grab_build_remote and grab_append_batch wire
+                                remote edges (Section 4.3, Remote Edge Construction):
+                                0 (default) entry j of the remote part belongs to the j-th target
+                                bucket; 1 candidates from a search over every other bucket, split
+                                into proximal and global picks                              */
+    GRAB_P_N_PROXIMAL = 9,   /* mode 1: remote positions kept for proximal candidates, 0..64;
+                                -1 (default) = ceil(k_remote / 2)                          */
+    GRAB_P_REMOTE_WINDOW = 10 /* mode 1: a candidate is proximal iff its attribute differs from the
+                                node's by at most this fraction of the attribute span of the index
+                                (largest minus smallest stored attribute, as int32 keys), rounded
+                                down; in [0, 1], default 0.2 (the paper's example)         */
 } grab_param;
 
 /* Creates an empty index for `dim`-dimensional fp32 vectors under `metric`.
@@ -109,13 +121,34 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
  * targets of bucket b are b+1, b-1, b+2, b-2, b+4, b-4, ... (adjacent attribute intervals first,
  * then doubling jumps), then the remaining offsets by size, skipping buckets that do not exist.
  * The paper draws remote candidates from a global graph built by a third-party pipeline
- * (Algorithm 1); here they come from exact search in the target bucket.  Distances use the same
- * fixed fp32 summation order as the search, ties go to the smaller slot.
+ * (Algorithm 1); here they come from exact search in the target bucket (GRAB_P_REMOTE_MODE 0) or
+ * from the library's own search over all other buckets (mode 1, see grab_build_remote).  Distances
+ * use the same fixed fp32 summation order as the search, ties go to the smaller slot.
  * pool = 0 means min(4 * k_local, 128): wide enough to reach past a node's own cluster, which is
  * what gives the graph its long links.  Requires 1 <= k_local <= 64, 0 <= k_remote <= 64,
  * k_local <= pool <= 128.  Errors: GRAB_EINVAL, GRAB_ESTATE (no layout), GRAB_ENOMEM, GRAB_EHIP;
  * on error the index is left without a graph. */
 grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, int32_t pool);
+
+/* Pass 2 of the construction alone (Section 4.3, Remote Edge Construction) on the graph the index
+ * holds, whatever made it: rewrites the remote part of every row under the reading that
+ * GRAB_P_REMOTE_MODE selects.
+ *   0: entry j = the nearest object of the j-th target bucket, as in grab_build_graph.
+ *   1: the paper's split.  Global candidates of a row = one run of the search (Algorithm 2) with
+ *      the row's own vector as query over every slot outside the row's bucket, against the graph
+ *      as it is when the call starts, with queue GRAB_P_APPEND_BEAM and the current seeds / width /
+ *      visited-cap / max-iter parameters (the library's search stands where the paper has a global
+ *      graph from a third-party pipeline, Algorithm 1).  A candidate is proximal iff its attribute
+ *      differs from the row's by at most the window (GRAB_P_REMOTE_WINDOW), any other one global.
+ *      The nearest GRAB_P_N_PROXIMAL proximal candidates overwrite remote positions 0.., the
+ *      nearest k_remote - n_proximal global ones the positions after them; a position with no pick
+ *      keeps what it holds.  Under this reading grab_build_graph first lets the interleaved merge
+ *      of pass 1 run on into the remote part (the redundant local edges, which the paper keeps
+ *      where too few remote candidates qualify), so the remote part of a row may hold edges that
+ *      stay inside the bucket, and grab_load_graph accepts such rows while mode 1 is set.
+ * Errors: GRAB_ESTATE (no graph), GRAB_EINVAL (n_proximal > k_remote, search parameters),
+ * GRAB_ENOMEM, GRAB_EHIP; the graph may be partly rewritten after GRAB_ENOMEM / GRAB_EHIP. */
+grab_status grab_build_remote(grab_index *ix);
 
 /* Range-constrained search (Algorithm 2) for nq queries: queries[nq][dim], closed ranges
  * lo[i] <= attribute <= hi[i], k results per query from a candidate queue of `beam` entries
@@ -149,15 +182,36 @@ grab_status grab_search_range_noalloc(grab_index *ix, const float *queries, cons
  * moving any existing slot (bucket = the one whose attribute interval holds the new value, else
  * the first one above it; slot = stable order of arrival inside the bucket).  Decisions about
  * existing nodes use the index as it was before the batch.  Per new object: candidate neighbours
- * by a search restricted to its bucket (queue GRAB_P_APPEND_BEAM, the current seeds / width /
- * visited-cap parameters); local forward edges by the diversity rule (Eq. 2) with back-fill;
- * remote entry j = nearest among the j-th remote entries of the candidates; then one reverse
- * request per written edge, applied per target in (kind, distance, source) order: a local request
- * must pass Eq. 2 with the freshness-biased distance (Eq. 3) and then fills an empty entry or
- * overwrites, among the target's neighbours that the new object points to itself, the one farthest
- * from the target; a remote request overwrites the target's remote entry that lies in the new object's
- * bucket iff the biased distance is smaller.  New external ids are n_prev .. n_prev+m-1 in input
- * order.  GRAB_EFULL if any bucket would overflow its slab: nothing is written then.
+ * by a search restricted to its bucket (queue GRAB_P_APPEND_BEAM; the current GRAB_P_N_SEEDS,
+ * GRAB_P_SEARCH_WIDTH, GRAB_P_VISITED_CAP and GRAB_P_MAX_ITER govern this search too, so a caller
+ * who caps iterations for its queries caps them here as well); local forward edges by the
+ * diversity rule (Eq. 2) with back-fill; the remote part and the reverse requests as
+ * GRAB_P_REMOTE_MODE says:
+ *   0: remote entry j = nearest among the j-th remote entries of the candidates (this departs from
+ *      Section 4.4's candidate search, which also looks outside the target bucket: in a graph wired
+ *      by target bucket the candidates' own remote entries already name the nodes to look at);
+ *      a remote request overwrites the target's remote entry that lies in the new object's
+ *      bucket iff the biased distance is smaller, else fills an empty entry.
+ *   1: a second candidate search over every slot outside the target bucket (Section 4.4, Parallel
+ *      Candidate Search: candidates from the target bucket and from the global scope), proximal and
+ *      global picks as in grab_build_remote, a position without a pick taking the nearest local
+ *      candidate not yet in the row; a remote request competes for the target's remote positions of
+ *      its class (proximal or global relative to the target): it takes the first one that is empty
+ *      or holds a node of the target's own bucket, else the one farthest from the target gives way
+ *      iff the biased distance is smaller.
+ * One reverse request per written edge that leaves no doubt about its kind, applied per target in
+ * (kind, distance, source) order: a local request must pass Eq. 2 with the freshness-biased
+ * distance (Eq. 3) and then fills an empty entry or overwrites, among the target's neighbours that
+ * the new object points to itself, the one farthest from the target.  The bias acts as alpha^2 on
+ * squared L2 distances; under GRAB_IP both sides of a biased comparison are first shifted to
+ * max(0, 1 + d), half the squared Euclidean distance on unit vectors (scaling minus the inner
+ * product itself would push similar newcomers away).  New external ids are n_prev .. n_prev+m-1 in
+ * input order.
+ * Capacity: a bucket holds count_b + floor((n_cap - n) / n_buckets) objects (see
+ * grab_build_buckets), so up to n_buckets - 1 of the n_cap slots asked for do not exist;
+ * grab_get_sizes reports the slots there are.  GRAB_EFULL if any bucket would overflow its slab,
+ * and GRAB_EINVAL: nothing is written then.  After GRAB_ENOMEM / GRAB_EHIP, which can strike
+ * between kernels, new rows may be written while the object count is not advanced: rebuild.
  * Needs k_local <= 64 and k_remote <= 64.
  * Errors: GRAB_EINVAL, GRAB_ESTATE (no graph), GRAB_EFULL, GRAB_ENOMEM, GRAB_EHIP. */
 grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_t *attrs, int64_t m);

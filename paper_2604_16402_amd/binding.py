@@ -18,13 +18,15 @@ OK, EINVAL, ESTATE, EFULL, ENOMEM, EHIP = range(6)
 STATUS_NAMES = {OK: "GRAB_OK", EINVAL: "GRAB_EINVAL", ESTATE: "GRAB_ESTATE", EFULL: "GRAB_EFULL",
                 ENOMEM: "GRAB_ENOMEM", EHIP: "GRAB_EHIP"}
 L2SQ, IP = 0, 1
-P_SEARCH_WIDTH, P_MAX_ITER, P_N_SEEDS, P_VISITED_CAP, P_SEED_SALT, P_ALPHA, P_APPEND_BEAM, P_PROFILE = range(8)
+P_SEARCH_WIDTH, P_MAX_ITER, P_N_SEEDS, P_VISITED_CAP, P_SEED_SALT, P_ALPHA, P_APPEND_BEAM, P_PROFILE, P_REMOTE_MODE, \
+    P_N_PROXIMAL, P_REMOTE_WINDOW = range(11)
 PARAMS = dict(search_width=P_SEARCH_WIDTH, max_iter=P_MAX_ITER, n_seeds=P_N_SEEDS, visited_cap=P_VISITED_CAP,
-              seed_salt=P_SEED_SALT, alpha=P_ALPHA, append_beam=P_APPEND_BEAM, profile=P_PROFILE)
+              seed_salt=P_SEED_SALT, alpha=P_ALPHA, append_beam=P_APPEND_BEAM, profile=P_PROFILE,
+              remote_mode=P_REMOTE_MODE, n_proximal=P_N_PROXIMAL, remote_window=P_REMOTE_WINDOW)
 EMPTY = 0xFFFFFFFF
 
 EXPORTS = ["grab_create", "grab_destroy", "grab_last_error", "grab_build_buckets", "grab_load_graph",
-           "grab_build_graph", "grab_search_range", "grab_search_range_noalloc", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
+           "grab_build_graph", "grab_build_remote", "grab_search_range", "grab_search_range_noalloc", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
            "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing",
            "grab_probe_gather", "grab_attr_image", "grab_attr_value", "grab_build_buckets_f32", "grab_search_range_f32",
            "grab_append_batch_f32"]
@@ -62,6 +64,7 @@ def load_library() -> ctypes.CDLL:
     lib.grab_build_buckets.argtypes = [vp, vp, vp, i64, i32, i64]
     lib.grab_load_graph.argtypes = [vp, vp, i32, vp, i32]
     lib.grab_build_graph.argtypes = [vp, i32, i32, i32]
+    lib.grab_build_remote.argtypes = [vp]
     lib.grab_search_range.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp]
     lib.grab_search_range_noalloc.argtypes = [vp, vp, vp, vp, i64, i32, i32, vp, vp]
     lib.grab_append_batch.argtypes = [vp, vp, vp, i64]
@@ -176,6 +179,9 @@ class Index:
 
     def build_graph(self, k_local: int, k_remote: int, pool: int = 0):
         self._check(self._lib.grab_build_graph(self._h, k_local, k_remote, pool))
+
+    def build_remote(self):
+        self._check(self._lib.grab_build_remote(self._h))
 
     def search_range(self, queries, lo, hi, k: int, beam: int, out_ids=None, out_dist=None):
         """Returns (ids[nq,k], dist[nq,k]); outputs are numpy unless device tensors are passed in."""

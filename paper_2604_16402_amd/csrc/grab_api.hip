@@ -73,6 +73,23 @@ static void drop_layout(grab_index *ix) {
     ix->n = ix->n_slots = 0; ix->B = 0; ix->kl = ix->kr = 0; ix->has_graph = false;
 }
 
+static grab_status check_remote_rule(grab_index *ix) {
+    if (ix->prm.remote_mode == 1 && ix->prm.n_proximal > ix->kr)
+        return grab_fail(ix, GRAB_EINVAL, "n_proximal %d exceeds k_remote %d", ix->prm.n_proximal, ix->kr);
+    return GRAB_OK;
+}
+
+RemoteRule grab_remote_rule(const grab_index *ix, int32_t kr) {
+    RemoteRule r;
+    r.mode = ix->prm.remote_mode;
+    r.n_proximal = ix->prm.n_proximal >= 0 ? ix->prm.n_proximal : (kr + 1) / 2;
+    if (r.n_proximal > kr) r.n_proximal = kr;
+    // attribute span of the index now, from the host copy of the bucket table
+    const double span = ix->B > 0 ? (double)((int64_t)ix->h_table[T_COLS * (ix->B - 1) + T_MAX] - (int64_t)ix->h_table[T_MIN]) : 0.0;
+    r.window = (int64_t)__builtin_floor(ix->prm.remote_window * span);
+    return r;
+}
+
 grab_status grab_resolve_search(grab_index *ix, int32_t k, int32_t beam, SearchLaunch &s) {
     const SearchParams &p = ix->prm;
     if (k < 1 || beam < k || beam > GRAB_MAX_BEAM) return grab_fail(ix, GRAB_EINVAL, "need 1 <= k <= beam <= %d", GRAB_MAX_BEAM);
@@ -161,6 +178,15 @@ grab_status grab_set_param(grab_index *ix, int32_t which, double value) {
                 for (hipEvent_t &e : ix->ev)
                     if (!e) GRAB_HIP(ix, hipEventCreate(&e));
             ix->profile = value == 1.0; return GRAB_OK;
+        case GRAB_P_REMOTE_MODE:
+            if (value != 0.0 && value != 1.0) return grab_fail(ix, GRAB_EINVAL, "remote_mode must be 0 or 1");
+            p.remote_mode = (int32_t)value; return GRAB_OK;
+        case GRAB_P_N_PROXIMAL:
+            if (value < -1 || value > 64 || value != (double)(int32_t)value) return grab_fail(ix, GRAB_EINVAL, "n_proximal must be -1..64");
+            p.n_proximal = (int32_t)value; return GRAB_OK;
+        case GRAB_P_REMOTE_WINDOW:
+            if (!(value >= 0.0 && value <= 1.0)) return grab_fail(ix, GRAB_EINVAL, "remote_window must be in [0, 1]");
+            p.remote_window = value; return GRAB_OK;
         default:
             return grab_fail(ix, GRAB_EINVAL, "unknown parameter %d", which);
     }
@@ -245,6 +271,7 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
     (void)hipStreamSynchronize(ix->stream);
     free_buf(tmp_l);
     free_buf(tmp_r);
+    if (ix->prm.remote_mode == 1) h_err[2] = 0;   // that reading keeps redundant local edges in the remote part
     if (st == GRAB_OK && (h_err[0] || h_err[1] || h_err[2]))
         st = grab_fail(ix, GRAB_EINVAL, "malformed graph: %d ids out of range, %d local edges leave their bucket, %d remote edges stay in it",
                        h_err[0], h_err[1], h_err[2]);
@@ -268,14 +295,31 @@ grab_status grab_build_graph(grab_index *ix, int32_t k_local, int32_t k_remote, 
     (void)hipFree(ix->A);
     ix->A = nullptr;
     GRAB_HIP(ix, hipMalloc((void **)&ix->A, (size_t)ix->n_slots * (k_local + k_remote) * 4));
-    grab_status st = grab_build_graph_device(ix, k_local, k_remote, pool);
+    ix->kl = k_local; ix->kr = k_remote;
+    SearchLaunch proto;
+    grab_status st = check_remote_rule(ix);
+    if (st == GRAB_OK) st = grab_resolve_search(ix, ix->prm.append_beam, ix->prm.append_beam, proto);
+    if (st == GRAB_OK) st = grab_build_graph_device(ix, k_local, k_remote, pool, proto);
     if (st != GRAB_OK) {
         (void)hipFree(ix->A);
         ix->A = nullptr;
+        ix->kl = ix->kr = 0;
         return st;
     }
-    ix->kl = k_local; ix->kr = k_remote; ix->has_graph = true;
+    ix->has_graph = true;
     return GRAB_OK;
+}
+
+grab_status grab_build_remote(grab_index *ix) {
+    if (!ix) return GRAB_EINVAL;
+    if (!ix->has_graph) return grab_fail(ix, GRAB_ESTATE, "no graph loaded");
+    SearchLaunch proto;
+    grab_status st = check_remote_rule(ix);
+    if (st == GRAB_OK) st = grab_resolve_search(ix, ix->prm.append_beam, ix->prm.append_beam, proto);
+    if (st != GRAB_OK) return st;
+    GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
+    ix->timed = false;
+    return grab_build_remote_device(ix, proto);
 }
 
 grab_status grab_search_range(grab_index *ix, const float *queries, const int32_t *lo, const int32_t *hi, int64_t nq,
@@ -446,7 +490,8 @@ grab_status grab_append_batch(grab_index *ix, const float *vectors, const int32_
         return grab_fail(ix, GRAB_EFULL, "%lld objects + %lld new exceed the %lld slots of the index", (long long)ix->n,
                          (long long)m, (long long)ix->n_slots);
     SearchLaunch proto;
-    grab_status st = grab_resolve_search(ix, ix->prm.append_beam, ix->prm.append_beam, proto);
+    grab_status st = check_remote_rule(ix);
+    if (st == GRAB_OK) st = grab_resolve_search(ix, ix->prm.append_beam, ix->prm.append_beam, proto);
     if (st != GRAB_OK) return st;
     const void *dv, *da;
     if ((st = grab_to_device(ix, vectors, (size_t)m * ix->dim * 4, ix->stage_q, &dv)) != GRAB_OK) return st;

@@ -69,6 +69,12 @@ __global__ void k_fill_range(int32_t *__restrict__ lo, int32_t *__restrict__ hi,
     if (i < m) { lo[i] = INT32_MIN; hi[i] = INT32_MAX; }
 }
 
+// scope of the global-scope candidate search: every slot outside the object's own bucket
+__global__ void k_scope_outside(const int32_t *__restrict__ bucket, int64_t m, int32_t *__restrict__ scope) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < m) scope[i] = -2 - bucket[i];
+}
+
 // feature row, attribute and id maps of the new objects (one thread per 16-byte piece)
 __global__ void k_write_new(const float4 *__restrict__ vecs, const int32_t *__restrict__ attrs,
                             const uint32_t *__restrict__ slot, int64_t m, int64_t n_prev, int32_t row_f4,
@@ -171,6 +177,13 @@ struct ForwardArgs {
     const uint32_t *by_bucket;  // batch positions in bucket order: the order the workgroups take them in
     int64_t m;
     int32_t beam, kl, kr, metric;
+    // proximal / global reading of the remote part (mode 1)
+    int32_t mode, kp;
+    int64_t window;
+    const uint32_t *gcand_s;    // global-scope candidate search results: slots [m][beam]
+    const float *gcand_d;
+    const int32_t *attr;        // attributes of the index, by slot
+    const int32_t *new_attr;    // attributes of the new objects, batch order
 };
 
 // Forward edges of one new node per wavefront (Section 4.4 step 2).  Local part (Eq. 2): scan the
@@ -199,7 +212,11 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     uint32_t *rej = reinterpret_cast<uint32_t *>(keptd + 64);
     float *rejd = reinterpret_cast<float *>(rej + 64);
     float *dtmp = rejd + 64;
-    uint32_t *uniq = reinterpret_cast<uint32_t *>(dtmp + 64);   // set of distinct remote candidates
+    uint32_t *pk = reinterpret_cast<uint32_t *>(dtmp + 64);     // mode 1: remote picks,
+    float *pkd = reinterpret_cast<float *>(pk + 64);            //         their distances,
+    uint32_t *rowl = reinterpret_cast<uint32_t *>(pkd + 64);    //         the local part of the new row,
+    uint32_t *ul = rowl + 64;                                   //         local candidates not in it
+    uint32_t *uniq = ul + 64;                                   // set of distinct remote candidates
     const int uniq_words = (2 * a.beam + 3) & ~3;    // keeps the query row behind it 16-byte aligned
     float *qlds = reinterpret_cast<float *>(uniq + uniq_words);
     float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
@@ -278,12 +295,56 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         if (j < nk) { v = kept[j]; d = keptd[j]; }
         else if (j - nk < nrej) { v = rej[j - nk]; d = rejd[j - nk]; }
         a.A[(size_t)self * K + j] = v;
+        rowl[j] = v;
         const int64_t r = i * K + j;
         a.key1[r] = v == GRAB_EMPTY ? ~0ull : ((u64)v << 1);
         a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
         a.reqd[r] = d;
     }
-    // ---- remote part
+    // ---- remote part, proximal / global reading: picks from the global-scope candidates; a position
+    // without a pick takes the nearest local candidate not yet in the row (a redundant local edge,
+    // which makes no reverse request)
+    if (a.mode == 1) {
+        if (a.kr == 0) return;
+        __syncthreads();
+        select_remote_wave(a.gcand_s + i * a.beam, a.gcand_d + i * a.beam, a.beam, a.attr, a.new_attr[i], a.window, a.kp,
+                           a.kr, lane, pk, pkd);
+        int nu = 0;
+        for (int c0 = 0; c0 < nc && nu < a.kr; c0 += 64) {
+            const int t = c0 + lane;
+            bool un = t < nc;
+            const uint32_t c = un ? cs[t] : GRAB_EMPTY;
+            if (un)
+                for (int x = 0; x < a.kl; ++x) un = un && rowl[x] != c;
+            const u64 mu = __ballot(un);
+            if (un) {
+                const int r = nu + __popcll(mu & lt_mask);
+                if (r < a.kr) ul[r] = c;
+            }
+            nu += __popcll(mu);
+        }
+        nu = min(nu, a.kr);
+        __syncthreads();
+        const bool has = lane < a.kr;
+        uint32_t v = GRAB_EMPTY;
+        float d = 0.0f;
+        if (has) { v = pk[lane]; d = pkd[lane]; }
+        const bool pick = has && v != GRAB_EMPTY;
+        const u64 mless = __ballot(has && !pick);
+        if (has && !pick) {
+            const int r = __popcll(mless & lt_mask);
+            v = r < nu ? ul[r] : GRAB_EMPTY;
+        }
+        if (has) {
+            a.A[(size_t)self * K + a.kl + lane] = v;
+            const int64_t r = i * K + a.kl + lane;
+            a.key1[r] = pick ? (((u64)v << 1) | 1ull) : ~0ull;
+            a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
+            a.reqd[r] = d;
+        }
+        return;
+    }
+    // ---- remote part, by target bucket
     if (a.kr > 0) {
         load_query<NCH>(a.vecs + (size_t)i * D, qreg, qlds, lane);
         __syncthreads();
@@ -350,7 +411,11 @@ struct RewireArgs {
     const float *reqd;      // by request index: dist(target, source)
     int64_t nreq;
     int32_t kl, kr, metric, B;
-    float a;                // alpha, squared for the squared-L2 metric
+    float a;                // alpha squared: the bias acts on squared distances (see bias_base)
+    // proximal / global reading of the remote part (mode 1)
+    int32_t mode, kp;
+    int64_t window;
+    const int32_t *attr;
 };
 
 __device__ __forceinline__ int bucket_of_slot_dev(const int32_t *__restrict__ table, int32_t B, uint32_t slot) {
@@ -399,15 +464,40 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
         if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
         eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);   // dist(v, R[j])
         __syncthreads();
+        const int bv = a.mode == 1 ? bucket_of_slot_dev(a.table, a.B, v) : 0;
+        const int32_t attr_v = a.mode == 1 ? a.attr[v] : 0;
         for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
             const uint32_t ridx = a.order[p];
             const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
             const float dvq = a.reqd[ridx];
-            const float lhs = a.a * dvq;
-            const int bq = bucket_of_slot_dev(a.table, a.B, q);
+            const float lhs = a.a * bias_base(dvq, a.metric);
             const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
-            const bool inb = mine != GRAB_EMPTY && bucket_of_slot_dev(a.table, a.B, mine) == bq;
             int at = -1;
+            if (a.mode == 1) {
+                // q competes for the positions of its class; an empty one or one holding a node of
+                // v's own bucket (a redundant local edge) is taken at once, else the farthest gives way
+                long long diff = (long long)a.attr[q] - (long long)attr_v;
+                if (diff < 0) diff = -diff;
+                const int j0 = diff <= a.window ? 0 : a.kp, j1 = diff <= a.window ? a.kp : len;
+                const bool inc = lane >= j0 && lane < j1;
+                const u64 free_m = __ballot(inc && (mine == GRAB_EMPTY || bucket_of_slot_dev(a.table, a.B, mine) == bv));
+                if (free_m) {
+                    at = __ffsll((long long)free_m) - 1;
+                } else if (j1 > j0) {
+                    u64 kf = inc ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : 0ull;
+                    u64 kmax = kf;
+#pragma unroll
+                    for (int s = 32; s > 0; s >>= 1) {
+                        uint32_t hi = __shfl_xor((uint32_t)(kmax >> 32), s), lo = __shfl_xor((uint32_t)kmax, s);
+                        u64 other = ((u64)hi << 32) | lo;
+                        kmax = other > kmax ? other : kmax;
+                    }
+                    const int far = __ffsll((long long)__ballot(inc && kf == kmax)) - 1;
+                    if (lhs < bias_base(dq[far], a.metric)) at = far;
+                }
+            } else {
+            const int bq = bucket_of_slot_dev(a.table, a.B, q);
+            const bool inb = mine != GRAB_EMPTY && bucket_of_slot_dev(a.table, a.B, mine) == bq;
             if (__ballot(inb)) {
                 u64 kf = inb ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : 0ull;
                 u64 kmax = kf;
@@ -418,10 +508,11 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
                     kmax = other > kmax ? other : kmax;
                 }
                 const int far = __ffsll((long long)__ballot(inb && kf == kmax)) - 1;
-                if (lhs < dq[far]) at = far;
+                if (lhs < bias_base(dq[far], a.metric)) at = far;
             } else {
                 const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
                 if (empties) at = __ffsll((long long)empties) - 1;
+            }
             }
             __syncthreads();
             if (at >= 0) {
@@ -439,14 +530,14 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
             const uint32_t ridx = a.order[p];
             const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
             const float dvq = a.reqd[ridx];
-            const float lhs = a.a * dvq;
+            const float lhs = a.a * bias_base(dvq, a.metric);
             for (int x = lane; x < K; x += 64) qrow[x] = a.A[(size_t)q * K + x];
             load_query<NCH>(a.X + (size_t)q * D, qreg, qlds, lane);
             if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
             eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);
             __syncthreads();
             const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
-            const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < dq[lane]);
+            const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < bias_base(dq[lane], a.metric));
             if (__ballot(blocked) == 0) {
                 const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
                 int at = -1;
@@ -484,7 +575,7 @@ template <int NCH>
 grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
     const size_t qbytes = EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4;
     if (phase == 0) {
-        size_t lds = (size_t)f.beam * 16 + 64 * 4 * 5 + (size_t)((2 * f.beam + 3) & ~3) * 4 + qbytes;
+        size_t lds = (size_t)f.beam * 16 + 64 * 4 * 9 + (size_t)((2 * f.beam + 3) & ~3) * 4 + qbytes;
         k_forward<NCH><<<dim3((unsigned)((m + 7) / 8 * 8)), dim3(64), lds, ix->stream>>>(f);
     } else {
         size_t lds = 64 * 4 * 4 + 128 * 4 + qbytes;
@@ -515,12 +606,17 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     const int64_t nreq = m * K;
     grab_status rc;
     // ---- arena
-    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_N };
+    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_CG_S, A_CG_D, A_SCOPE, A_N };
     size_t need[A_N];
     for (size_t &x : need) x = 0;
     need[A_BUCKET] = need[A_KEYS] = need[A_IDX] = need[A_KEYS_S] = need[A_IDX_S] = need[A_SLOT] = need[A_LO] = need[A_HI] = (size_t)m * 4;
     need[A_STARTS] = need[A_COUNTS] = (size_t)B * 4;
     need[A_CL_S] = need[A_CL_D] = (size_t)m * beam * 4;
+    const RemoteRule rule = grab_remote_rule(ix, kr);
+    if (rule.mode == 1) {
+        need[A_CG_S] = need[A_CG_D] = (size_t)m * beam * 4;
+        need[A_SCOPE] = (size_t)m * 4;
+    }
     need[A_KEY1] = need[A_KEY2] = need[A_K2S] = need[A_K1G] = need[A_K1S] = (size_t)nreq * 8;
     need[A_REQD] = need[A_ORD0] = need[A_ORD1] = need[A_ORD2] = (size_t)nreq * 4;
     size_t tmp1 = 0, tmp2 = 0;
@@ -573,6 +669,13 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
     if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
     ix->last_nq = 0;
+    if (rule.mode == 1 && kr > 0) {
+        // ---- 3': the same search over every other bucket (Section 4.4: candidates from the global scope)
+        k_scope_outside<<<blocks_for(m), TPB, 0, st>>>(bucket, m, (int32_t *)P(A_SCOPE));
+        s.only_bucket = (const int32_t *)P(A_SCOPE); s.out_ids = (uint32_t *)P(A_CG_S); s.out_dist = (float *)P(A_CG_D);
+        if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
+        if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
+    }
     // ---- 4: forward selection, new adjacency rows, reverse requests
     ForwardArgs f;
     f.X = ix->X; f.A = ix->A; f.vecs = d_vecs; f.slot = slot;
@@ -580,6 +683,9 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     f.key1 = (u64 *)P(A_KEY1); f.key2 = (u64 *)P(A_KEY2); f.reqd = (float *)P(A_REQD);
     f.by_bucket = (const uint32_t *)P(A_IDX_S); f.m = m;
     f.beam = beam; f.kl = kl; f.kr = kr; f.metric = ix->metric;
+    f.mode = rule.mode; f.kp = rule.n_proximal; f.window = rule.window;
+    f.gcand_s = (const uint32_t *)P(A_CG_S); f.gcand_d = (const float *)P(A_CG_D);
+    f.attr = ix->attr; f.new_attr = d_attrs;
     RewireArgs r;
     memset(&r, 0, sizeof(r));
     if ((rc = launch_append(ix, f, r, m, 0)) != GRAB_OK) return rc;
@@ -597,7 +703,8 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.order = (const uint32_t *)P(A_ORD2);
     r.key2 = (const u64 *)P(A_KEY2); r.reqd = (const float *)P(A_REQD); r.nreq = nreq;
     r.kl = kl; r.kr = kr; r.metric = ix->metric; r.table = ix->table; r.B = B;
-    r.a = ix->metric == GRAB_L2SQ ? ix->prm.alpha * ix->prm.alpha : ix->prm.alpha;
+    r.mode = rule.mode; r.kp = rule.n_proximal; r.window = rule.window; r.attr = ix->attr;
+    r.a = ix->prm.alpha * ix->prm.alpha;
     if ((rc = launch_append(ix, f, r, m, 1)) != GRAB_OK) return rc;
     // ---- 6: table
     k_widen<<<blocks_for(m), TPB, 0, st>>>(d_attrs, bucket, m, ix->table);

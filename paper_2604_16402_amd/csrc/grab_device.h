@@ -257,6 +257,53 @@ __device__ __forceinline__ void eval_rows(const float *__restrict__ X, const flo
     }
 }
 
+// Remote edge selection (Section 4.3, Remote Edge Construction) for one node per wavefront.
+// gs[0..ng) / gd: candidate slots and distances ordered by (distance, slot), GRAB_EMPTY-padded.
+// A candidate is proximal iff its attribute differs from attr_u by at most `window`.  pk[0..kp)
+// receives the first kp proximal candidates, pk[kp..kr) the first kr - kp others, pkd their
+// distances; GRAB_EMPTY where a class runs out.  pk / pkd are LDS; every lane of the workgroup
+// (one wavefront) must call.
+__device__ __forceinline__ void select_remote_wave(const uint32_t *__restrict__ gs, const float *__restrict__ gd, int ng,
+                                                   const int32_t *__restrict__ attr, int32_t attr_u, int64_t window,
+                                                   int kp, int kr, int lane, uint32_t *pk, float *pkd) {
+    for (int j = lane; j < kr; j += 64) { pk[j] = GRAB_EMPTY; pkd[j] = 0.0f; }
+    __syncthreads();
+    const u64 lt_mask = (1ull << lane) - 1ull;
+    int np = 0, ngl = 0;
+    for (int c0 = 0; c0 < ng && (np < kp || ngl < kr - kp); c0 += 64) {
+        const int t = c0 + lane;
+        const uint32_t c = t < ng ? gs[t] : GRAB_EMPTY;
+        const bool valid = c != GRAB_EMPTY;
+        bool prox = false;
+        if (valid) {
+            long long diff = (long long)attr[c] - (long long)attr_u;
+            if (diff < 0) diff = -diff;
+            prox = diff <= window;
+        }
+        const u64 mp = __ballot(valid && prox), mg = __ballot(valid && !prox);
+        if (valid && prox) {
+            const int r = np + __popcll(mp & lt_mask);
+            if (r < kp) { pk[r] = c; pkd[r] = gd[t]; }
+        }
+        if (valid && !prox) {
+            const int r = ngl + __popcll(mg & lt_mask);
+            if (r < kr - kp) { pk[kp + r] = c; pkd[kp + r] = gd[t]; }
+        }
+        np += __popcll(mp);
+        ngl += __popcll(mg);
+    }
+    __syncthreads();
+}
+
+// what the freshness bias of Eq. 3 scales: the distance itself for squared L2; for minus the inner
+// product, which is negative for similar vectors, max(0, 1 + d): half the squared Euclidean
+// distance on unit vectors
+__device__ __forceinline__ float bias_base(float d, int metric) {
+    if (metric == GRAB_L2SQ) return d;
+    const float s = 1.0f + d;
+    return s > 0.0f ? s : 0.0f;
+}
+
 // the "query" side of eval_rows from a row in memory: registers for rows up to 256 floats,
 // LDS (qlds, dim floats) beyond; callers synchronise before the next eval_rows
 template <int NCH>

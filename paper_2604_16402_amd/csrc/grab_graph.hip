@@ -275,16 +275,20 @@ __global__ void k_rev_fill(const uint32_t *__restrict__ key1s, const uint32_t *_
     if (rank < kl) R[(int64_t)v * kl + rank] = (uint32_t)(key2[order[p]] & 0xFFFFFFFFull);
 }
 
-// F0, R0, F1, R1, ... without empties and repeats; the first kl survivors are the local edges
+// F0, R0, F1, R1, ... (the reverse list ends after kl entries, the forward list goes on to P)
+// without empties and repeats; the first kl survivors are the necessary local edges; with
+// want = K the next ones fill the rest of the row as redundant local edges (Section 4.3, Local
+// Router Construction)
 __global__ void k_interleave(const uint32_t *__restrict__ F, const uint32_t *__restrict__ R,
                              const uint32_t *__restrict__ slot2id, int64_t n_slots, int32_t P, int32_t kl, int32_t K,
-                             uint32_t *__restrict__ A) {
+                             int32_t want, uint32_t *__restrict__ A) {
     int64_t u = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (u >= n_slots || slot2id[u] == GRAB_EMPTY) return;
     uint32_t *row = A + u * K;
     int w = 0;
-    for (int j = 0; j < kl && w < kl; ++j)
-        for (int side = 0; side < 2 && w < kl; ++side) {
+    for (int j = 0; j < P && w < want; ++j)
+        for (int side = 0; side < 2 && w < want; ++side) {
+            if (side == 1 && j >= kl) continue;
             const uint32_t c = side == 0 ? F[u * P + j] : R[u * kl + j];
             if (c == GRAB_EMPTY) continue;
             bool dup = false;
@@ -333,7 +337,7 @@ int remote_targets(int b, int B, int kr, int *out) {
 
 }  // namespace
 
-grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int32_t pool) {
+grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int32_t pool, const SearchLaunch &proto) {
     hipStream_t st = ix->stream;
     const int32_t B = ix->B, K = kl + kr;
     const int64_t N = ix->n_slots, ne = N * kl;
@@ -372,16 +376,11 @@ grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int3
     G_ALLOC(key1, (size_t)ne * 4); G_ALLOC(key1g, (size_t)ne * 4); G_ALLOC(key1s, (size_t)ne * 4);
     G_ALLOC(ord0, (size_t)ne * 4); G_ALLOC(ord1, (size_t)ne * 4); G_ALLOC(ord2, (size_t)ne * 4);
     G_ALLOC(key2, (size_t)ne * 8); G_ALLOC(key2s, (size_t)ne * 8);
-    G_ALLOC(tgt, (size_t)B * 4 * (kr + 1));
-    // target tables: row 0 = the bucket itself, row 1+j = j-th remote target
+    G_ALLOC(tgt, (size_t)B * 4);
+    // pass 1 searches every bucket for its own nearest objects
     {
-        std::vector<int32_t> h((size_t)B * (kr + 1), -1);
-        std::vector<int> t(kr > 0 ? kr : 1);
-        for (int b = 0; b < B; ++b) {
-            h[b] = b;
-            int n = remote_targets(b, B, kr, t.data());
-            for (int j = 0; j < n; ++j) h[(size_t)(1 + j) * B + b] = t[j];
-        }
+        std::vector<int32_t> h((size_t)B, -1);
+        for (int b = 0; b < B; ++b) h[b] = b;
         G_HIP(hipMemcpyAsync(tgt, h.data(), h.size() * 4, hipMemcpyHostToDevice, st));
         G_HIP(hipStreamSynchronize(st));
     }
@@ -408,14 +407,128 @@ grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int3
         G_HIP(rocprim::radix_sort_pairs(sort_tmp, t1, key1g, key1s, ord1, ord2, (size_t)ne, 0, 32, st));
         k_rev_fill<<<blocks_for(ne), TPB, 0, st>>>(key1s, ord2, key2, ne, kl, R);
     }
-    k_interleave<<<blocks_for(N), TPB, 0, st>>>(F, R, ix->slot2id, N, pool, kl, K, ix->A);
-    // pass 2: remote entries
-    for (int j = 0; j < kr; ++j) {
-        k.tgt = tgt + (size_t)(1 + j) * B; k.out_s = ix->A; k.out_d = nullptr;
-        k.out_stride = K; k.out_off = kl + j; k.P = 1; k.exclude_self = 0;
-        if ((rc = launch_graph(ix, &k, nullptr, tiles)) != GRAB_OK) { cleanup(); return rc; }
-    }
+    k_interleave<<<blocks_for(N), TPB, 0, st>>>(F, R, ix->slot2id, N, pool, kl, K, ix->prm.remote_mode == 1 ? K : kl, ix->A);
     G_HIP(hipGetLastError());
+    G_HIP(hipStreamSynchronize(st));
+    cleanup();
+    // pass 2: remote entries
+    ix->kl = kl; ix->kr = kr;
+    return grab_build_remote_device(ix, proto);
+}
+
+namespace {
+
+// scope of construction's candidate search for the row at each slot: every slot outside the
+// row's own bucket; nothing for a slot without an object
+__global__ void k_scope_rows(const int32_t *__restrict__ table, int32_t B, const uint32_t *__restrict__ slot2id,
+                             int64_t first, int64_t count, int32_t *__restrict__ scope) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i >= count) return;
+    const int64_t u = first + i;
+    int32_t sc = INT32_MIN;
+    if (slot2id[u] != GRAB_EMPTY) {
+        int l = 0, r = B;   // last bucket whose base <= slot
+        while (r - l > 1) {
+            int m = (l + r) >> 1;
+            if ((int64_t)table[T_COLS * m + T_BASE] <= u) l = m; else r = m;
+        }
+        sc = -2 - l;
+    }
+    scope[i] = sc;
+}
+
+__global__ void k_full_range(int32_t *__restrict__ lo, int32_t *__restrict__ hi, int64_t m) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (i < m) { lo[i] = INT32_MIN; hi[i] = INT32_MAX; }
+}
+
+// fusion (Section 4.3, Remote Edge Construction): one wavefront per row; proximal and global picks
+// from the row's global candidates overwrite the redundant positions, a position without a pick
+// keeps its redundant local edge
+__global__ __launch_bounds__(64) void k_fuse(const uint32_t *__restrict__ cand_s, const float *__restrict__ cand_d, int32_t beam,
+                                             const int32_t *__restrict__ attr, const uint32_t *__restrict__ slot2id,
+                                             int64_t first, int64_t count, int32_t kl, int32_t kr, int32_t kp, int64_t window,
+                                             uint32_t *__restrict__ A) {
+    __shared__ uint32_t pk[64];
+    __shared__ float pkd[64];
+    const int64_t i = blockIdx.x;
+    const int lane = threadIdx.x;
+    if (i >= count) return;
+    const int64_t u = first + i;
+    if (slot2id[u] == GRAB_EMPTY) return;
+    select_remote_wave(cand_s + i * beam, cand_d + i * beam, beam, attr, attr[u], window, kp, kr, lane, pk, pkd);
+    if (lane < kr && pk[lane] != GRAB_EMPTY) A[u * (kl + kr) + kl + lane] = pk[lane];
+}
+
+}  // namespace
+
+grab_status grab_build_remote_device(grab_index *ix, const SearchLaunch &proto) {
+    hipStream_t st = ix->stream;
+    const int32_t B = ix->B, kl = ix->kl, kr = ix->kr, K = kl + kr;
+    const int64_t N = ix->n_slots;
+    if (kr == 0) return GRAB_OK;
+    std::vector<void *> tmp;
+    auto cleanup = [&]() { for (void *p : tmp) (void)hipFree(p); };
+    const RemoteRule rule = grab_remote_rule(ix, kr);
+    if (rule.mode == 0) {
+        // entry j = the nearest object of the j-th target bucket
+        int32_t max_n = 0;
+        for (int b = 0; b < B; ++b) max_n = ix->h_table[T_COLS * b + T_NTOT] > max_n ? ix->h_table[T_COLS * b + T_NTOT] : max_n;
+        const unsigned tiles = (unsigned)((max_n + 31) / 32);
+        int32_t *tgt;
+        G_ALLOC(tgt, (size_t)B * 4 * kr);
+        std::vector<int32_t> h((size_t)B * kr, -1);
+        std::vector<int> t(kr);
+        for (int b = 0; b < B; ++b) {
+            int n = remote_targets(b, B, kr, t.data());
+            for (int j = 0; j < n; ++j) h[(size_t)j * B + b] = t[j];
+        }
+        G_HIP(hipMemcpyAsync(tgt, h.data(), h.size() * 4, hipMemcpyHostToDevice, st));
+        G_HIP(hipStreamSynchronize(st));
+        KnnArgs k;
+        k.X = ix->X; k.table = ix->table; k.n_slots = N; k.metric = ix->metric;
+        grab_status rc;
+        for (int j = 0; j < kr; ++j) {
+            k.tgt = tgt + (size_t)j * B; k.out_s = ix->A; k.out_d = nullptr;
+            k.out_stride = K; k.out_off = kl + j; k.P = 1; k.exclude_self = 0;
+            if ((rc = launch_graph(ix, &k, nullptr, tiles)) != GRAB_OK) { cleanup(); return rc; }
+        }
+        G_HIP(hipGetLastError());
+        G_HIP(hipStreamSynchronize(st));
+        cleanup();
+        return GRAB_OK;
+    }
+    // proximal / global reading: global candidates of every row from the library's own search over
+    // a copy of the graph as it is now (so that no search sees a row already rewritten)
+    const int64_t chunk = N < (1ll << 20) ? N : (1ll << 20);
+    const int32_t beam = proto.beam;
+    uint32_t *snap, *cand_s, *seeds, *counters;
+    float *cand_d;
+    int32_t *scope, *lo, *hi;
+    QueryPlan *plans;
+    G_ALLOC(snap, (size_t)N * K * 4);
+    G_ALLOC(cand_s, (size_t)chunk * beam * 4); G_ALLOC(cand_d, (size_t)chunk * beam * 4);
+    G_ALLOC(scope, (size_t)chunk * 4); G_ALLOC(lo, (size_t)chunk * 4); G_ALLOC(hi, (size_t)chunk * 4);
+    G_ALLOC(plans, (size_t)chunk * sizeof(QueryPlan));
+    G_ALLOC(seeds, (size_t)chunk * proto.n_seeds * 4);
+    G_ALLOC(counters, (size_t)chunk * 8 * 4);
+    G_HIP(hipMemcpyAsync(snap, ix->A, (size_t)N * K * 4, hipMemcpyDeviceToDevice, st));
+    k_full_range<<<blocks_for(chunk), TPB, 0, st>>>(lo, hi, chunk);
+    grab_status rc;
+    for (int64_t first = 0; first < N; first += chunk) {
+        const int64_t count = N - first < chunk ? N - first : chunk;
+        k_scope_rows<<<blocks_for(count), TPB, 0, st>>>(ix->table, B, ix->slot2id, first, count, scope);
+        SearchLaunch s = proto;
+        s.queries = ix->X + (size_t)first * ix->dim; s.lo = lo; s.hi = hi; s.only_bucket = scope; s.adj = snap; s.nq = count;
+        s.plans = plans; s.seeds = seeds; s.counters = counters; s.out_ids = cand_s; s.out_dist = cand_d; s.out_slots = true;
+        if ((rc = grab_plan_order(ix, s)) != GRAB_OK) { cleanup(); return rc; }
+        if ((rc = grab_launch_select(ix, s)) != GRAB_OK) { cleanup(); return rc; }
+        if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) { cleanup(); return rc; }
+        k_fuse<<<dim3((unsigned)count), dim3(64), 0, st>>>(cand_s, cand_d, beam, ix->attr, ix->slot2id, first, count, kl, kr,
+                                                           rule.n_proximal, rule.window, ix->A);
+        G_HIP(hipGetLastError());
+    }
+    ix->last_nq = 0;
     G_HIP(hipStreamSynchronize(st));
 #undef G_ALLOC
 #undef G_HIP

@@ -40,7 +40,17 @@ struct SearchParams {
     uint32_t seed_salt = 0;
     float alpha = 0.6f;
     int32_t append_beam = 64;
+    int32_t remote_mode = 0;      // 0: remote entry j belongs to the j-th target bucket; 1: proximal / global split
+    int32_t n_proximal = -1;      // mode 1: remote positions for proximal candidates; -1: ceil(k_remote / 2)
+    double remote_window = 0.2;   // mode 1: proximal = attribute within this fraction of the attribute span
 };
+
+// the remote wiring in force for one construction or insertion call (Section 4.3, Remote Edge Construction)
+struct RemoteRule {
+    int32_t mode, n_proximal;
+    int64_t window;
+};
+RemoteRule grab_remote_rule(const grab_index *ix, int32_t kr);
 
 struct DevBuf {
     void *p = nullptr;
@@ -111,7 +121,11 @@ grab_status grab_launch_load_graph(grab_index *ix, const uint32_t *d_local, int3
 struct SearchLaunch {
     const float *queries;   // device [nq][dim]
     const int32_t *lo, *hi; // device [nq]
-    const int32_t *only_bucket; // device [nq] or nullptr: restrict to one bucket's slab (append)
+    // device [nq] or nullptr: the scope of each query when it is not an attribute range (candidate
+    // searches of insertion and construction): b >= 0 = the slots of bucket b's slab, -2 - b = every
+    // slot outside it, INT32_MIN = nothing (a row without an object)
+    const int32_t *only_bucket;
+    const uint32_t *adj = nullptr;   // adjacency to walk instead of the index's own (construction's snapshot)
     int64_t nq;
     int32_t k, beam, width, max_iter, n_seeds, visited_cap;
     uint32_t salt;
@@ -143,6 +157,8 @@ grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batc
 // append: the whole insertion for m objects already on the device; `proto` carries the search
 // parameters resolved for beam = append_beam
 // construction: fills ix->A (already allocated for kl+kr entries per slot)
-grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int32_t pool);
+grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int32_t pool, const SearchLaunch &proto);
+// pass 2 alone on the graph the index holds; `proto` as for append
+grab_status grab_build_remote_device(grab_index *ix, const SearchLaunch &proto);
 grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_t *d_attrs, int64_t m,
                                const SearchLaunch &proto);

@@ -56,11 +56,16 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
     const int64_t q = blockIdx.x;
     const int lane = threadIdx.x;
     const int lo = lo_[q], hi = hi_[q];
+    // scope of the query: -1 = its attribute range; b >= 0 = the slab of bucket b; -2 - b = every
+    // slot outside the slab of bucket b; INT32_MIN = nothing
     const int only = only_bucket ? only_bucket[q] : -1;
+    const int ex = (only <= -2 && only != INT32_MIN) ? -2 - only : -1;   // excluded bucket
     int b0 = 0, b1 = -1;
     if (only >= 0) {
         b0 = b1 = only;
-    } else if (lo <= hi) {
+    } else if (ex >= 0) {
+        b0 = 0; b1 = B - 1;
+    } else if (only == -1 && lo <= hi) {
         // bucket intervals are ordered, so counting gives the run: buckets entirely below lo
         // come first, buckets starting at or below hi form a prefix
         int below = 0, start_ok = 0;
@@ -85,8 +90,9 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
     const int base0 = t0[T_BASE], ns0 = t0[T_NSORT], nt0 = t0[T_NTOT];
     const int base1 = t1[T_BASE], ns1 = t1[T_NSORT], nt1 = t1[T_NTOT];
     int sa0, se0, se1 = 0, tail0, tail1 = 0;
-    if (only >= 0) {           // whole slab, nothing to check
+    if (only >= 0 || ex >= 0) {   // whole slabs, nothing to check: the "sorted span" is every occupied slot
         sa0 = 0; se0 = nt0; tail0 = 0;
+        se1 = nt1; tail1 = 0;
     } else {
         sa0 = wave_bound(attr + base0, ns0, lo, false, lane);
         se0 = (b1 == b0) ? wave_bound(attr + base0, ns0, hi, true, lane) : ns0;
@@ -104,7 +110,8 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
         int i = i0 + lane, c = 0;
         if (i < nb) {
             int b = b0 + i;
-            if (b == b0) c = (se0 - sa0) + tail0;
+            if (b == ex) c = 0;
+            else if (b == b0) c = (se0 - sa0) + tail0;
             else if (b == b1) c = se1 + tail1;
             else c = table[T_COLS * b + T_NTOT];
         }
@@ -142,12 +149,20 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
     }
     if (lane == 0) {
         p.V = V; p.n_seeds = count;
-        p.s0 = base0 + sa0; p.e0 = base0 + se0;
-        p.t0s = base0 + ns0; p.t0e = base0 + ns0 + tail0;
-        if (b1 > b0) {
-            p.ms = table[T_COLS * (b0 + 1) + T_BASE];
-            p.e1 = base1 + se1;
-            p.t1s = base1 + ns1; p.t1e = base1 + ns1 + tail1;
+        if (ex >= 0) {
+            // everything before the excluded slab, and everything after it
+            const int32_t *te = table + T_COLS * ex;
+            p.s0 = base0; p.e0 = te[T_BASE];
+            p.ms = te[T_BASE] + te[T_CAP]; p.e1 = base1 + t1[T_CAP];
+            if (V == 0) { p.b0 = 0; p.b1 = -1; }     // nothing lies outside the only bucket
+        } else {
+            p.s0 = base0 + sa0; p.e0 = base0 + se0;
+            p.t0s = base0 + ns0; p.t0e = base0 + ns0 + tail0;
+            if (b1 > b0) {
+                p.ms = table[T_COLS * (b0 + 1) + T_BASE];
+                p.e1 = base1 + se1;
+                p.t1s = base1 + ns1; p.t1e = base1 + ns1 + tail1;
+            }
         }
         p.first_valid = p.s0;
         p.end_valid = b1 > b0 ? p.e1 : p.e0;
@@ -184,8 +199,9 @@ __global__ __launch_bounds__(256) void k_order_bin(const int32_t *__restrict__ t
     const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
     int bin = last, local = 0;
     if (q < nq) {
-        if (only_bucket) {
-            bin = only_bucket[q];
+        if (only_bucket && only_bucket[q] != -1) {
+            const int sc = only_bucket[q];      // scoped queries: by the bucket they are scoped to
+            bin = sc >= 0 ? sc : (sc == INT32_MIN ? last : -2 - sc);
         } else {
             const int lo = lo_[q], hi = hi_[q];
             if (lo <= hi) {
@@ -629,7 +645,7 @@ grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
 grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s) {
     if (s.nq == 0) return GRAB_OK;
     BeamArgs a;
-    a.X = ix->X; a.attr = ix->attr; a.A = ix->A; a.slot2id = ix->slot2id;
+    a.X = ix->X; a.attr = ix->attr; a.A = s.adj ? s.adj : ix->A; a.slot2id = ix->slot2id;
     a.queries = s.queries; a.lo = s.lo; a.hi = s.hi; a.plans = s.plans; a.seeds = s.seeds;
     a.counters = s.counters; a.out_ids = s.out_ids; a.out_dist = s.out_dist;
     a.order = s.order; a.nq = s.nq;

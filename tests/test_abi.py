@@ -57,7 +57,7 @@ def test_calls_out_of_order_and_bad_parameters():
     assert e.value.status == B.ESTATE
     for name, bad in [("search_width", 0), ("search_width", 9), ("visited_cap", 0), ("visited_cap", 1e6),
                       ("alpha", 0.0), ("alpha", 1.5), ("append_beam", 0), ("max_iter", -1), ("n_seeds", -3),
-                      ("profile", 2)]:
+                      ("profile", 2), ("remote_mode", 2), ("n_proximal", 65), ("remote_window", 1.5)]:
         with pytest.raises(B.GrabError) as e:
             ix.set_param(name, bad)
         assert e.value.status == B.EINVAL
