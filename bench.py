@@ -5,7 +5,9 @@ One step = one `grab_search_range` call (bucket-select + seeding kernel, then th
 wave-per-query beam-search kernel) over the whole query batch of the headline workload:
 1,000,000 x 128 fp32 base vectors (256-component Gaussian mixture), uniform integer attribute,
 64 buckets, local degree 32 + remote degree 8, 10,000 queries with 10 % ranges, k = 10.
-All inputs are seeded synthetic data resident in HBM before the timed region.
+All inputs are seeded synthetic data resident in HBM before the timed region.  The index is the
+library's own from end to end: grab_build_buckets, then grab_build_graph (`--graph harness`
+searches the torch-built harness graph instead).
 
 The search parameters (beam, seeds, width, visited capacity) are the fastest of a small grid
 whose measured Recall@10 against exhaustive filtered k-NN is at least 0.95, which is how the
@@ -57,6 +59,18 @@ def main():
     ap.add_argument("--scale", type=int, default=0, help="shrink the workload to this many base vectors (debug)")
     ap.add_argument("--config", default="", help="beam,n_seeds,width,visited_cap[,max_iter]: skip the grid")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--graph", choices=["library", "harness"], default="library",
+                    help="library: the graph grab_build_graph builds (default); harness: the torch-built harness graph")
+    ap.add_argument("--no-recall", action="store_true",
+                    help="with --config: no ground truth, so the process runs no torch matmul (the form to profile)")
+    ap.add_argument("--remote-mode", type=int, default=0, help="remote wiring of construction and insertion (GRAB_P_REMOTE_MODE)")
+    ap.add_argument("--remote-window", type=float, default=0.2, help="remote mode 1: proximal window as a fraction of the attribute span")
+    ap.add_argument("--n-proximal", type=int, default=-1, help="remote mode 1: proximal positions (-1: half of the remote degree)")
+    ap.add_argument("--rewire-from-targets", action="store_true",
+                    help="remote mode 1: construct by target bucket first (mode 0), then rewrite the remote parts with grab_build_remote "
+                         "under mode 1, whose candidate searches then run over a graph that already has cross-bucket edges")
+    ap.add_argument("--holdout-stream", type=int, default=101, help="query stream of the recall check on fresh queries")
+    ap.add_argument("--parity", action="store_true", help="dynamic workload: compare the whole index and one search batch with the oracle after every append")
     ap.add_argument("--alpha", type=float, default=0.6, help="dynamic workload: freshness bias of Eq. 3")
     ap.add_argument("--append-beam", type=int, default=128, help="dynamic workload: queue size of append's searches")
     ap.add_argument("--append-seeds", type=int, default=256, help="dynamic workload: seeds of append's candidate search")
@@ -70,7 +84,10 @@ def main():
         sys.exit(2)
 
     import torch
-    from paper_2604_16402_amd import binding, groundtruth as GT, workloads as W
+    from paper_2604_16402_amd import binding, workloads as W
+    if args.no_recall and not args.config:
+        print("bench.py: --no-recall needs --config (the grid is chosen by recall)", file=sys.stderr)
+        sys.exit(2)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the search path has no CPU fallback", file=sys.stderr)
@@ -102,23 +119,40 @@ def main():
     ix.build_buckets(Xd, ad, cfg.buckets, n_cap)
     torch.cuda.synchronize()
     build["build_buckets_ms"] = round((time.perf_counter() - t) * 1e3, 2)
-    t = time.perf_counter()
-    ix.build_graph(cfg.k_local, cfg.k_remote, 0)       # the library's own two-pass construction (pool 128), timed only
-    torch.cuda.synchronize()
-    build["build_graph_ms"] = round((time.perf_counter() - t) * 1e3, 2)
-    table, id2slot, _ = ix.get_layout()
-    ends = table[:, 0].astype(np.int64) + table[:, 3]
-    bucket_of = np.searchsorted(ends, id2slot.astype(np.int64), side="right")
-    la, ra = W.build_graph(X, bucket_of, cfg.buckets, cfg.k_local, cfg.k_remote, metric=cfg.metric,
-                           device="cuda:0", chunk=16384,
-                           progress=lambda b: log(f"[bench] harness graph: bucket {b + 1} of {cfg.buckets}") if (b + 1) % 16 == 0 else None)
-    lad, rad = torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev)
-    torch.cuda.synchronize()
-    t = time.perf_counter()
-    ix.load_graph(lad, rad)     # the seeded harness graph both the library and the oracle search on
-    torch.cuda.synchronize()
-    build["load_graph_ms"] = round((time.perf_counter() - t) * 1e3, 2)
-    log(f"[bench] index + harness graph built in {time.time() - t0:.1f}s; library calls: {build}")
+    def construct(index):
+        """grab_build_graph under the chosen remote wiring; returns seconds"""
+        index.set_param("remote_mode", 0 if args.rewire_from_targets else args.remote_mode)
+        index.set_param("remote_window", args.remote_window); index.set_param("n_proximal", args.n_proximal)
+        if args.remote_mode == 1:      # construction's candidate search: the tunables of insertion's
+            index.set_param("append_beam", args.append_beam); index.set_param("n_seeds", args.append_seeds)
+            index.set_param("search_width", args.append_width); index.set_param("max_iter", args.append_max_iter)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        index.build_graph(cfg.k_local, cfg.k_remote, 0)       # the library's own two-pass construction (pool 128)
+        if args.remote_mode == 1 and args.rewire_from_targets:
+            index.set_param("remote_mode", 1)
+            index.build_remote()
+        torch.cuda.synchronize()
+        index.set_param("max_iter", 0)
+        return time.perf_counter() - t
+    build["build_graph_ms"] = round(construct(ix) * 1e3, 2)
+    la = ra = None
+    if args.graph == "harness":
+        from harness import graphs as HG
+        table, id2slot, _ = ix.get_layout()
+        ends = table[:, 0].astype(np.int64) + table[:, 3]
+        bucket_of = np.searchsorted(ends, id2slot.astype(np.int64), side="right")
+        la, ra = HG.build_graph(X, bucket_of, cfg.buckets, cfg.k_local, cfg.k_remote, metric=cfg.metric,
+                               device="cuda:0", chunk=16384,
+                               progress=lambda b: log(f"[bench] harness graph: bucket {b + 1} of {cfg.buckets}") if (b + 1) % 16 == 0 else None)
+        lad, rad = torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev)
+        torch.cuda.synchronize()
+        t = time.perf_counter()
+        ix.load_graph(lad, rad)
+        torch.cuda.synchronize()
+        build["load_graph_ms"] = round((time.perf_counter() - t) * 1e3, 2)
+    build["graph"] = args.graph
+    log(f"[bench] index built in {time.time() - t0:.1f}s; library calls: {build}")
 
     if args.copy_calibration:
         src = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
@@ -129,11 +163,14 @@ def main():
         del src, dst
 
     if cfg.append_rounds:
-        return run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build)
+        return run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct)
 
     qd = torch.from_numpy(q).to(dev)
     lod, hid = torch.from_numpy(lo).to(dev), torch.from_numpy(hi).to(dev)
-    gt = GT.exact_filtered_knn(Xd, ad, qd, lod, hid, k, cfg.metric, chunk=max(32, min(512, (1 << 29) // cfg.n)))
+    GT = gt = None
+    if not args.no_recall:
+        from harness import groundtruth as GT
+        gt = GT.exact_filtered_knn(Xd, ad, qd, lod, hid, k, cfg.metric, chunk=max(32, min(512, (1 << 29) // cfg.n)))
     nq = len(q)
     ids = torch.empty((nq, k), dtype=torch.int32, device=dev)
     dist = torch.empty((nq, k), dtype=torch.float32, device=dev)
@@ -165,7 +202,7 @@ def main():
         beam = set_cfg(chosen)
         run_once(beam)
         torch.cuda.synchronize()
-        chosen_recall = GT.recall(ids, gt)
+        chosen_recall = GT.recall(ids, gt) if gt is not None else None
     else:
         best = None
         sweep = []
@@ -215,13 +252,16 @@ def main():
     bytes_per_launch = float((row + ctr[:, 2] * row + ctr[:, 1] * K * 4 + ctr[:, 5] * 4 + k * 8).sum())
     avg_beam_ms = float(np.mean(beam_ms))
     achieved = bytes_per_launch / (avg_beam_ms * 1e-3) / 1e9
+    # HBM-side traffic of this kernel at this setting: FETCH_SIZE + WRITE_SIZE of separate
+    # `rocprofv3 --pmc` runs of this program, kept in profiles/ (counters cannot be read from inside)
     traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic_beam_search_c2.json")
-    if os.path.exists(tpath) and args.workload == "c2" and not args.scale and abs(args.selectivity - 0.1) < 1e-9:
+    tpath = os.path.join(ROOT, "profiles", "traffic_beam_search.json")
+    sel_key = "log-uniform" if args.selectivity <= 0 else format(args.selectivity, "g")
+    if os.path.exists(tpath) and not args.scale:
         try:
-            tj = json.load(open(tpath))
-            for ent in tj.get("settings", []):
-                if list(ent.get("config", [])) == list(chosen) + [0] * (5 - len(chosen)):
+            for ent in json.load(open(tpath)).get("settings", []):
+                if (ent.get("workload") == args.workload and str(ent.get("selectivity")) == sel_key and ent.get("graph") == args.graph
+                        and list(ent.get("config", [])) == list(chosen) + [0] * (5 - len(chosen))):
                     traffic = ent.get("hbm_bytes_per_launch")
         except Exception:
             traffic = None
@@ -230,10 +270,34 @@ def main():
     gather_gbs = g_bytes / (g_ms * 1e-3) / 1e9
     roofline = {"bound": "hbm", "kernel": "k_beam_search<%d,%d>" % (cfg.dim // 32, 1 if chosen[0] <= 64 else 2 if chosen[0] <= 128 else 4 if chosen[0] <= 256 else 8), "achieved": round(achieved, 1), "peak": PEAK_HBM_GBS,
                 "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
+                # achieved / frac price the ALGORITHMIC bytes (what the method must move); the traffic_* pair
+                # prices the bytes the counters saw crossing from the memory fabric into L2
+                "frac_kind": "algorithmic bytes / kernel time / HBM peak",
+                "traffic_gbs": None if traffic is None else round(traffic / (avg_beam_ms * 1e-3) / 1e9, 1),
+                "traffic_frac": None if traffic is None else round(traffic / (avg_beam_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                "note": "rows served by L2 lower traffic below the algorithmic bytes; the byte counters sit between L2 and the "
+                        "memory fabric, so rows served by the 256 MB Infinity Cache still count as traffic: on an index that "
+                        "partly fits it (1M x 128 = 0.67 GB) true HBM utilisation is below traffic_frac by an unmeasured amount",
                 "bytes_per_launch": bytes_per_launch, "avg_kernel_ms": round(avg_beam_ms, 4),
                 "select_kernel_ms": round(float(np.mean(select_ms)), 4),
                 "evals_per_query": round(float(ctr[:, 2].mean()), 1), "parents_per_query": round(float(ctr[:, 1].mean()), 1),
                 "random_row_gather_gbs": round(gather_gbs, 1)}
+
+    # ---- the chosen setting on queries it was not chosen on
+    holdout = None
+    if gt is not None:
+        q2 = torch.from_numpy(W.query_vectors(cfg, stream=args.holdout_stream)).to(dev)
+        lo2, hi2 = W.ranges(cfg, args.selectivity if args.selectivity > 0 else None, stream=300 + args.holdout_stream)
+        lo2d, hi2d = torch.from_numpy(lo2).to(dev), torch.from_numpy(hi2).to(dev)
+        ids2 = torch.empty((len(q2), k), dtype=torch.int32, device=dev)
+        dist2 = torch.empty((len(q2), k), dtype=torch.float32, device=dev)
+        ix.search_range(q2, lo2d, hi2d, k, beam, ids2, dist2)
+        torch.cuda.synchronize()
+        gt2 = GT.exact_filtered_knn(Xd, ad, q2, lo2d, hi2d, k, cfg.metric, chunk=max(32, min(512, (1 << 29) // cfg.n)))
+        holdout = round(GT.recall(ids2, gt2), 4)
+        del q2, ids2, dist2, gt2
+        run_once(beam)                 # the counters and outputs below are those of the timed batch again
+        torch.cuda.synchronize()
 
     # ---- CPU baseline: the oracle as it stands, all host cores, same inputs and graph
     cpu = None
@@ -242,7 +306,12 @@ def main():
         from oracle import oracle as O
         t0 = time.time()
         ora = O.Index(X, attrs, cfg.buckets, metric=cfg.metric)
-        ora.load_graph(la, ra)
+        if la is not None:
+            ora.load_graph(la, ra)
+        else:
+            # the oracle times its search over the graph the library built (that construction is
+            # compared with the oracle's own, bit for bit, by the GPU tests)
+            ora.k_local, ora.k_remote, ora.A = cfg.k_local, cfg.k_remote, ix.get_graph()
         ora.params.update(search_width=chosen[2], n_seeds=chosen[1], visited_cap=max(chosen[3], chosen[1]),
                           max_iter=(chosen[4] if len(chosen) > 4 and chosen[4] > 0 else None))
         cores = min(O.max_threads(), os.cpu_count() or 1)
@@ -273,7 +342,8 @@ def main():
                                f"{nq} queries, {(format(args.selectivity, '.0%') if args.selectivity > 0 else 'log-uniform 0.1%..100%')} range, k={k}",
                    "beam": chosen[0], "n_seeds": chosen[1], "search_width": chosen[2], "visited_cap": max(chosen[3], chosen[1]),
                    "max_iter": (chosen[4] if len(chosen) > 4 and chosen[4] > 0 else 2 * chosen[0]),
-                   "recall_at_10": round(chosen_recall, 4)},
+                   "recall_at_10": None if chosen_recall is None else round(chosen_recall, 4),
+                   "recall_at_10_holdout": holdout, "graph": args.graph, "remote_mode": args.remote_mode},
         "roofline": roofline, "cpu_baseline": cpu, "parity_vs_oracle": parity, "build": build,
         # every swept setting: [beam, n_seeds, search_width, visited_cap, max_iter (0 = 2 x beam), recall@10, queries/s]
         "sweep": sweep,
@@ -283,14 +353,26 @@ def main():
     print(json.dumps(out), flush=True)
 
 
-def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
+def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
     """Dynamic workload: rounds of `grab_append_batch` (100k new objects with attributes over the
     whole domain) each followed by a fresh 10k-query search batch at 10 % range (Section 5.3's
     stability protocol on synthetic data).  Reports append vectors/s and search QPS per round."""
     import torch
-    from paper_2604_16402_amd import groundtruth as GT, workloads as W
+    from harness import groundtruth as GT
+    from paper_2604_16402_amd import workloads as W
     k = cfg.k
     beam, S, w, vc = [int(x) for x in (args.config or "32,512,4,1400").split(",")][:4]
+    ora = None
+    parity_rounds = []
+    if args.parity:
+        # the oracle follows every append on its own copy of the index, starting from the graph the
+        # library built (construction itself is compared with the oracle by the GPU tests)
+        from oracle import oracle as O
+        ora = O.Index(X, attrs, cfg.buckets, n_cap=ix.sizes()["n_slots"], metric=cfg.metric)
+        ora.k_local, ora.k_remote, ora.A = cfg.k_local, cfg.k_remote, ix.get_graph()
+        ora.params.update(alpha=args.alpha, append_beam=args.append_beam, remote_mode=args.remote_mode,
+                          remote_window=args.remote_window, n_proximal=None if args.n_proximal < 0 else args.n_proximal)
+        assert ora.n_cap == ix.sizes()["n_slots"]
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     ix.set_param("alpha", args.alpha)
     ix.set_param("append_beam", args.append_beam)
@@ -341,6 +423,15 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
         ix.append_batch(nx, na)
         torch.cuda.synchronize()
         t_app = time.perf_counter() - t
+        if ora is not None:
+            ora.params.update(visited_cap=2800, n_seeds=args.append_seeds, search_width=args.append_width, max_iter=args.append_max_iter)
+            t = time.perf_counter()
+            ora.append(nx.cpu().numpy(), na.cpu().numpy(), threads=O.max_threads())
+            t_ora = time.perf_counter() - t
+            table, id2slot, slot2id = ix.get_layout()
+            same = bool(np.array_equal(table, ora.table) and np.array_equal(id2slot, ora.id2slot[:ora.n]) and
+                        np.array_equal(slot2id, ora.slot2id) and np.array_equal(ix.get_graph(), ora.A))
+            parity_rounds.append({"round": r + 1, "index_identical": same, "oracle_append_s": round(t_ora, 2)})
         allX, alla = torch.cat([allX, nx]), torch.cat([alla, na])
         ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
         ix.set_param("max_iter", 0)
@@ -357,6 +448,12 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
         torch.cuda.synchronize()
         t_s = (time.perf_counter() - t) / 10
         gt = GT.exact_filtered_knn(allX, alla, q, lod, hid, k, cfg.metric)
+        if ora is not None:
+            ora.params.update(visited_cap=vc, n_seeds=S, search_width=w, max_iter=None)
+            o_ids, o_dist, _ = ora.search(q.cpu().numpy(), lo, hi, k, beam, threads=O.max_threads())
+            parity_rounds[-1]["search_identical"] = bool(np.array_equal(ids.cpu().numpy().view(np.uint32), o_ids) and
+                                                         np.array_equal(dist.cpu().numpy(), o_dist))
+            log(f"[bench] parity after round {r + 1}: {parity_rounds[-1]}")
         new_frac = float((ids.cpu().numpy().view(np.uint32) >= cfg.n).mean())
         rounds.append({"round": r + 1, "objects": ix.sizes()["n"], "append_vectors_per_s": round(cfg.append_batch / t_app, 1),
                        "append_ms": round(t_app * 1e3, 2), "search_qps": round(len(q) / t_s, 1),
@@ -365,21 +462,18 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
     at_recall["after_appends"] = qps_at_recall(ix, q, lod, hid, gt, ids, dist)
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     # connectivity of the grown graph (Section 5.4's diagnostic)
-    from paper_2604_16402_amd import binding, diagnostics
+    from harness import diagnostics
+    from paper_2604_16402_amd import binding
     _, _, slot2id = ix.get_layout()
     final_adj = ix.get_graph()
     scc = diagnostics.strong_components(final_adj, slot2id != 0xFFFFFFFF)
     n_orphans = diagnostics.orphans(final_adj, slot2id != 0xFFFFFFFF)
     del final_adj
     log(f"[bench] after the appends: {scc} strongly connected components, {n_orphans} objects without an in-edge")
-    # context: the same final data set bulk-built by the harness, searched with the same setting
+    # context: the same final data set built in bulk by grab_build_graph, searched with the same setting
     ref = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
     ref.build_buckets(allX, alla, cfg.buckets)
-    table, id2slot, _ = ref.get_layout()
-    ends = table[:, 0].astype(np.int64) + table[:, 3]
-    la, ra = W.build_graph(allX.cpu().numpy(), np.searchsorted(ends, id2slot.astype(np.int64), side="right"), cfg.buckets,
-                           cfg.k_local, cfg.k_remote, metric=cfg.metric, device="cuda:0", chunk=16384)
-    ref.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
+    construct(ref)
     ref.set_param("visited_cap", vc); ref.set_param("n_seeds", S); ref.set_param("search_width", w)
     ref.search_range(q, lod, hid, k, beam, ids, dist)
     torch.cuda.synchronize()
@@ -394,7 +488,9 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build):
                                   f"{cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, 10000 queries per round, "
                                   f"{args.selectivity:.0%} range, k={k}",
                       "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width, "append_max_iter": args.append_max_iter,
-                      "alpha": args.alpha},
+                      "alpha": args.alpha, "remote_mode": args.remote_mode, "remote_window": args.remote_window,
+                      "n_proximal": args.n_proximal, "rewire_from_targets": args.rewire_from_targets, "graph": "library"},
+           "parity_vs_oracle": parity_rounds or None,
            "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
            "search_rate_at_recall_0.95": at_recall, "strong_components_final": scc, "orphans_final": n_orphans, "bulk_rebuilt_reference_final": rebuilt, "build": build}
     ix.close()

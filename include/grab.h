@@ -24,7 +24,9 @@
  *     grab_build_buckets input and continue n, n+1, ... in append order.  "Slots" are
  *     physical row numbers of the bucket-major device arrays.
  *   - 0xFFFFFFFF marks an empty adjacency entry and a missing result.
- *   - dim must be a multiple of 32 (rows are whole 128-byte lines) and at most 2048.
+ *   - dim must be one of 32, 64, 96, 128, 160, 192, 256, 384, 512, 640, 768, 960, 1024, 1536,
+ *     2048 (rows are whole 128-byte lines, and the kernels are built per row length);
+ *     grab_create refuses any other value with GRAB_EINVAL.
  *   - The queries of a batch are independent; the library runs them in an order of its own
  *     (grouped by the buckets they select) and every result is what it would be in any order.
  *   - Not thread-safe per handle; different handles are independent.

@@ -111,7 +111,7 @@ extern "C" {
 grab_status grab_create(grab_index **out, int32_t dim, int32_t metric, void *hip_stream) {
     if (!out) return GRAB_EINVAL;
     *out = nullptr;
-    if (dim < 32 || dim > 2048 || dim % 32 != 0) return GRAB_EINVAL;
+    if (!grab_dim_supported(dim)) return GRAB_EINVAL;   // one of GRAB_DIM_LIST
     if (metric != GRAB_L2SQ && metric != GRAB_IP) return GRAB_EINVAL;
     grab_index *ix = new (std::nothrow) grab_index();
     if (!ix) return GRAB_ENOMEM;

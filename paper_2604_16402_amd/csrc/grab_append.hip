@@ -588,8 +588,7 @@ grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireAr
 grab_status launch_append(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
     switch (ix->dim / 32) {
 #define GRAB_CASE(N) case N: return launch_append_t<N>(ix, f, r, m, phase);
-        GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
-        GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
+        GRAB_FOR_EACH_NCH(GRAB_CASE)
 #undef GRAB_CASE
         default:
             return grab_fail(ix, GRAB_EINVAL, "dim %d has no append kernel", ix->dim);

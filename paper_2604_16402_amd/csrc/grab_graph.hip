@@ -313,8 +313,7 @@ grab_status launch_graph_t(grab_index *ix, const KnnArgs *k, const PruneArgs *p,
 grab_status launch_graph(grab_index *ix, const KnnArgs *k, const PruneArgs *p, unsigned tiles) {
     switch (ix->dim / 32) {
 #define GRAB_CASE(N) case N: return launch_graph_t<N>(ix, k, p, tiles);
-        GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
-        GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
+        GRAB_FOR_EACH_NCH(GRAB_CASE)
 #undef GRAB_CASE
         default:
             return grab_fail(ix, GRAB_EINVAL, "dim %d has no construction kernel", ix->dim);

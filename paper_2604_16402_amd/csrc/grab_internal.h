@@ -15,6 +15,22 @@
 #define GRAB_MAX_CAND 512   // search_width * degree, and the seed chunk size
 #define GRAB_WAVE 64
 
+// The vector lengths the kernels are built for, in 32-float (128-byte) units: every kernel that
+// reads feature rows is instantiated once per entry, so that a whole row's loads can be issued
+// before the first multiply.  grab_create refuses any other length.
+#define GRAB_FOR_EACH_NCH(X) X(1) X(2) X(3) X(4) X(5) X(6) X(8) X(12) X(16) X(20) X(24) X(30) X(32) X(48) X(64)
+#define GRAB_DIM_LIST "32, 64, 96, 128, 160, 192, 256, 384, 512, 640, 768, 960, 1024, 1536, 2048"
+inline bool grab_dim_supported(int dim) {
+    if (dim % 32) return false;
+    switch (dim / 32) {
+#define GRAB_DIM_CASE(N) case N:
+        GRAB_FOR_EACH_NCH(GRAB_DIM_CASE)
+#undef GRAB_DIM_CASE
+        return true;
+        default: return false;
+    }
+}
+
 // bucket table columns (Section 4.2.4: the bucket<->index metadata)
 enum { T_BASE = 0, T_NSORT = 1, T_NTOT = 2, T_CAP = 3, T_MIN = 4, T_MAX = 5, T_COLS = 6 };
 

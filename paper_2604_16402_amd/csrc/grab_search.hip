@@ -588,8 +588,7 @@ grab_status launch_probe_t(grab_index *ix, int64_t waves, int32_t batches, float
 grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batches, float *sink, double *bytes) {
     switch (ix->dim / 32) {
 #define GRAB_CASE(N) case N: return launch_probe_t<N>(ix, waves, batches, sink, bytes);
-        GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
-        GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
+        GRAB_FOR_EACH_NCH(GRAB_CASE)
 #undef GRAB_CASE
         default:
             return grab_fail(ix, GRAB_EINVAL, "dim %d has no search kernel", ix->dim);
@@ -661,10 +660,9 @@ grab_status grab_launch_beam(grab_index *ix, const SearchLaunch &s) {
     const int nch = ix->dim / 32;
     switch (nch) {
 #define GRAB_CASE(N) case N: return launch_beam_t<N>(ix, a, s.order ? s.order_len : s.nq, H);
-        GRAB_CASE(1) GRAB_CASE(2) GRAB_CASE(3) GRAB_CASE(4) GRAB_CASE(8) GRAB_CASE(16) GRAB_CASE(24)
-        GRAB_CASE(30) GRAB_CASE(32) GRAB_CASE(48) GRAB_CASE(64)
+        GRAB_FOR_EACH_NCH(GRAB_CASE)
 #undef GRAB_CASE
         default:
-            return grab_fail(ix, GRAB_EINVAL, "dim %d has no search kernel (supported: 32,64,96,128,256,512,768,960,1024,1536,2048)", ix->dim);
+            return grab_fail(ix, GRAB_EINVAL, "dim %d has no search kernel", ix->dim);
     }
 }

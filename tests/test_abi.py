@@ -34,6 +34,12 @@ def test_create_validates_arguments(lib):
     h = ctypes.c_void_p()
     assert lib.grab_create(ctypes.byref(h), 100, 0, None) == 1      # dim not a multiple of 32
     assert lib.grab_create(ctypes.byref(h), 4096, 0, None) == 1     # dim too large
+    supported = [32, 64, 96, 128, 160, 192, 256, 384, 512, 640, 768, 960, 1024, 1536, 2048]
+    for dim in range(32, 2049, 32):                                  # a length without kernels is refused up front
+        rc = lib.grab_create(ctypes.byref(h), dim, 0, None)
+        assert rc == (0 if dim in supported else 1), dim
+        if rc == 0:
+            lib.grab_destroy(h)
     assert lib.grab_create(ctypes.byref(h), 128, 7, None) == 1      # unknown metric
     assert lib.grab_create(None, 128, 0, None) == 1
     assert lib.grab_create(ctypes.byref(h), 128, 0, None) == 0 and h.value

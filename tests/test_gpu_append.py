@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import oracle as O
+from harness import graphs as HG
 from paper_2604_16402_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -75,7 +76,7 @@ def _pair(n, dim, B, kl, kr, n_cap, seed, components=16, metric=W.L2SQ):
                    append_rounds=3, append_batch=max(64, n // 8))
     X, a = W.base_vectors(cfg), W.attributes(cfg)
     ora = O.Index(X, a, B, n_cap=n_cap, metric=metric)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric,
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric,
                            device="cuda:0" if n > 20000 else "cpu", chunk=8192)
     ora.load_graph(la, ra)
     ix = binding.Index(dim, metric)

@@ -83,7 +83,8 @@ def test_full_size_build_properties_and_recall():
     # one, structural properties on every row, and search recall on the built graph
     import time
     import torch
-    from paper_2604_16402_amd import binding, groundtruth as GT
+    from harness import groundtruth as GT
+    from paper_2604_16402_amd import binding
     dev = torch.device("cuda:0")
     cfg = W.CONFIGS["c2"]
     X, a, q = W.base_vectors(cfg), W.attributes(cfg), W.query_vectors(cfg)

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 from oracle import oracle as O
+from harness import graphs as HG
 from paper_2604_16402_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -28,7 +29,7 @@ def test_float_attributes_match_oracle_through_build_search_and_append():
     a = rng.random(n).astype(np.float32)                      # uniform in [0,1) as in Section 5.1
     a[:6] = [0.0, -0.0, 0.5, 0.5, 1.0, -0.25]
     ora = O.Index(X, O.float_order_key(a), nb, n_cap=n_cap)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), nb, kl, kr)
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), nb, kl, kr)
     ora.load_graph(la, ra)
     dev = torch.device("cuda:0")
     ix = B.Index(dim)

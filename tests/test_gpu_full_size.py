@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 
 from oracle import oracle as O
+from harness import graphs as HG
 from paper_2604_16402_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -12,7 +13,8 @@ pytestmark = pytest.mark.gpu
 @pytest.fixture(scope="module")
 def c2_full():
     import torch
-    from paper_2604_16402_amd import binding, groundtruth as GT
+    from harness import groundtruth as GT
+    from paper_2604_16402_amd import binding
     dev = torch.device("cuda:0")
     cfg = W.CONFIGS["c2"]
     X, a, q = W.base_vectors(cfg), W.attributes(cfg), W.query_vectors(cfg)
@@ -23,7 +25,7 @@ def c2_full():
     table, id2slot, slot2id = ix.get_layout()
     assert np.array_equal(table, ora.table) and np.array_equal(id2slot, ora.id2slot[:cfg.n])
     assert np.array_equal(slot2id, ora.slot2id)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, device="cuda:0", chunk=16384)
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, device="cuda:0", chunk=16384)
     ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
     ora.load_graph(la, ra)
     return dict(cfg=cfg, X=X, attrs=a, q=q, ix=ix, ora=ora, dev=dev, Xd=Xd, ad=ad, GT=GT)
@@ -75,7 +77,8 @@ def test_full_size_matches_oracle(c2_full, sel, beam, seeds, width, vcap, max_it
 
 def _full_pair(name, n_queries=None):
     import torch
-    from paper_2604_16402_amd import binding, groundtruth as GT
+    from harness import groundtruth as GT
+    from paper_2604_16402_amd import binding
     dev = torch.device("cuda:0")
     cfg = W.CONFIGS[name]
     X, a = W.base_vectors(cfg), W.attributes(cfg)
@@ -87,7 +90,7 @@ def _full_pair(name, n_queries=None):
     table, id2slot, slot2id = ix.get_layout()
     assert np.array_equal(table, ora.table) and np.array_equal(id2slot, ora.id2slot[:cfg.n])
     assert np.array_equal(slot2id, ora.slot2id)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, metric=cfg.metric,
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, metric=cfg.metric,
                            device="cuda:0", chunk=16384)
     ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
     ora.load_graph(la, ra)
@@ -169,7 +172,7 @@ def test_dynamic_config_matches_oracle_at_full_size():
     ix = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
     ix.build_buckets(torch.from_numpy(X).to(dev), torch.from_numpy(a).to(dev), cfg.buckets, n_cap)
     ora = O.Index(X, a, cfg.buckets, n_cap=n_cap)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, device="cuda:0", chunk=16384)
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, device="cuda:0", chunk=16384)
     ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
     ora.load_graph(la, ra)
     for r in range(2):

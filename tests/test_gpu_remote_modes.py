@@ -8,6 +8,7 @@ import numpy as np
 import pytest
 
 from oracle import oracle as O
+from harness import graphs as HG
 from paper_2604_16402_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -101,7 +102,7 @@ def test_second_pass_alone_on_a_loaded_graph(mode):
     # grab_build_remote on a graph the harness made: 100,000 objects, 16 buckets
     n, B, kl, kr = 100_000, 16, 32, 8
     cfg, ix, ora, X, a = _fresh_pair(n, 128, B, n, seed=4242, components=64)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), B, kl, kr, device="cuda:0", chunk=8192)
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), B, kl, kr, device="cuda:0", chunk=8192)
     ix.load_graph(la, ra)
     ora.load_graph(la, ra)
     _set(ix, ora, remote_mode=mode, append_beam=64, n_seeds=128, search_width=2, max_iter=24)
@@ -134,7 +135,7 @@ def test_second_pass_alone_on_a_loaded_graph(mode):
 def test_append_matches_oracle_under_both_readings(n, dim, B, kl, kr, n_cap, beam, width, metric, mode):
     cfg, ix, ora, X, a = _fresh_pair(n, dim, B, n_cap, seed=n + dim + mode, metric=metric)
     _set(ix, ora, remote_mode=mode, append_beam=beam, search_width=width, n_seeds=96)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric, device="cuda:0" if n > 20000 else "cpu", chunk=8192)
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric, device="cuda:0" if n > 20000 else "cpu", chunk=8192)
     ix.load_graph(la, ra)
     ora.load_graph(la, ra)
     if mode == 1:                        # remote parts as the second reading builds them, on both sides

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 
 from oracle import oracle as O
+from harness import graphs as HG
 from paper_2604_16402_amd import workloads as W
 
 pytestmark = pytest.mark.gpu
@@ -84,7 +85,7 @@ def _random_case(n, dim, B, kl, kr, metric, seed, n_cap=None, nq=300, domain=Non
                    normalise=(metric == W.IP), seed=seed)
     X, a, q = W.base_vectors(cfg), W.attributes(cfg), W.query_vectors(cfg)
     ora = O.Index(X, a, B, n_cap=n_cap, metric=metric)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric)
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric)
     ora.load_graph(la, ra)
     return dict(cfg=cfg, X=X, attrs=a, queries=q, local=la, remote=ra, oracle=ora)
 
@@ -239,9 +240,9 @@ def test_wide_parameter_surface(torch_dev, dim, kl, kr, beam, width, seeds, vcap
     cfg = W.Config("wide", n, dim, 8, 0.4, n, B, min(kl, 64), min(kr, 64), 200, (0.3,), seed=dim + kl)
     X, a, q = W.base_vectors(cfg), W.attributes(cfg), W.query_vectors(cfg)
     ora = O.Index(X, a, B)
-    la, ra = W.build_graph(X, ora.bucket_of_ids(), B, min(kl, 64), kr, pool=min(2 * kl, 200))
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), B, min(kl, 64), kr, pool=min(2 * kl, 200))
     if kl > 64:      # pad the local part with further in-bucket neighbours to reach the requested width
-        la2, _ = W.build_graph(X, ora.bucket_of_ids(), B, kl, 0, pool=kl + 20)
+        la2, _ = HG.build_graph(X, ora.bucket_of_ids(), B, kl, 0, pool=kl + 20)
         la = la2
     ora.load_graph(la, ra)
     c = dict(cfg=cfg, X=X, attrs=a, local=la, remote=ra)

@@ -2,7 +2,8 @@
 import numpy as np
 
 from oracle import oracle as O
-from paper_2604_16402_amd import diagnostics, workloads as W
+from harness import diagnostics
+from paper_2604_16402_amd import workloads as W
 
 
 def test_generators_are_seeded_and_shaped():

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from oracle import oracle as O
+from harness import graphs as HG
 from paper_2604_16402_amd import workloads as W
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
@@ -39,7 +40,7 @@ def grown():
     cfg = W.scaled(W.CONFIGS["c5"], 6000, n_queries=300, buckets=8, components=16, append_batch=750)
     X, a = W.base_vectors(cfg), W.attributes(cfg)
     ix = O.Index(X, a, cfg.buckets, n_cap=8000)
-    la, ra = W.build_graph(X, ix.bucket_of_ids(), cfg.buckets, 16, 4)
+    la, ra = HG.build_graph(X, ix.bucket_of_ids(), cfg.buckets, 16, 4)
     ix.load_graph(la, ra)
     before = dict(X=ix.X.copy(), attr=ix.attr.copy(), slot2id=ix.slot2id.copy(), A=ix.A.copy(), table=ix.table.copy())
     batches = []
@@ -189,7 +190,7 @@ def _fresh(alpha, cap=8000):
     cfg = W.scaled(W.CONFIGS["c5"], 3000, n_queries=100, buckets=4, components=8, append_batch=400)
     X, a = W.base_vectors(cfg), W.attributes(cfg)
     ix = O.Index(X, a, cfg.buckets, n_cap=cap)
-    la, ra = W.build_graph(X, ix.bucket_of_ids(), cfg.buckets, 12, 3)
+    la, ra = HG.build_graph(X, ix.bucket_of_ids(), cfg.buckets, 12, 3)
     ix.load_graph(la, ra)
     ix.params["alpha"] = alpha
     return cfg, ix
@@ -247,7 +248,7 @@ def test_no_node_loses_its_last_in_edge(grown):
     indeg0 = np.bincount(A0[A0 != O.EMPTY].astype(np.int64), minlength=ix.n_cap)
     old_slots = np.nonzero(b["slot2id"] != O.EMPTY)[0]
     assert ((indeg[old_slots] > 0) | (indeg0[old_slots] == 0)).all()
-    from paper_2604_16402_amd import diagnostics
+    from harness import diagnostics
     before = diagnostics.strong_components(b["A"], b["slot2id"] != O.EMPTY)
     after = diagnostics.strong_components(ix.A, ix.slot2id != O.EMPTY)
     assert after <= before + 2                    # appends do not fragment the graph (Section 5.4)
