@@ -160,39 +160,102 @@ def test_ten_million_inner_product_zipf_config_matches_oracle():
     ix.close()
 
 
-def test_dynamic_config_matches_oracle_at_full_size():
-    # 1M x 128 base, an append of 100,000 objects (the dynamic workload's round) and one of 30,000, whole
-    # index compared after each append, then a 10,000-query batch at 10 % range
+@pytest.fixture(scope="module")
+def c5_inputs():
+    """The dynamic workload's base set (1M x 128, 64 buckets) with the harness graph, made once."""
+    cfg = W.CONFIGS["c5"]
+    X, a = W.base_vectors(cfg), W.attributes(cfg)
+    n_cap = cfg.n + int(1.2 * cfg.append_rounds * cfg.append_batch)      # the capacity bench.py asks for
+    ora = O.Index(X, a, cfg.buckets, n_cap=n_cap)
+    la, ra = HG.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, device="cuda:0", chunk=16384)
+    return dict(cfg=cfg, X=X, a=a, n_cap=n_cap, la=la, ra=ra)
+
+
+def _c5_pair(c):
     import torch
     from paper_2604_16402_amd import binding
     dev = torch.device("cuda:0")
-    cfg = W.CONFIGS["c5"]
-    X, a = W.base_vectors(cfg), W.attributes(cfg)
-    n_cap = cfg.n + 3 * cfg.append_batch
+    cfg = c["cfg"]
     ix = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
-    ix.build_buckets(torch.from_numpy(X).to(dev), torch.from_numpy(a).to(dev), cfg.buckets, n_cap)
-    ora = O.Index(X, a, cfg.buckets, n_cap=n_cap)
-    la, ra = HG.build_graph(X, ora.bucket_of_ids(), cfg.buckets, cfg.k_local, cfg.k_remote, device="cuda:0", chunk=16384)
-    ix.load_graph(torch.from_numpy(la.view(np.int32)).to(dev), torch.from_numpy(ra.view(np.int32)).to(dev))
-    ora.load_graph(la, ra)
-    for r in range(2):
+    ix.build_buckets(torch.from_numpy(c["X"]).to(dev), torch.from_numpy(c["a"]).to(dev), cfg.buckets, c["n_cap"])
+    ora = O.Index(c["X"], c["a"], cfg.buckets, n_cap=c["n_cap"])
+    return ix, ora, dev
+
+
+def _same_whole_index(ix, ora):
+    table, id2slot, slot2id = ix.get_layout()
+    assert np.array_equal(table, ora.table) and np.array_equal(id2slot, ora.id2slot[:ora.n])
+    assert np.array_equal(slot2id, ora.slot2id)
+    got = ix.get_graph()
+    if not np.array_equal(got, ora.A):
+        bad = np.nonzero((got != ora.A).any(1))[0]
+        raise AssertionError(f"{len(bad)} adjacency rows differ, first slot {bad[0]}: {got[bad[0]]} vs {ora.A[bad[0]]}")
+
+
+def test_all_ten_rounds_of_the_dynamic_config_match_the_oracle(c5_inputs):
+    # 1M x 128 growing to 2M by ten appends of 100,000 objects, with the candidate-search setting
+    # bench.py uses for this workload; the whole index is compared after every append, and a
+    # 10,000-query batch at 10 % range after rounds 1, 5 and 10 (by round 10 the appended tails are
+    # as long as the sorted prefixes)
+    import torch
+    c = c5_inputs
+    cfg = c["cfg"]
+    ix, ora, dev = _c5_pair(c)
+    ix.load_graph(torch.from_numpy(c["la"].view(np.int32)).to(dev), torch.from_numpy(c["ra"].view(np.int32)).to(dev))
+    ora.load_graph(c["la"], c["ra"])
+    ix.set_param("append_beam", 128); ora.params["append_beam"] = 128
+    for r in range(cfg.append_rounds):
         nx, na = W.append_vectors(cfg, r), W.append_attributes(cfg, r)
-        if r == 1:                                   # second batch smaller: lands on tails that already hold objects
-            nx, na = nx[:30_000], na[:30_000]
+        ix.set_param("visited_cap", 2800); ix.set_param("n_seeds", 256); ix.set_param("search_width", 4); ix.set_param("max_iter", 24)
+        ora.params.update(visited_cap=2800, n_seeds=256, search_width=4, max_iter=24)
         ix.append_batch(torch.from_numpy(nx).to(dev), torch.from_numpy(na).to(dev))
         ora.append(nx, na, threads=O.max_threads())
-        table, id2slot, slot2id = ix.get_layout()
-        assert np.array_equal(table, ora.table) and np.array_equal(id2slot, ora.id2slot[:ora.n])
-        assert np.array_equal(slot2id, ora.slot2id)
-        assert np.array_equal(ix.get_graph(), ora.A)
+        _same_whole_index(ix, ora)
+        print(f"round {r + 1}: {ora.n} objects, index identical", flush=True)
+        if r in (0, 4, 9):
+            q = W.query_vectors(cfg, stream=100 + r)
+            lo, hi = W.ranges(cfg, 0.1, stream=300 + r)
+            ix.set_param("visited_cap", 1400); ix.set_param("n_seeds", 512); ix.set_param("search_width", 4); ix.set_param("max_iter", 0)
+            ora.params.update(visited_cap=1400, n_seeds=512, search_width=4, max_iter=None)
+            _compare(cfg, ix, ora, q, lo, hi, 32, dev)
+            assert ix.get_counters(len(q))[:, 5].sum() > 0      # appended tails of edge buckets were pre-checked by attribute
+    assert ora.n == 2_000_000
     xs, at = ix.get_rows()
     live = ora.slot2id != O.EMPTY
     assert np.array_equal(xs[live], ora.X[live]) and np.array_equal(at[live], ora.attr[live])
+    t = ora.table
+    assert (t[:, 2] - t[:, 1] > 0.8 * t[:, 1]).all()              # tails about as long as the sorted prefixes
+    ix.close()
+
+
+def test_second_reading_matches_the_oracle_at_full_size(c5_inputs):
+    # the proximal/global wiring at 1M x 128: pass 2 of the construction over the harness graph
+    # (one candidate search per object), then an append of 100,000 objects and one of 30,000
+    import torch
+    c = c5_inputs
+    cfg = c["cfg"]
+    ix, ora, dev = _c5_pair(c)
+    ix.set_param("remote_mode", 1); ora.params["remote_mode"] = 1
+    ix.load_graph(torch.from_numpy(c["la"].view(np.int32)).to(dev), torch.from_numpy(c["ra"].view(np.int32)).to(dev))
+    ora.load_graph(c["la"], c["ra"])
+    ix.set_param("append_beam", 64); ora.params["append_beam"] = 64
+    ix.set_param("visited_cap", 2800); ix.set_param("n_seeds", 128); ix.set_param("search_width", 4); ix.set_param("max_iter", 16)
+    ora.params.update(visited_cap=2800, n_seeds=128, search_width=4, max_iter=16)
+    ix.build_remote()
+    ora.build_remote(threads=O.max_threads())
+    _same_whole_index(ix, ora)
+    print("pass 2 identical", flush=True)
+    for r in range(2):
+        nx, na = W.append_vectors(cfg, r), W.append_attributes(cfg, r)
+        if r == 1:
+            nx, na = nx[:30_000], na[:30_000]
+        ix.append_batch(torch.from_numpy(nx).to(dev), torch.from_numpy(na).to(dev))
+        ora.append(nx, na, threads=O.max_threads())
+        _same_whole_index(ix, ora)
+        print(f"append {r + 1} identical", flush=True)
     q = W.query_vectors(cfg)
     lo, hi = W.ranges(cfg, 0.1)
-    for beam, seeds, width, vcap in [(64, 0, 1, 2800), (32, 256, 4, 1400)]:
-        ix.set_param("visited_cap", vcap); ix.set_param("n_seeds", seeds); ix.set_param("search_width", width)
-        ora.params.update(visited_cap=vcap, n_seeds=seeds or None, search_width=width)
-        _compare(cfg, ix, ora, q, lo, hi, beam, dev)
-    assert ix.get_counters(len(q))[:, 5].sum() > 0      # appended tails of edge buckets were pre-checked by attribute
+    ix.set_param("visited_cap", 1400); ix.set_param("n_seeds", 256); ix.set_param("max_iter", 0)
+    ora.params.update(visited_cap=1400, n_seeds=256, max_iter=None)
+    _compare(cfg, ix, ora, q, lo, hi, 32, dev)
     ix.close()
