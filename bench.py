@@ -76,6 +76,11 @@ def main():
     ap.add_argument("--append-seeds", type=int, default=256, help="dynamic workload: seeds of append's candidate search")
     ap.add_argument("--append-width", type=int, default=4, help="dynamic workload: search width of append's candidate search")
     ap.add_argument("--append-max-iter", type=int, default=24, help="dynamic workload: iteration cap of append's candidate search")
+    ap.add_argument("--append-remote-cands", type=int, default=0,
+                    help="dynamic workload, remote mode 0: nearest candidates whose remote entries are looked at (0: all)")
+    ap.add_argument("--append-visited-cap", type=int, default=1400,
+                    help="dynamic workload: visited capacity of append's candidate search (seeds + max_iter * width * degree must fit, "
+                         "or searches stop early; a smaller table leaves room for more resident wavefronts)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy five times (reference dispatch for rocprofv3 --pmc byte counters)")
     args = ap.parse_args()
@@ -370,12 +375,13 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
         from oracle import oracle as O
         ora = O.Index(X, attrs, cfg.buckets, n_cap=ix.sizes()["n_slots"], metric=cfg.metric)
         ora.k_local, ora.k_remote, ora.A = cfg.k_local, cfg.k_remote, ix.get_graph()
-        ora.params.update(alpha=args.alpha, append_beam=args.append_beam, remote_mode=args.remote_mode,
+        ora.params.update(alpha=args.alpha, append_beam=args.append_beam, remote_mode=args.remote_mode, append_remote_cands=args.append_remote_cands,
                           remote_window=args.remote_window, n_proximal=None if args.n_proximal < 0 else args.n_proximal)
         assert ora.n_cap == ix.sizes()["n_slots"]
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     ix.set_param("alpha", args.alpha)
     ix.set_param("append_beam", args.append_beam)
+    ix.set_param("append_remote_cands", args.append_remote_cands)
     DYN_GRID = [(32, 96, 2, 1400, 20), (36, 96, 2, 1400, 21), (40, 96, 2, 1400, 24), (40, 128, 3, 1400, 18), (48, 64, 2, 1400, 0),
                 (48, 96, 2, 1400, 28), (48, 128, 4, 1400, 0), (48, 128, 3, 1400, 20), (56, 128, 3, 1400, 24), (64, 64, 2, 1400, 0),
                 (64, 128, 4, 1400, 0), (64, 128, 3, 1400, 28), (64, 256, 4, 4000, 0), (96, 128, 3, 2800, 36), (96, 256, 4, 4000, 0),
@@ -411,20 +417,25 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
     at_recall = {"before_appends": qps_at_recall(ix, q0, lo0d, hi0d, GT.exact_filtered_knn(Xd, ad, q0, lo0d, hi0d, k, cfg.metric), ids0, dist0)}
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     rounds = []
+    app_stats = []
     allX, alla = Xd, ad
     for r in range(cfg.append_rounds):
         nx = torch.from_numpy(W.append_vectors(cfg, r)).to(dev)
         na = torch.from_numpy(W.append_attributes(cfg, r)).to(dev)
         # append's candidate search: beam append_beam, its own seeds and width
-        ix.set_param("visited_cap", 2800); ix.set_param("n_seeds", args.append_seeds); ix.set_param("search_width", args.append_width)
+        ix.set_param("visited_cap", args.append_visited_cap); ix.set_param("n_seeds", args.append_seeds); ix.set_param("search_width", args.append_width)
         ix.set_param("max_iter", args.append_max_iter)
+        ix.set_param("profile", 1)
         torch.cuda.synchronize()
         t = time.perf_counter()
         ix.append_batch(nx, na)
         torch.cuda.synchronize()
         t_app = time.perf_counter() - t
+        st = ix.get_append_stats(timing=True)
+        ix.set_param("profile", 0)
+        app_stats.append(st)
         if ora is not None:
-            ora.params.update(visited_cap=2800, n_seeds=args.append_seeds, search_width=args.append_width, max_iter=args.append_max_iter)
+            ora.params.update(visited_cap=args.append_visited_cap, n_seeds=args.append_seeds, search_width=args.append_width, max_iter=args.append_max_iter)
             t = time.perf_counter()
             ora.append(nx.cpu().numpy(), na.cpu().numpy(), threads=O.max_threads())
             t_ora = time.perf_counter() - t
@@ -456,7 +467,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
             log(f"[bench] parity after round {r + 1}: {parity_rounds[-1]}")
         new_frac = float((ids.cpu().numpy().view(np.uint32) >= cfg.n).mean())
         rounds.append({"round": r + 1, "objects": ix.sizes()["n"], "append_vectors_per_s": round(cfg.append_batch / t_app, 1),
-                       "append_ms": round(t_app * 1e3, 2), "search_qps": round(len(q) / t_s, 1),
+                       "append_ms": round(t_app * 1e3, 2), "phase_ms": [round(x, 3) for x in st["ms"]], "search_qps": round(len(q) / t_s, 1),
                        "recall_at_10": round(GT.recall(ids, gt), 4), "results_from_appended": round(new_frac, 4)})
         log(f"[bench] round {r + 1}: {rounds[-1]}")
     at_recall["after_appends"] = qps_at_recall(ix, q, lod, hid, gt, ids, dist)
@@ -481,16 +492,44 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
     at_recall["bulk_rebuilt"] = qps_at_recall(ref, q, lod, hid, gt, ids, dist)
     ref.close()
     log(f"[bench] bulk-rebuilt reference on the final {ix.sizes()['n']} objects: {rebuilt}")
+    # ---- what an append must move (algorithmic bytes from the call's own work counters), per phase
+    row, K, m = cfg.dim * 4, cfg.k_local + cfg.k_remote, cfg.append_batch
+    n_search = 2 if args.remote_mode == 1 else 1
+
+    def phase_bytes(c):
+        nreq = c["requests_local"] + c["requests_remote"]
+        search = c["search_evals"] * row + c["search_parents"] * K * 4 + n_search * m * row
+        forward = (c["candidates_scanned"] + c["remote_rows_evaluated"]) * row + n_search * m * args.append_beam * 8 \
+            + (m * args.append_beam * cfg.k_remote * 4 if args.remote_mode == 0 else m * args.append_beam * 4) + m * K * (4 + 20)
+        write_sort = 2 * m * row + 2 * 2 * nreq * 12
+        rewire = c["groups_local"] * cfg.k_local * (row + 4) + c["groups_remote"] * cfg.k_remote * (row + 4) \
+            + c["requests_local"] * (row + K * 4 + 16) + c["requests_remote"] * 16 \
+            + (c["applied_local"] * cfg.k_local + c["applied_remote"] * cfg.k_remote) * 4
+        return [search, forward, write_sort, rewire]
+    pb = np.array([phase_bytes(c) for c in app_stats], dtype=np.float64)
+    pms = np.array([c["ms"] for c in app_stats], dtype=np.float64)
+    mean_call_ms = float(np.mean([x["append_ms"] for x in rounds]))
+    names = ["candidate search (k_select_seed + k_beam_search)", "forward selection (k_forward)",
+             "new rows + request sorting (k_write_new, radix sorts)", "reverse rewiring (k_rewire)"]
+    roofline = {"bound": "hbm", "kernel": "grab_append_batch: all kernels of one call", "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "achieved": round(float(pb.sum(1).mean()) / (mean_call_ms * 1e-3) / 1e9, 1),
+                "frac": round(float(pb.sum(1).mean()) / (mean_call_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                "frac_kind": "algorithmic bytes of the call (from its work counters) / wall time of the call / HBM peak",
+                "traffic": None, "bytes_per_call": float(pb.sum(1).mean()),
+                "phases": [{"phase": names[i], "ms": round(float(pms[:, i].mean()), 3), "bytes": float(pb[:, i].mean()),
+                            "gbs": round(float(pb[:, i].mean()) / (float(pms[:, i].mean()) * 1e-3) / 1e9, 1),
+                            "frac": round(float(pb[:, i].mean()) / (float(pms[:, i].mean()) * 1e-3) / 1e9 / PEAK_HBM_GBS, 4)} for i in range(4)],
+                "work_counters_last_call": {k_: v for k_, v in app_stats[-1].items() if k_ != "ms"}}
     out = {"metric": "dynamic workload: append vectors/s and filtered queries/s per round (1M -> 2M x 128 fp32, 10% range)",
            "value": round(float(np.mean([x["append_vectors_per_s"] for x in rounds])), 1), "unit": "appended vectors/s",
            "n_gpus": 1, "higher_is_better": True, "dtype": "f32", "data": "synthetic", "vs_baseline": None,
            "config": {"workload": f"{cfg.name}: {cfg.n} x {cfg.dim} fp32 growing by {cfg.append_rounds} x {cfg.append_batch}, "
                                   f"{cfg.buckets} buckets, degree {cfg.k_local}+{cfg.k_remote}, 10000 queries per round, "
                                   f"{args.selectivity:.0%} range, k={k}",
-                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width, "append_max_iter": args.append_max_iter,
+                      "beam": beam, "n_seeds": S, "search_width": w, "visited_cap": vc, "append_beam": args.append_beam, "append_seeds": args.append_seeds, "append_width": args.append_width, "append_max_iter": args.append_max_iter, "append_visited_cap": args.append_visited_cap, "append_remote_cands": args.append_remote_cands,
                       "alpha": args.alpha, "remote_mode": args.remote_mode, "remote_window": args.remote_window,
                       "n_proximal": args.n_proximal, "rewire_from_targets": args.rewire_from_targets, "graph": "library"},
-           "parity_vs_oracle": parity_rounds or None,
+           "roofline": roofline, "parity_vs_oracle": parity_rounds or None,
            "mean_search_qps": round(float(np.mean([x["search_qps"] for x in rounds])), 1), "rounds": rounds,
            "search_rate_at_recall_0.95": at_recall, "strong_components_final": scc, "orphans_final": n_orphans, "bulk_rebuilt_reference_final": rebuilt, "build": build}
     ix.close()

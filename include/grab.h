@@ -76,6 +76,9 @@ typedef enum {
                                 into proximal and global picks                              */
     GRAB_P_N_PROXIMAL = 9,   /* mode 1: remote positions kept for proximal candidates, 0..64;
                                 -1 (default) = ceil(k_remote / 2)                          */
+    GRAB_P_APPEND_REMOTE_CANDS = 11, /* grab_append_batch under mode 0: the remote part of a new row
+                                is chosen among the remote entries of its nearest this-many local
+                                candidates; 0 (default) = all GRAB_P_APPEND_BEAM of them           */
     GRAB_P_REMOTE_WINDOW = 10 /* mode 1: a candidate is proximal iff its attribute differs from the
                                 node's by at most this fraction of the attribute span of the index
                                 (largest minus smallest stored attribute, as int32 keys), rounded
@@ -256,6 +259,17 @@ grab_status grab_get_counters(grab_index *ix, uint32_t *per_query, int64_t nq);
  * in which the queries run; ms[1] beam-search kernel; in milliseconds (host array).  Waits for the search to
  * finish.  GRAB_ESTATE if profiling was off. */
 grab_status grab_get_timing(grab_index *ix, float ms[2]);
+
+/* Work counters and phase durations of the most recent grab_append_batch (either may be NULL).
+ * counts[12] (host) = {reverse requests made for local edges, for remote edges; (target, kind)
+ * groups of requests for local parts, for remote parts; requests that rewrote an entry, local,
+ * remote; candidates examined by the Eq. 2 scans of the forward selection; vector rows evaluated
+ * for the remote parts of the new rows (reading by target bucket only); local requests that passed
+ * the biased Eq. 2 test; distance evaluations, and expanded parents, of the candidate searches;
+ * 0}.  ms[4] (host, needs GRAB_P_PROFILE = 1 before the call) = candidate search(es), forward
+ * selection, new rows + request sorting, reverse rewiring, in milliseconds, from HIP events on
+ * the index's stream.  GRAB_ESTATE if no insertion has run, or ms is asked for without profiling. */
+grab_status grab_get_append_stats(grab_index *ix, uint64_t counts[12], float ms[4]);
 
 /* ---- float attributes ------------------------------------------------------------------------
  * The filter of Section 3 is over a scalar attribute, and Section 5.1 draws it as a float in

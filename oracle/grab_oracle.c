@@ -470,6 +470,8 @@ int oracle_max_threads(void) {
  *     j-th remote entry of every node of a bucket points into the same target bucket, so the new
  *     row keeps that structure: it is the online form of the remote wiring (Section 4.3 pass 2,
  *     "proximal" and "global" remote edges), found through graph locality instead of a scan.
+ *     `remote_cands` > 0 looks at the remote entries of the nearest remote_cands candidates only
+ *     (the nearest candidates' remote neighbours are the ones near q; 0 = all candidates).
  *     (Section 4.4 has the candidate search also look outside the target bucket; nearest-anywhere candidates
  *     gave new nodes remote edges into arbitrary far buckets, which a range filter rejects, and
  *     recall of the dynamic workload decayed with every batch.)
@@ -579,11 +581,12 @@ static int request_cmp(const void *a, const void *b) {
 /* Eq. 2 scan over `nc` ordered candidates (slot, dist to q); writes up to `cap` slots to row,
  * returns how many were kept by the rule (the rest of the row is back-fill, then EMPTY) */
 static int forward_select(const oracle_index *ix, const uint32_t *cs, const float *cd, int nc, int cap,
-                          uint32_t *row) {
+                          uint32_t *row, uint64_t *scanned) {
     int kept = 0, nrej = 0;
     uint32_t *rej = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)(nc > 0 ? nc : 1));
     for (int t = 0; t < nc && kept < cap; ++t) {
         int ok = 1;
+        ++*scanned;
         for (int j = 0; j < kept && ok; ++j) {
             float dcn = oracle_distance(ix->X + (size_t)cs[t] * ix->dim, ix->X + (size_t)row[j] * ix->dim, ix->dim, ix->metric);
             if (!(cd[t] < dcn)) ok = 0;
@@ -597,12 +600,17 @@ static int forward_select(const oracle_index *ix, const uint32_t *cs, const floa
     return kept;
 }
 
-/* Returns 0, or 3 when a bucket is out of tail room (nothing written).  `pr` holds the search
+/* stats (may be NULL) receives the work counters of the call: 0 requests made for local edges,
+ * 1 for remote edges, 2 (target, kind) groups for local parts, 3 for remote parts, 4 requests that
+ * rewrote an entry, local, 5 remote, 6 candidates examined by the Eq. 2 scans, 7 rows evaluated
+ * for the remote parts of new rows (mode 0), 8 local requests that passed the biased test,
+ * 9 distance evaluations and 10 expanded parents of the candidate searches, 11 unused.
+ * Returns 0, or 3 when a bucket is out of tail room (nothing written).  `pr` holds the search
  * parameters already resolved for beam = append_beam.  id2slot has room for n_prev + m entries.
  * kept_out (may be NULL): per new node {entries kept by Eq. 2 in the local part, in the remote part}. */
 int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_t append_beam,
                   const float *vecs, const int32_t *attrs, int64_t m, int64_t n_prev, uint32_t *id2slot,
-                  int32_t *kept_out, int32_t threads, const remote_rule *rr) {
+                  int32_t *kept_out, int32_t threads, const remote_rule *rr, uint64_t *stats, int32_t remote_cands) {
     const int B = ix->n_buckets, kl = ix->k_local, kr = ix->k_remote, K = kl + kr, dim = ix->dim;
     const int mode = rr ? rr->mode : 0;
     if (mode != 0 && (mode != 1 || rr->n_proximal < 0 || rr->n_proximal > kr || rr->window < 0)) return 1;
@@ -635,6 +643,7 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             free(bucket); free(slot); free(count);
             return 3;
         }
+    uint64_t st[12] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
     /* 3 + 4 on the snapshot */
     uint32_t *rows = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)m * K);
     float *rowd = (float *)malloc(sizeof(float) * (size_t)m * K);   /* dist(q, row entry) */
@@ -649,6 +658,8 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         float *cd = (float *)malloc(sizeof(float) * (size_t)append_beam);
         uint32_t *gs = (uint32_t *)malloc(sizeof(uint32_t) * (size_t)append_beam);
         float *gd = (float *)malloc(sizeof(float) * (size_t)append_beam);
+        uint64_t my_scanned = 0, my_rows = 0, my_evals = 0, my_parents = 0;
+        uint32_t ctr[8];
 #ifdef _OPENMP
 #pragma omp for schedule(static)
 #endif
@@ -657,10 +668,11 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             uint32_t *row = rows + (size_t)i * K;
             int kept[2] = {0, 0};
             /* local part: Eq. 2 selection over the candidates found in the target bucket */
-            int64_t nQ = search_one(ix, pr, q, 0, 0, bucket[i], append_beam, sc, NULL);
+            int64_t nQ = search_one(ix, pr, q, 0, 0, bucket[i], append_beam, sc, ctr);
+            my_evals += ctr[C_EVALS]; my_parents += ctr[C_PARENTS];
             int nc = 0;
             for (int64_t j = 0; j < nQ; ++j) { cs[nc] = sc->Q[j].slot; cd[nc] = sc->Q[j].dist; nc++; }
-            kept[0] = forward_select(ix, cs, cd, nc, kl, row);
+            kept[0] = forward_select(ix, cs, cd, nc, kl, row, &my_scanned);
             for (int j = 0; j < kl; ++j) {
                 float d = 0.0f;
                 if (row[j] != EMPTY)
@@ -671,11 +683,15 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             if (mode == 0) {
             /* remote part: entry j is the nearest to q among the j-th remote entries of its local
              * candidates (they all lie in the j-th target bucket when the graph was built that way) */
+            const int nrc = remote_cands > 0 && remote_cands < nc ? remote_cands : nc;   /* the nearest candidates only */
             for (int j = 0; j < kr; ++j) {
                 uint32_t best = EMPTY, best_img = 0; float best_d = 0.0f;
-                for (int t = 0; t < nc; ++t) {
+                for (int t = 0; t < nrc; ++t) {
                     uint32_t r = ix->A[(size_t)cs[t] * K + kl + j];
                     if (r == EMPTY) continue;
+                    int seen = 0;       /* a row several candidates share is one evaluation */
+                    for (int x = 0; x < t && !seen; ++x) seen = ix->A[(size_t)cs[x] * K + kl + j] == r;
+                    my_rows += !seen;
                     float d = oracle_distance(q, ix->X + (size_t)r * dim, dim, ix->metric);
                     uint32_t im = dist_image(d);
                     if (best == EMPTY || im < best_img || (im == best_img && r < best)) { best = r; best_img = im; best_d = d; }
@@ -687,7 +703,8 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             }
             } else {
             /* 3', 4': global-scope candidates, proximal / global picks, redundant local edges elsewhere */
-            int64_t nG = search_one(ix, pr, q, 0, 0, -2 - bucket[i], append_beam, sc, NULL);
+            int64_t nG = search_one(ix, pr, q, 0, 0, -2 - bucket[i], append_beam, sc, ctr);
+            my_evals += ctr[C_EVALS]; my_parents += ctr[C_PARENTS];
             int ng = 0;
             for (int64_t j = 0; j < nG; ++j) { gs[ng] = sc->Q[j].slot; gd[ng] = sc->Q[j].dist; ng++; }
             select_remote(ix, attrs[i], gs, gd, ng, rr, row + kl, rowd + (size_t)i * K + kl);
@@ -708,6 +725,10 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
         }
         free(cs); free(cd); free(gs); free(gd);
         scratch_free(sc);
+#ifdef _OPENMP
+#pragma omp critical
+#endif
+        { st[6] += my_scanned; st[7] += my_rows; st[9] += my_evals; st[10] += my_parents; }
     }
     /* write the new nodes */
     int64_t nreq = 0;
@@ -725,6 +746,7 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             float d = rowd[(size_t)i * K + j];
             req[nreq].v = v; req[nreq].kind = rowk[(size_t)i * K + j]; req[nreq].img = dist_image(d);
             req[nreq].q = s; req[nreq].dist = d;
+            st[req[nreq].kind]++;
             nreq++;
         }
     }
@@ -734,11 +756,14 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
     const float a = alpha * alpha;
     int64_t ngroups = 0;
     int64_t *gstart = (int64_t *)malloc(sizeof(int64_t) * (size_t)(nreq + 1));
-    for (int64_t r = 0; r < nreq; ++r)
+    for (int64_t r = 0; r < nreq; ++r) {
         if (r == 0 || req[r].v != req[r - 1].v) gstart[ngroups++] = r;
+        if (r == 0 || req[r].v != req[r - 1].v || req[r].kind != req[r - 1].kind) st[2 + req[r].kind]++;
+    }
     gstart[ngroups] = nreq;
+    uint64_t applied_l = 0, applied_r = 0, passed = 0;
 #ifdef _OPENMP
-#pragma omp parallel for schedule(dynamic, 64) num_threads(threads)
+#pragma omp parallel for schedule(dynamic, 64) num_threads(threads) reduction(+ : applied_l, applied_r, passed)
 #endif
     for (int64_t g = 0; g < ngroups; ++g)
     for (int64_t r = gstart[g]; r < gstart[g + 1]; ++r) {
@@ -759,9 +784,9 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             }
             if (far >= 0) {
                 float dfar = oracle_distance(xv, ix->X + (size_t)R[far] * dim, dim, ix->metric);
-                if (lhs < bias_base(ix, dfar)) R[far] = req[r].q;
+                if (lhs < bias_base(ix, dfar)) { R[far] = req[r].q; applied_r++; }
             } else if (empty_at >= 0) {
-                R[empty_at] = req[r].q;
+                R[empty_at] = req[r].q; applied_r++;
             }
             continue;
         }
@@ -774,14 +799,14 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             int take = -1, far = -1; uint32_t far_img = 0;
             for (int j = j0; j < j1 && take < 0; ++j)
                 if (R[j] == EMPTY || bucket_of_slot(ix, R[j]) == bv) take = j;
-            if (take >= 0) { R[take] = req[r].q; continue; }
+            if (take >= 0) { R[take] = req[r].q; applied_r++; continue; }
             for (int j = j0; j < j1; ++j) {
                 uint32_t im = dist_image(oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric));
                 if (far < 0 || im > far_img || (im == far_img && R[j] > R[far])) { far = j; far_img = im; }
             }
             if (far >= 0) {
                 float dfar = oracle_distance(xv, ix->X + (size_t)R[far] * dim, dim, ix->metric);
-                if (lhs < bias_base(ix, dfar)) R[far] = req[r].q;
+                if (lhs < bias_base(ix, dfar)) { R[far] = req[r].q; applied_r++; }
             }
             continue;
         }
@@ -792,7 +817,8 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             if (!(lhs < bias_base(ix, dqn))) pass = 0;
         }
         if (!pass) continue;
-        if (empty_at >= 0) { R[empty_at] = req[r].q; continue; }
+        passed++;
+        if (empty_at >= 0) { R[empty_at] = req[r].q; applied_l++; continue; }
         /* the newcomer may only take the place of a neighbour it points to itself, so that the
          * pathway v -> n survives as v -> q -> n; among those the one farthest from v (ties: smaller slot) */
         int victim = -1; uint32_t victim_img = 0;
@@ -804,9 +830,11 @@ int oracle_append(oracle_index *ix, const oracle_params *pr, float alpha, int32_
             uint32_t im = dist_image(oracle_distance(xv, ix->X + (size_t)R[j] * dim, dim, ix->metric));
             if (victim < 0 || im > victim_img || (im == victim_img && R[j] < R[victim])) { victim = j; victim_img = im; }
         }
-        if (victim >= 0) R[victim] = req[r].q;
+        if (victim >= 0) { R[victim] = req[r].q; applied_l++; }
     }
     free(gstart);
+    st[4] = applied_l; st[5] = applied_r; st[8] = passed;
+    if (stats) memcpy(stats, st, sizeof(st));
     /* 6 */
     for (int64_t i = 0; i < m; ++i) {
         int32_t *t = ix->table + 6 * bucket[i];

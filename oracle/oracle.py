@@ -42,6 +42,10 @@ class _Params(ctypes.Structure):
                 ("seed_salt", ctypes.c_uint32)]
 
 
+APPEND_STATS = ["requests_local", "requests_remote", "groups_local", "groups_remote", "applied_local", "applied_remote",
+                "candidates_scanned", "remote_rows_evaluated", "local_requests_passed", "search_evals", "search_parents"]
+
+
 class _RemoteRule(ctypes.Structure):
     _fields_ = [("mode", ctypes.c_int32), ("n_proximal", ctypes.c_int32), ("window", ctypes.c_int64)]
 
@@ -157,7 +161,7 @@ class Index:
         # (n_proximal None = ceil(k_remote / 2); remote_window = fraction of the attribute span)
         self.params = dict(search_width=1, max_iter=None, n_seeds=None, visited_cap=2800,
                            seed_salt=0, alpha=0.6, append_beam=64, remote_mode=0, n_proximal=None,
-                           remote_window=0.2)
+                           remote_window=0.2, append_remote_cands=0)
 
     # -- M_I2B: bucket of every external id
     def bucket_of_ids(self) -> np.ndarray:
@@ -321,12 +325,15 @@ class Index:
         if self.n + m > len(self.id2slot):
             raise OverflowError("more objects than slots")
         kept = np.zeros((m, 2), dtype=np.int32)
+        stats = np.zeros(12, dtype=np.uint64)
         ix, pr, rr = self._c_index(), self._resolved_append_params(), self._c_remote_rule()
         f = _load().oracle_append
         f.restype = ctypes.c_int
         rc = f(ctypes.byref(ix), ctypes.byref(pr), ctypes.c_float(self.params["alpha"]),
                ctypes.c_int32(self.params["append_beam"]), _ptr(vectors), _ptr(attrs), ctypes.c_int64(m),
-               ctypes.c_int64(self.n), _ptr(self.id2slot), _ptr(kept), ctypes.c_int32(threads), ctypes.byref(rr))
+               ctypes.c_int64(self.n), _ptr(self.id2slot), _ptr(kept), ctypes.c_int32(threads), ctypes.byref(rr),
+               _ptr(stats), ctypes.c_int32(self.params["append_remote_cands"]))
+        self.last_append_stats = dict(zip(APPEND_STATS, (int(x) for x in stats)))
         if rc == 3:
             raise OverflowError("a bucket is out of tail room")
         if rc:

@@ -19,15 +19,16 @@ STATUS_NAMES = {OK: "GRAB_OK", EINVAL: "GRAB_EINVAL", ESTATE: "GRAB_ESTATE", EFU
                 ENOMEM: "GRAB_ENOMEM", EHIP: "GRAB_EHIP"}
 L2SQ, IP = 0, 1
 P_SEARCH_WIDTH, P_MAX_ITER, P_N_SEEDS, P_VISITED_CAP, P_SEED_SALT, P_ALPHA, P_APPEND_BEAM, P_PROFILE, P_REMOTE_MODE, \
-    P_N_PROXIMAL, P_REMOTE_WINDOW = range(11)
+    P_N_PROXIMAL, P_REMOTE_WINDOW, P_APPEND_REMOTE_CANDS = range(12)
 PARAMS = dict(search_width=P_SEARCH_WIDTH, max_iter=P_MAX_ITER, n_seeds=P_N_SEEDS, visited_cap=P_VISITED_CAP,
               seed_salt=P_SEED_SALT, alpha=P_ALPHA, append_beam=P_APPEND_BEAM, profile=P_PROFILE,
-              remote_mode=P_REMOTE_MODE, n_proximal=P_N_PROXIMAL, remote_window=P_REMOTE_WINDOW)
+              remote_mode=P_REMOTE_MODE, n_proximal=P_N_PROXIMAL, remote_window=P_REMOTE_WINDOW,
+              append_remote_cands=P_APPEND_REMOTE_CANDS)
 EMPTY = 0xFFFFFFFF
 
 EXPORTS = ["grab_create", "grab_destroy", "grab_last_error", "grab_build_buckets", "grab_load_graph",
            "grab_build_graph", "grab_build_remote", "grab_search_range", "grab_search_range_noalloc", "grab_append_batch", "grab_set_param", "grab_get_sizes", "grab_get_layout",
-           "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing",
+           "grab_get_graph", "grab_get_rows", "grab_select_range", "grab_get_counters", "grab_get_timing", "grab_get_append_stats",
            "grab_probe_gather", "grab_attr_image", "grab_attr_value", "grab_build_buckets_f32", "grab_search_range_f32",
            "grab_append_batch_f32"]
 
@@ -76,6 +77,7 @@ def load_library() -> ctypes.CDLL:
     lib.grab_select_range.argtypes = [vp, vp, vp, i64, i32, vp, vp]
     lib.grab_get_counters.argtypes = [vp, vp, i64]
     lib.grab_get_timing.argtypes = [vp, vp]
+    lib.grab_get_append_stats.argtypes = [vp, vp, vp]
     lib.grab_probe_gather.argtypes = [vp, i64, i32, vp, vp]
     lib.grab_attr_image.argtypes = [ctypes.c_float]
     lib.grab_attr_value.argtypes = [i32]
@@ -271,6 +273,20 @@ class Index:
         nbytes = np.zeros(1, dtype=np.float64)
         self._check(self._lib.grab_probe_gather(self._h, waves, batches, ms.ctypes.data, nbytes.ctypes.data))
         return float(ms[0]), float(nbytes[0])
+
+    APPEND_STATS = ["requests_local", "requests_remote", "groups_local", "groups_remote", "applied_local", "applied_remote",
+                    "candidates_scanned", "remote_rows_evaluated", "local_requests_passed", "search_evals", "search_parents"]
+
+    def get_append_stats(self, timing: bool = False):
+        """Work counters of the last append_batch as a dict; with timing=True also `ms` = (search,
+        forward selection, new rows + sorting, rewiring); needs set_param("profile", 1)."""
+        counts = np.zeros(12, dtype=np.uint64)
+        ms = np.zeros(4, dtype=np.float32)
+        self._check(self._lib.grab_get_append_stats(self._h, counts.ctypes.data, ms.ctypes.data if timing else None))
+        out = dict(zip(self.APPEND_STATS, (int(x) for x in counts)))
+        if timing:
+            out["ms"] = [float(x) for x in ms]
+        return out
 
     def get_timing(self):
         """(select_ms, beam_ms) of the last search; needs set_param("profile", 1) before it."""

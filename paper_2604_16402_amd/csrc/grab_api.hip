@@ -137,10 +137,12 @@ void grab_destroy(grab_index *ix) {
     DevBuf *bufs[] = {&ix->plans, &ix->seeds, &ix->counters, &ix->stage_q, &ix->stage_lo, &ix->stage_hi,
                       &ix->stage_ids, &ix->stage_dist, &ix->stage_misc, &ix->flags, &ix->stage_fa, &ix->stage_flo,
                       &ix->stage_fhi, &ix->conv_a, &ix->conv_lo, &ix->conv_hi, &ix->attr_flag, &ix->q_bin, &ix->q_rank,
-                      &ix->q_order, &ix->bin_count};
+                      &ix->q_order, &ix->bin_count, &ix->app_stats};
     for (DevBuf *b : bufs) free_buf(*b);
     for (DevBuf &b : ix->app) free_buf(b);
     for (hipEvent_t e : ix->ev)
+        if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : ix->app_ev)
         if (e) (void)hipEventDestroy(e);
     delete ix;
 }
@@ -174,9 +176,12 @@ grab_status grab_set_param(grab_index *ix, int32_t which, double value) {
             p.append_beam = (int32_t)value; return GRAB_OK;
         case GRAB_P_PROFILE:
             if (value != 0.0 && value != 1.0) return grab_fail(ix, GRAB_EINVAL, "profile must be 0 or 1");
-            if (value == 1.0)
+            if (value == 1.0) {
                 for (hipEvent_t &e : ix->ev)
                     if (!e) GRAB_HIP(ix, hipEventCreate(&e));
+                for (hipEvent_t &e : ix->app_ev)
+                    if (!e) GRAB_HIP(ix, hipEventCreate(&e));
+            }
             ix->profile = value == 1.0; return GRAB_OK;
         case GRAB_P_REMOTE_MODE:
             if (value != 0.0 && value != 1.0) return grab_fail(ix, GRAB_EINVAL, "remote_mode must be 0 or 1");
@@ -184,6 +189,9 @@ grab_status grab_set_param(grab_index *ix, int32_t which, double value) {
         case GRAB_P_N_PROXIMAL:
             if (value < -1 || value > 64 || value != (double)(int32_t)value) return grab_fail(ix, GRAB_EINVAL, "n_proximal must be -1..64");
             p.n_proximal = (int32_t)value; return GRAB_OK;
+        case GRAB_P_APPEND_REMOTE_CANDS:
+            if (value < 0 || value > GRAB_MAX_BEAM || value != (double)(int32_t)value) return grab_fail(ix, GRAB_EINVAL, "append_remote_cands must be 0..512");
+            p.append_remote_cands = (int32_t)value; return GRAB_OK;
         case GRAB_P_REMOTE_WINDOW:
             if (!(value >= 0.0 && value <= 1.0)) return grab_fail(ix, GRAB_EINVAL, "remote_window must be in [0, 1]");
             p.remote_window = value; return GRAB_OK;
@@ -454,6 +462,18 @@ grab_status grab_get_timing(grab_index *ix, float ms[2]) {
     GRAB_HIP(ix, hipEventSynchronize(ix->ev[2]));
     GRAB_HIP(ix, hipEventElapsedTime(&ms[0], ix->ev[0], ix->ev[1]));
     GRAB_HIP(ix, hipEventElapsedTime(&ms[1], ix->ev[1], ix->ev[2]));
+    return GRAB_OK;
+}
+
+grab_status grab_get_append_stats(grab_index *ix, uint64_t counts[12], float ms[4]) {
+    if (!ix) return GRAB_EINVAL;
+    if (!ix->app_has_stats) return grab_fail(ix, GRAB_ESTATE, "no insertion has run on this index");
+    GRAB_HIP(ix, hipStreamSynchronize(ix->stream));
+    if (counts) GRAB_HIP(ix, hipMemcpy(counts, ix->app_stats.p, 12 * sizeof(uint64_t), hipMemcpyDefault));
+    if (ms) {
+        if (!ix->app_timed) return grab_fail(ix, GRAB_ESTATE, "the last insertion was not profiled");
+        for (int i = 0; i < 4; ++i) GRAB_HIP(ix, hipEventElapsedTime(&ms[i], ix->app_ev[i], ix->app_ev[i + 1]));
+    }
     return GRAB_OK;
 }
 

@@ -165,6 +165,24 @@ __device__ __forceinline__ void group_vs_rows(const float *__restrict__ X, const
     }
 }
 
+// Work counters of one insertion call (device, 64-bit), reported by grab_get_append_stats
+enum { ST_REQ_LOCAL = 0, ST_REQ_REMOTE, ST_GROUPS_LOCAL, ST_GROUPS_REMOTE, ST_APPLIED_LOCAL, ST_APPLIED_REMOTE, ST_SCANNED,
+       ST_REMOTE_ROWS, ST_LOCAL_PASS, ST_SEARCH_EVALS, ST_SEARCH_PARENTS, ST_SPARE, ST_N };
+
+__global__ void k_zero_stats(u64 *__restrict__ stats) {
+    if (threadIdx.x < ST_N) stats[threadIdx.x] = 0;
+}
+
+// distance evaluations and expanded parents of a candidate search, summed over its queries
+__global__ void k_sum_search_counters(const uint32_t *__restrict__ counters, int64_t nq, u64 *__restrict__ stats) {
+    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    u64 ev = 0, pa = 0;
+    if (i < nq) { pa = counters[i * 8 + 1]; ev = counters[i * 8 + 2]; }
+#pragma unroll
+    for (int m = 32; m > 0; m >>= 1) { ev += shfl_xor64(ev, m); pa += shfl_xor64(pa, m); }
+    if ((threadIdx.x & 63) == 0) { atomicAdd(&stats[ST_SEARCH_EVALS], ev); atomicAdd(&stats[ST_SEARCH_PARENTS], pa); }
+}
+
 struct ForwardArgs {
     const float *X;
     uint32_t *A;
@@ -178,12 +196,13 @@ struct ForwardArgs {
     int64_t m;
     int32_t beam, kl, kr, metric;
     // proximal / global reading of the remote part (mode 1)
-    int32_t mode, kp;
+    int32_t mode, kp, remote_cands;
     int64_t window;
     const uint32_t *gcand_s;    // global-scope candidate search results: slots [m][beam]
     const float *gcand_d;
     const int32_t *attr;        // attributes of the index, by slot
     const int32_t *new_attr;    // attributes of the new objects, batch order
+    uint32_t *node_out;         // [m][2]: candidates examined by the Eq. 2 scan, rows evaluated for the remote part
 };
 
 // Forward edges of one new node per wavefront (Section 4.4 step 2).  Local part (Eq. 2): scan the
@@ -234,6 +253,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     }
     __syncthreads();
     int nk = 0, nrej = 0;
+    unsigned scanned = 0, remote_rows = 0;   // candidates examined by the Eq. 2 scan; rows evaluated for the remote part
     if constexpr (EvalShape<NCH>::QREG) {
         // eight candidates at a time, one per lane group: their rows are loaded together, each is
         // compared with every row kept so far and with the other seven, and the chunk is then
@@ -265,6 +285,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
                     else if (nrej < 64) { rej[nrej] = cs[t0 + g]; rejd[nrej] = dqc; }
                 }
                 if (ok) { ++nk; keptmask |= 1u << g; } else if (nrej < 64) ++nrej;
+                ++scanned;
             }
             __syncthreads();
         }
@@ -286,9 +307,13 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
                 else if (nrej < 64) { rej[nrej] = c; rejd[nrej] = dqc; }
             }
             if (ok) ++nk; else if (nrej < 64) ++nrej;
+            ++scanned;
             __syncthreads();
         }
     }
+    auto flush_stats = [&]() __attribute__((always_inline)) {
+        if (lane == 0) { a.node_out[2 * i] = scanned; a.node_out[2 * i + 1] = remote_rows; }
+    };
     for (int j = lane; j < a.kl; j += 64) {
         uint32_t v = GRAB_EMPTY;
         float d = 0.0f;
@@ -305,7 +330,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     // without a pick takes the nearest local candidate not yet in the row (a redundant local edge,
     // which makes no reverse request)
     if (a.mode == 1) {
-        if (a.kr == 0) return;
+        if (a.kr == 0) { flush_stats(); return; }
         __syncthreads();
         select_remote_wave(a.gcand_s + i * a.beam, a.gcand_d + i * a.beam, a.beam, a.attr, a.new_attr[i], a.window, a.kp,
                            a.kr, lane, pk, pkd);
@@ -342,6 +367,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
             a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
             a.reqd[r] = d;
         }
+        flush_stats();
         return;
     }
     // ---- remote part, by target bucket
@@ -355,9 +381,10 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         for (int x = lane; x < uniq_words; x += 64) uniq[x] = GRAB_EMPTY;
         __syncthreads();
         int nr = 0;
-        for (int c0 = 0; c0 < nc; c0 += 64) {
+        const int nrc = a.remote_cands > 0 && a.remote_cands < nc ? a.remote_cands : nc;   // the nearest candidates only
+        for (int c0 = 0; c0 < nrc; c0 += 64) {
             const int t = c0 + lane;
-            uint32_t r = t < nc ? a.A[(size_t)cs[t] * K + a.kl + j] : GRAB_EMPTY;
+            uint32_t r = t < nrc ? a.A[(size_t)cs[t] * K + a.kl + j] : GRAB_EMPTY;
             bool ok = false;
             if (r != GRAB_EMPTY) {
                 uint32_t h = (uint32_t)(((u64)(r * 0x9E3779B1u) * (u64)uniq_words) >> 32);
@@ -373,6 +400,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
             nr += __popcll(m);
         }
         __syncthreads();
+        remote_rows += (unsigned)nr;
         u64 best = ~0ull;
         if (nr > 0) {
             eval_rows<NCH>(a.X, qreg, qlds, rs, nr, lane, a.metric, rd);
@@ -399,6 +427,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         }
         __syncthreads();
     }
+    flush_stats();
 }
 
 struct RewireArgs {
@@ -416,6 +445,7 @@ struct RewireArgs {
     int32_t mode, kp;
     int64_t window;
     const int32_t *attr;
+    uint32_t *grp_out;      // by sorted position of a group's first request: requests applied | passed << 16
 };
 
 __device__ __forceinline__ int bucket_of_slot_dev(const int32_t *__restrict__ table, int32_t B, uint32_t slot) {
@@ -438,10 +468,16 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int D = NCH * 32;
     const int lane = threadIdx.x;
+    // one wavefront per sorted position; only the one on the first request of a group works.  (A
+    // wavefront that walks a stretch of positions and applies the groups starting in it one after
+    // another was slower, 8.7 ms against 6.6 ms per 100,000 objects: a group is a chain of
+    // dependent memory round trips, and many short-lived wavefronts overlap those chains better.)
     const int64_t p0 = blockIdx.x;
     const u64 key = a.key1s[p0];
     if (key == ~0ull) return;
     if (p0 > 0 && a.key1s[p0 - 1] == key) return;
+    unsigned st_applied = 0, st_pass = 0;
+    {
     const uint32_t v = (uint32_t)(key >> 1);
     const int kind = (int)(key & 1ull);
     const int K = a.kl + a.kr, off = kind ? a.kl : 0, len = kind ? a.kr : a.kl;
@@ -518,6 +554,7 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
             if (at >= 0) {
                 if (lane == at) { R[at] = q; Rl[at] = q; dq[at] = dvq; }
                 changed = true;
+                ++st_applied;
             }
             __syncthreads();
         }
@@ -539,6 +576,7 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
             const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
             const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < bias_base(dq[lane], a.metric));
             if (__ballot(blocked) == 0) {
+                ++st_pass;
                 const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
                 int at = -1;
                 if (empties) {
@@ -563,12 +601,51 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
                 if (at >= 0) {
                     if (lane == at) { R[at] = q; Rl[at] = q; dv[at] = dvq; }
                     changed = true;
+                    ++st_applied;
                 }
             }
             __syncthreads();
         }
     }
     if (changed && lane < len) a.A[(size_t)v * K + off + lane] = R[lane];
+    }
+    if (lane == 0) a.grp_out[p0] = st_applied | (st_pass << 16);
+}
+
+// Work counters of the call from what the kernels left behind: requests and groups by kind from
+// the sorted keys, applied / passed requests from the group heads, scan lengths from the new nodes
+__global__ __launch_bounds__(TPB) void k_reduce_stats(const u64 *__restrict__ key1s, const uint32_t *__restrict__ grp_out, int64_t nreq,
+                                                      const uint32_t *__restrict__ node_out, int64_t m, u64 *__restrict__ stats) {
+    __shared__ u64 acc[ST_N];
+    if (threadIdx.x < ST_N) acc[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t p = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    u64 v[ST_N];
+#pragma unroll
+    for (int x = 0; x < ST_N; ++x) v[x] = 0;
+    if (p < nreq) {
+        const u64 key = key1s[p];
+        if (key != ~0ull) {
+            const int kind = (int)(key & 1ull);
+            v[ST_REQ_LOCAL + kind] = 1;
+            if (p == 0 || key1s[p - 1] != key) {
+                const uint32_t g = grp_out[p];
+                v[ST_GROUPS_LOCAL + kind] = 1;
+                v[ST_APPLIED_LOCAL + kind] = g & 0xFFFFu;
+                v[ST_LOCAL_PASS] = g >> 16;
+            }
+        }
+    }
+    if (p < m) { v[ST_SCANNED] = node_out[2 * p]; v[ST_REMOTE_ROWS] = node_out[2 * p + 1]; }
+#pragma unroll
+    for (int x = 0; x < ST_SEARCH_EVALS; ++x) {
+        u64 t = v[x];
+#pragma unroll
+        for (int sft = 32; sft > 0; sft >>= 1) t += shfl_xor64(t, sft);
+        if ((threadIdx.x & 63) == 0 && t) atomicAdd(&acc[x], t);
+    }
+    __syncthreads();
+    if (threadIdx.x < ST_SEARCH_EVALS && acc[threadIdx.x]) atomicAdd(&stats[threadIdx.x], acc[threadIdx.x]);
 }
 
 template <int NCH>
@@ -586,6 +663,7 @@ grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireAr
 }
 
 grab_status launch_append(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
+    if (!(phase == 0 ? f.node_out : r.grp_out)) return grab_fail(ix, GRAB_EINVAL, "insertion kernels need their counter arrays");
     switch (ix->dim / 32) {
 #define GRAB_CASE(N) case N: return launch_append_t<N>(ix, f, r, m, phase);
         GRAB_FOR_EACH_NCH(GRAB_CASE)
@@ -605,12 +683,14 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     const int64_t nreq = m * K;
     grab_status rc;
     // ---- arena
-    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_CG_S, A_CG_D, A_SCOPE, A_N };
+    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_CG_S, A_CG_D, A_SCOPE, A_NODE_OUT, A_GRP_OUT, A_N };
     size_t need[A_N];
     for (size_t &x : need) x = 0;
     need[A_BUCKET] = need[A_KEYS] = need[A_IDX] = need[A_KEYS_S] = need[A_IDX_S] = need[A_SLOT] = need[A_LO] = need[A_HI] = (size_t)m * 4;
     need[A_STARTS] = need[A_COUNTS] = (size_t)B * 4;
     need[A_CL_S] = need[A_CL_D] = (size_t)m * beam * 4;
+    need[A_NODE_OUT] = (size_t)m * 8;
+    need[A_GRP_OUT] = (size_t)nreq * 4;
     const RemoteRule rule = grab_remote_rule(ix, kr);
     if (rule.mode == 1) {
         need[A_CG_S] = need[A_CG_D] = (size_t)m * beam * 4;
@@ -627,7 +707,10 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     if ((int)ix->app.size() < A_N) ix->app.resize(A_N);
     for (int i = 0; i < A_N; ++i)
         if ((rc = grab_reserve(ix, ix->app[i], need[i])) != GRAB_OK) return rc;
+    if ((rc = grab_reserve(ix, ix->app_stats, ST_N * 8)) != GRAB_OK) return rc;
+    u64 *stats = (u64 *)ix->app_stats.p;
     auto P = [&](int i) { return ix->app[i].p; };
+    auto mark = [&](int i) { if (ix->profile) (void)hipEventRecord(ix->app_ev[i], st); };
     int32_t *bucket = (int32_t *)P(A_BUCKET), *starts = (int32_t *)P(A_STARTS), *counts = (int32_t *)P(A_COUNTS);
     uint32_t *slot = (uint32_t *)P(A_SLOT);
 
@@ -655,6 +738,8 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
                              ix->h_table[T_COLS * full + T_NTOT], ix->h_table[T_COLS * full + T_CAP], over);
     }
     // ---- 3: local candidate search against the pre-batch index (new rows are not visible yet)
+    k_zero_stats<<<1, 64, 0, st>>>(stats);
+    mark(0);
     k_fill_range<<<blocks_for(m), TPB, 0, st>>>((int32_t *)P(A_LO), (int32_t *)P(A_HI), m);
     if ((rc = grab_reserve(ix, ix->plans, m * sizeof(QueryPlan))) != GRAB_OK) return rc;
     if ((rc = grab_reserve(ix, ix->seeds, (size_t)m * proto.n_seeds * 4)) != GRAB_OK) return rc;
@@ -667,6 +752,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     if ((rc = grab_plan_order(ix, s)) != GRAB_OK) return rc;
     if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
     if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
+    k_sum_search_counters<<<blocks_for(m), TPB, 0, st>>>(s.counters, m, stats);
     ix->last_nq = 0;
     if (rule.mode == 1 && kr > 0) {
         // ---- 3': the same search over every other bucket (Section 4.4: candidates from the global scope)
@@ -674,7 +760,9 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
         s.only_bucket = (const int32_t *)P(A_SCOPE); s.out_ids = (uint32_t *)P(A_CG_S); s.out_dist = (float *)P(A_CG_D);
         if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
         if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
+        k_sum_search_counters<<<blocks_for(m), TPB, 0, st>>>(s.counters, m, stats);
     }
+    mark(1);
     // ---- 4: forward selection, new adjacency rows, reverse requests
     ForwardArgs f;
     f.X = ix->X; f.A = ix->A; f.vecs = d_vecs; f.slot = slot;
@@ -682,12 +770,13 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     f.key1 = (u64 *)P(A_KEY1); f.key2 = (u64 *)P(A_KEY2); f.reqd = (float *)P(A_REQD);
     f.by_bucket = (const uint32_t *)P(A_IDX_S); f.m = m;
     f.beam = beam; f.kl = kl; f.kr = kr; f.metric = ix->metric;
-    f.mode = rule.mode; f.kp = rule.n_proximal; f.window = rule.window;
+    f.mode = rule.mode; f.kp = rule.n_proximal; f.window = rule.window; f.remote_cands = ix->prm.append_remote_cands;
     f.gcand_s = (const uint32_t *)P(A_CG_S); f.gcand_d = (const float *)P(A_CG_D);
-    f.attr = ix->attr; f.new_attr = d_attrs;
+    f.attr = ix->attr; f.new_attr = d_attrs; f.node_out = (uint32_t *)P(A_NODE_OUT);
     RewireArgs r;
     memset(&r, 0, sizeof(r));
     if ((rc = launch_append(ix, f, r, m, 0)) != GRAB_OK) return rc;
+    mark(2);
     // ---- the new objects themselves
     const int32_t row_f4 = ix->dim / 4;
     k_write_new<<<blocks_for(m * row_f4), TPB, 0, st>>>((const float4 *)d_vecs, d_attrs, slot, m, ix->n, row_f4, (float4 *)ix->X,
@@ -702,9 +791,12 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.order = (const uint32_t *)P(A_ORD2);
     r.key2 = (const u64 *)P(A_KEY2); r.reqd = (const float *)P(A_REQD); r.nreq = nreq;
     r.kl = kl; r.kr = kr; r.metric = ix->metric; r.table = ix->table; r.B = B;
-    r.mode = rule.mode; r.kp = rule.n_proximal; r.window = rule.window; r.attr = ix->attr;
+    r.mode = rule.mode; r.kp = rule.n_proximal; r.window = rule.window; r.attr = ix->attr; r.grp_out = (uint32_t *)P(A_GRP_OUT);
     r.a = ix->prm.alpha * ix->prm.alpha;
+    mark(3);
     if ((rc = launch_append(ix, f, r, m, 1)) != GRAB_OK) return rc;
+    mark(4);
+    k_reduce_stats<<<blocks_for(nreq > m ? nreq : m), TPB, 0, st>>>(r.key1s, r.grp_out, nreq, f.node_out, m, stats);
     // ---- 6: table
     k_widen<<<blocks_for(m), TPB, 0, st>>>(d_attrs, bucket, m, ix->table);
     k_grow<<<blocks_for(B), TPB, 0, st>>>(ix->table, counts, B);
@@ -712,5 +804,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     GRAB_HIP(ix, hipMemcpyAsync(ix->h_table, ix->table, sizeof(int32_t) * T_COLS * B, hipMemcpyDeviceToHost, st));
     GRAB_HIP(ix, hipStreamSynchronize(st));
     ix->n += m;
+    ix->app_timed = ix->profile;
+    ix->app_has_stats = true;
     return GRAB_OK;
 }

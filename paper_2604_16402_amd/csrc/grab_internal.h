@@ -59,6 +59,7 @@ struct SearchParams {
     int32_t remote_mode = 0;      // 0: remote entry j belongs to the j-th target bucket; 1: proximal / global split
     int32_t n_proximal = -1;      // mode 1: remote positions for proximal candidates; -1: ceil(k_remote / 2)
     double remote_window = 0.2;   // mode 1: proximal = attribute within this fraction of the attribute span
+    int32_t append_remote_cands = 0;  // mode 0 insertion: candidates whose remote entries are looked at; 0: all
 };
 
 // the remote wiring in force for one construction or insertion call (Section 4.3, Remote Edge Construction)
@@ -106,6 +107,9 @@ struct grab_index {
     int64_t last_nq = 0;
     const uint32_t *last_counters = nullptr;   // where the most recent search wrote its counters
     std::vector<DevBuf> app;     // append's work arena
+    DevBuf app_stats;            // work counters of the last insertion (12 x uint64)
+    bool app_has_stats = false, app_timed = false;
+    hipEvent_t app_ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
 
     bool profile = false;
     bool timed = false;          // the last search recorded events

@@ -85,15 +85,18 @@ def _pair(n, dim, B, kl, kr, n_cap, seed, components=16, metric=W.L2SQ):
     return cfg, ix, ora, X, a
 
 
-@pytest.mark.parametrize("n,dim,B,kl,kr,n_cap,beam,width", [
-    (6000, 128, 8, 16, 4, 9000, 64, 1),
-    (5000, 64, 5, 24, 8, 8000, 32, 2),
-    (3000, 960, 3, 20, 4, 4500, 48, 1),
-    (100000, 128, 16, 32, 8, 150000, 64, 1),
+@pytest.mark.parametrize("n,dim,B,kl,kr,n_cap,beam,width,rcands", [
+    (6000, 128, 8, 16, 4, 9000, 64, 1, 0),
+    (5000, 64, 5, 24, 8, 8000, 32, 2, 0),
+    (3000, 960, 3, 20, 4, 4500, 48, 1, 0),
+    (100000, 128, 16, 32, 8, 150000, 64, 1, 0),
+    (6000, 128, 8, 16, 4, 9000, 128, 2, 24),      # remote parts from the nearest 24 of 128 candidates
+    (4000, 160, 4, 12, 4, 6000, 64, 1, 0),        # five 128-byte lines per row
+    (4000, 384, 4, 12, 4, 6000, 64, 1, 8),
 ])
-def test_append_matches_oracle(n, dim, B, kl, kr, n_cap, beam, width):
+def test_append_matches_oracle(n, dim, B, kl, kr, n_cap, beam, width, rcands):
     cfg, ix, ora, X, a = _pair(n, dim, B, kl, kr, n_cap, seed=n + dim)
-    for k, v in [("append_beam", beam), ("search_width", width)]:
+    for k, v in [("append_beam", beam), ("search_width", width), ("append_remote_cands", rcands)]:
         ix.set_param(k, v)
         ora.params[k] = v
     allX, alla = [X], [a]
@@ -104,6 +107,7 @@ def test_append_matches_oracle(n, dim, B, kl, kr, n_cap, beam, width):
         ix.append_batch(nx, na)
         ora.append(nx, na, threads=O.max_threads())
         _same_index(ix, ora)
+        assert ix.get_append_stats() == ora.last_append_stats      # the same work, counted the same way
         allX.append(nx); alla.append(na)
     # searches over the grown index: tails are live, so the attribute-read path is exercised
     q = W.query_vectors(cfg)

@@ -20,6 +20,9 @@ def _case(n, dim, B, metric, seed, n_cap=None):
     (2500, 64, 5, 12, 8, 0, W.L2SQ, 3000),      # pool default, more remote entries than buckets allow, slack
     (2000, 96, 4, 20, 2, 40, W.IP, None),
     (1500, 960, 3, 8, 2, 24, W.L2SQ, None),
+    (1500, 160, 3, 12, 3, 24, W.L2SQ, None),
+    (1500, 640, 3, 12, 3, 24, W.L2SQ, None),
+    (1500, 384, 3, 12, 3, 24, W.IP, 1800),
     (700, 32, 9, 33, 5, 64, W.L2SQ, None),      # buckets (~78 rows) barely larger than the pool
     (300, 32, 6, 32, 3, 64, W.L2SQ, None),      # buckets (50 rows) smaller than the pool: short lists
     (4000, 128, 5, 32, 4, 128, W.L2SQ, None),   # 128 candidates: two per lane

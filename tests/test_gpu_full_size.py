@@ -211,6 +211,7 @@ def test_all_ten_rounds_of_the_dynamic_config_match_the_oracle(c5_inputs):
         ix.append_batch(torch.from_numpy(nx).to(dev), torch.from_numpy(na).to(dev))
         ora.append(nx, na, threads=O.max_threads())
         _same_whole_index(ix, ora)
+        assert ix.get_append_stats() == ora.last_append_stats
         print(f"round {r + 1}: {ora.n} objects, index identical", flush=True)
         if r in (0, 4, 9):
             q = W.query_vectors(cfg, stream=100 + r)

@@ -53,6 +53,7 @@ def test_hand_worked_append_with_proximal_and_global_picks_on_gpu(alpha):
     table, id2slot, _ = ix.get_layout()
     assert id2slot[8:10].tolist() == g["new_slots"] and table.tolist() == want["table"]
     assert ix.get_graph().tolist() == want["adj_slots"]
+    assert ix.get_append_stats() == want["stats"]
     ix.close()
 
 
@@ -149,6 +150,7 @@ def test_append_matches_oracle_under_both_readings(n, dim, B, kl, kr, n_cap, bea
         ix.append_batch(nx, na)
         ora.append(nx, na, threads=O.max_threads())
         _same_index(ix, ora)
+        assert ix.get_append_stats() == ora.last_append_stats      # the same work, counted the same way
     new = ora.id2slot[n:ora.n]
     indeg = np.bincount(ora.A[ora.A != O.EMPTY].astype(np.int64), minlength=ora.n_cap)
     assert (indeg[new] > 0).mean() > 0.98

@@ -97,6 +97,10 @@ def _random_case(n, dim, B, kl, kr, metric, seed, n_cap=None, nq=300, domain=Non
     (256, W.L2SQ, 1500, 4, 20, 2, None),       # 8 lines per row (still register-resident query)
     (960, W.L2SQ, 1200, 3, 48, 8, None),       # 30 lines per row, query staged in LDS
     (128, W.L2SQ, 2000, 4, 61, 3, None),       # degree 64
+    (160, W.L2SQ, 2000, 4, 16, 4, None),       # 5 lines per row
+    (192, W.IP, 2000, 4, 16, 4, 2400),         # 6 lines per row
+    (384, W.L2SQ, 1500, 3, 20, 4, None),       # 12 lines per row: query staged in LDS, two batches of pieces
+    (640, W.L2SQ, 1500, 3, 20, 4, None),       # 20 lines per row
 ])
 def test_other_shapes_match_oracle(torch_dev, dim, metric, n, B, kl, kr, n_cap):
     c = _random_case(n, dim, B, kl, kr, metric, seed=dim + n, n_cap=n_cap)

@@ -236,6 +236,33 @@ def test_bias_opens_rows_for_newcomers():
             assert (s in ix.A[t]) == bool(same or O.EMPTY in part)
 
 
+def test_remote_part_from_the_nearest_candidates_only():
+    # append_remote_cands = 1: remote entry j of a new row is the j-th remote entry of its nearest
+    # local candidate; a value at or above the queue size changes nothing
+    rows = {}
+    for rc in (0, 1, 64, 500):
+        cfg, ix = _fresh(0.6)
+        ix.params["append_remote_cands"] = rc
+        pre = ix.A.copy()
+        ix.append(W.append_vectors(cfg, 0), W.append_attributes(cfg, 0))
+        rows[rc] = ix.A[ix.id2slot[3000:3400]].copy()
+        if rc == 1:
+            kl = ix.k_local
+            nx = W.append_vectors(cfg, 0)
+            for i in range(0, 400, 9):
+                s = ix.id2slot[3000 + i]
+                b = int(ix.bucket_of_slots([s])[0])
+                members = np.arange(ix.table[b, 0], ix.table[b, 0] + ix.table[b, 2])
+                members = members[ix.slot2id[members] < 3000]
+                d = [(float(O.distance(nx[i], ix.X[c])), int(c)) for c in members]
+                nearest = min(d)[1]       # 64 seeds in a bucket of 750: the search finds the nearest object (checked: it is in the row)
+                if nearest != rows[1][i][0]:
+                    continue
+                assert rows[1][i][kl:].tolist() == pre[nearest][kl:].tolist()
+    assert np.array_equal(rows[0], rows[64]) and np.array_equal(rows[0], rows[500])
+    assert not np.array_equal(rows[0], rows[1])
+
+
 def test_no_node_loses_its_last_in_edge(grown):
     # an edge x->n is only overwritten by a newcomer that points to n itself, so in-degrees never
     # fall to zero and every appended object that was accepted anywhere stays reachable

@@ -34,6 +34,7 @@ def test_hand_worked_append_with_proximal_and_global_picks(alpha):
     assert kept.tolist() == g["kept"]
     assert ix.A.tolist() == want["adj_slots"]
     assert ix.table.tolist() == want["table"]
+    assert ix.last_append_stats == want["stats"]
 
 
 def test_scoped_searches_see_exactly_their_scope():
