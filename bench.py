@@ -69,6 +69,7 @@ def main():
     ap.add_argument("--rewire-from-targets", action="store_true",
                     help="remote mode 1: construct by target bucket first (mode 0), then rewrite the remote parts with grab_build_remote "
                          "under mode 1, whose candidate searches then run over a graph that already has cross-bucket edges")
+    ap.add_argument("--rounds", type=int, default=0, help="dynamic workload: stop after this many appends (0: all)")
     ap.add_argument("--holdout-stream", type=int, default=101, help="query stream of the recall check on fresh queries")
     ap.add_argument("--parity", action="store_true", help="dynamic workload: compare the whole index and one search batch with the oracle after every append")
     ap.add_argument("--alpha", type=float, default=0.6, help="dynamic workload: freshness bias of Eq. 3")
@@ -90,7 +91,7 @@ def main():
 
     import torch
     from paper_2604_16402_amd import binding, workloads as W
-    if args.no_recall and not args.config:
+    if args.no_recall and not args.config and not W.CONFIGS[args.workload].append_rounds:
         print("bench.py: --no-recall needs --config (the grid is chosen by recall)", file=sys.stderr)
         sys.exit(2)
 
@@ -363,8 +364,11 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
     whole domain) each followed by a fresh 10k-query search batch at 10 % range (Section 5.3's
     stability protocol on synthetic data).  Reports append vectors/s and search QPS per round."""
     import torch
-    from harness import groundtruth as GT
-    from paper_2604_16402_amd import workloads as W
+    from paper_2604_16402_amd import binding, workloads as W
+    GT = None
+    if not args.no_recall:
+        from harness import groundtruth as GT
+    n_rounds = args.rounds or cfg.append_rounds
     k = cfg.k
     beam, S, w, vc = [int(x) for x in (args.config or "32,512,4,1400").split(",")][:4]
     ora = None
@@ -409,17 +413,33 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
             return None
         return {"queries_per_s": round(len(q) / best[0], 1), "recall_at_10": round(best[1], 4), "setting": best[2]}
 
+    def bulk_reference(allX, alla, q, lod, hid, gt, ids, dist):
+        """context: the same final data set built in bulk by grab_build_graph, searched with the same setting"""
+        ref = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
+        ref.build_buckets(allX, alla, cfg.buckets)
+        construct(ref)
+        ref.set_param("visited_cap", vc); ref.set_param("n_seeds", S); ref.set_param("search_width", w)
+        ref.search_range(q, lod, hid, k, beam, ids, dist)
+        torch.cuda.synchronize()
+        out = {"recall_at_10": round(GT.recall(ids, gt), 4)}
+        at_recall["bulk_rebuilt"] = qps_at_recall(ref, q, lod, hid, gt, ids, dist)
+        ref.close()
+        log(f"[bench] bulk-rebuilt reference on the final {ix.sizes()['n']} objects: {out}")
+        return out
+
     q0 = torch.from_numpy(W.query_vectors(cfg, stream=100)).to(dev)
     lo0, hi0 = W.ranges(cfg, args.selectivity, stream=300)
     lo0d, hi0d = torch.from_numpy(lo0).to(dev), torch.from_numpy(hi0).to(dev)
     ids0 = torch.empty((len(q0), k), dtype=torch.int32, device=dev)
     dist0 = torch.empty((len(q0), k), dtype=torch.float32, device=dev)
-    at_recall = {"before_appends": qps_at_recall(ix, q0, lo0d, hi0d, GT.exact_filtered_knn(Xd, ad, q0, lo0d, hi0d, k, cfg.metric), ids0, dist0)}
+    at_recall = {}
+    if GT is not None:
+        at_recall["before_appends"] = qps_at_recall(ix, q0, lo0d, hi0d, GT.exact_filtered_knn(Xd, ad, q0, lo0d, hi0d, k, cfg.metric), ids0, dist0)
     ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
     rounds = []
     app_stats = []
     allX, alla = Xd, ad
-    for r in range(cfg.append_rounds):
+    for r in range(n_rounds):
         nx = torch.from_numpy(W.append_vectors(cfg, r)).to(dev)
         na = torch.from_numpy(W.append_attributes(cfg, r)).to(dev)
         # append's candidate search: beam append_beam, its own seeds and width
@@ -458,7 +478,7 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
             ix.search_range(q, lod, hid, k, beam, ids, dist)
         torch.cuda.synchronize()
         t_s = (time.perf_counter() - t) / 10
-        gt = GT.exact_filtered_knn(allX, alla, q, lod, hid, k, cfg.metric)
+        gt = GT.exact_filtered_knn(allX, alla, q, lod, hid, k, cfg.metric) if GT is not None else None
         if ora is not None:
             ora.params.update(visited_cap=vc, n_seeds=S, search_width=w, max_iter=None)
             o_ids, o_dist, _ = ora.search(q.cpu().numpy(), lo, hi, k, beam, threads=O.max_threads())
@@ -468,30 +488,21 @@ def run_dynamic(args, cfg, ix, X, attrs, Xd, ad, dev, build, construct):
         new_frac = float((ids.cpu().numpy().view(np.uint32) >= cfg.n).mean())
         rounds.append({"round": r + 1, "objects": ix.sizes()["n"], "append_vectors_per_s": round(cfg.append_batch / t_app, 1),
                        "append_ms": round(t_app * 1e3, 2), "phase_ms": [round(x, 3) for x in st["ms"]], "search_qps": round(len(q) / t_s, 1),
-                       "recall_at_10": round(GT.recall(ids, gt), 4), "results_from_appended": round(new_frac, 4)})
+                       "recall_at_10": None if gt is None else round(GT.recall(ids, gt), 4), "results_from_appended": round(new_frac, 4)})
         log(f"[bench] round {r + 1}: {rounds[-1]}")
-    at_recall["after_appends"] = qps_at_recall(ix, q, lod, hid, gt, ids, dist)
-    ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
-    # connectivity of the grown graph (Section 5.4's diagnostic)
-    from harness import diagnostics
-    from paper_2604_16402_amd import binding
-    _, _, slot2id = ix.get_layout()
-    final_adj = ix.get_graph()
-    scc = diagnostics.strong_components(final_adj, slot2id != 0xFFFFFFFF)
-    n_orphans = diagnostics.orphans(final_adj, slot2id != 0xFFFFFFFF)
-    del final_adj
-    log(f"[bench] after the appends: {scc} strongly connected components, {n_orphans} objects without an in-edge")
-    # context: the same final data set built in bulk by grab_build_graph, searched with the same setting
-    ref = binding.Index(cfg.dim, cfg.metric, stream=torch.cuda.current_stream(dev).cuda_stream)
-    ref.build_buckets(allX, alla, cfg.buckets)
-    construct(ref)
-    ref.set_param("visited_cap", vc); ref.set_param("n_seeds", S); ref.set_param("search_width", w)
-    ref.search_range(q, lod, hid, k, beam, ids, dist)
-    torch.cuda.synchronize()
-    rebuilt = {"recall_at_10": round(GT.recall(ids, gt), 4)}
-    at_recall["bulk_rebuilt"] = qps_at_recall(ref, q, lod, hid, gt, ids, dist)
-    ref.close()
-    log(f"[bench] bulk-rebuilt reference on the final {ix.sizes()['n']} objects: {rebuilt}")
+    scc = n_orphans = rebuilt = None
+    if GT is not None:
+        at_recall["after_appends"] = qps_at_recall(ix, q, lod, hid, gt, ids, dist)
+        ix.set_param("visited_cap", vc); ix.set_param("n_seeds", S); ix.set_param("search_width", w)
+        # connectivity of the grown graph (Section 5.4's diagnostic)
+        from harness import diagnostics
+        _, _, slot2id = ix.get_layout()
+        final_adj = ix.get_graph()
+        scc = diagnostics.strong_components(final_adj, slot2id != 0xFFFFFFFF)
+        n_orphans = diagnostics.orphans(final_adj, slot2id != 0xFFFFFFFF)
+        del final_adj
+        log(f"[bench] after the appends: {scc} strongly connected components, {n_orphans} objects without an in-edge")
+        rebuilt = bulk_reference(allX, alla, q, lod, hid, gt, ids, dist)
     # ---- what an append must move (algorithmic bytes from the call's own work counters), per phase
     row, K, m = cfg.dim * 4, cfg.k_local + cfg.k_remote, cfg.append_batch
     n_search = 2 if args.remote_mode == 1 else 1

@@ -14,6 +14,9 @@
 #define GRAB_MAX_BEAM 512
 #define GRAB_MAX_CAND 512   // search_width * degree, and the seed chunk size
 #define GRAB_WAVE 64
+// counter block of the search's launch order: one 128-byte line per bin, one more for the tail
+#define GRAB_BIN_STRIDE 32
+#define GRAB_BIN_BLOCK_BYTES ((size_t)(GRAB_BIN_STRIDE * (GRAB_MAX_BUCKETS + 2)) * 4)
 
 // The vector lengths the kernels are built for, in 32-float (128-byte) units: every kernel that
 // reads feature rows is instantiated once per entry, so that a whole row's loads can be issued
@@ -105,6 +108,7 @@ struct grab_index {
     // launch order of the queries of a search (grab_plan_order)
     DevBuf q_bin, q_rank, q_order, bin_count;
     int64_t last_nq = 0;
+    bool order_dirty = true;     // the bin counters of the launch order may not be zero
     const uint32_t *last_counters = nullptr;   // where the most recent search wrote its counters
     std::vector<DevBuf> app;     // append's work arena
     DevBuf app_stats;            // work counters of the last insertion (12 x uint64)
@@ -156,9 +160,10 @@ struct SearchLaunch {
     float *out_dist;    // device [nq][k]
     bool out_slots;
     // launch order (all nullptr: query i runs in workgroup i): see grab_plan_order
-    int32_t *q_bin = nullptr, *q_rank = nullptr, *bin_count = nullptr;
+    int32_t *q_bin = nullptr, *bin_count = nullptr;
     uint32_t *order = nullptr;   // [order_len]: query of each workgroup, GRAB_EMPTY for none
     int64_t order_len = 0;
+    bool *order_dirty = nullptr; // host flag: bin_count may not be zero (null: always clear it first)
 };
 // Reserves the buffers that let the search run its queries grouped by first selected bucket, one
 // contiguous run of that order per XCD (queries that read the same buckets then share L2 and the

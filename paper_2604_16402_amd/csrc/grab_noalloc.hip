@@ -26,7 +26,7 @@ constexpr size_t OFF_QRANK = OFF_QBIN + SZ_Q32;
 constexpr size_t OFF_ORDER = OFF_QRANK + SZ_Q32;
 constexpr size_t SZ_ORDER = (size_t)(NOALLOC_MAX_NQ + 2048) * 4;   // nq rounded up to eight short runs
 constexpr size_t OFF_BINS = OFF_ORDER + SZ_ORDER;
-constexpr size_t SZ_BINS = (size_t)(GRAB_MAX_BUCKETS + 1 + 63) / 64 * 64 * 4;
+constexpr size_t SZ_BINS = (GRAB_BIN_BLOCK_BYTES + 255) / 256 * 256;   // the counter block of the launch order
 constexpr size_t OFF_SEEDS = OFF_BINS + SZ_BINS;
 constexpr size_t SZ_SEEDS = (size_t)NOALLOC_MAX_SEED_WORDS * 4;
 constexpr size_t SCRATCH_BYTES = OFF_SEEDS + SZ_SEEDS;            // about 18 MiB per GPU
@@ -83,15 +83,15 @@ extern "C" grab_status grab_search_range_noalloc(grab_index *ix, const float *qu
     s.out_ids = out_ids; s.out_dist = out_dist;
     if (nq >= 2048) {   // the launch order of grab_search_range, in the same parts of the array every time
         s.q_bin = reinterpret_cast<int32_t *>(base + OFF_QBIN);
-        s.q_rank = reinterpret_cast<int32_t *>(base + OFF_QRANK);
         s.bin_count = reinterpret_cast<int32_t *>(base + OFF_BINS);
         s.order = reinterpret_cast<uint32_t *>(base + OFF_ORDER);
         s.order_len = grab_order_len(nq);
+        s.order_dirty = nullptr;   // the array is shared by every handle on this GPU: clear the counters each time
     }
     ix->timed = false;
     if (ix->profile) GRAB_HIP(ix, hipEventRecord(ix->ev[0], ix->stream));
-    // the select launch clears the bin counts and the order before it uses them; plans, seeds and
-    // counters are written in full for queries 0..nq-1 and nothing beyond is read
+    // the bin counters are cleared before use and every entry of the order is written; plans, seeds
+    // and counters are written in full for queries 0..nq-1 and nothing beyond is read
     if ((st = grab_launch_select(ix, s)) != GRAB_OK) return st;
     if (ix->profile) GRAB_HIP(ix, hipEventRecord(ix->ev[1], ix->stream));
     if ((st = grab_launch_beam(ix, s)) != GRAB_OK) return st;

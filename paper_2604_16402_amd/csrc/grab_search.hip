@@ -42,17 +42,64 @@ __device__ int wave_bound(const int32_t *__restrict__ a, int n, int key, bool st
     return lo;
 }
 
+// two searches of wave_bound's kind in lockstep, so that their memory round trips overlap
+__device__ void wave_bound2(const int32_t *__restrict__ a1, int n1, int key1, bool strict1,
+                            const int32_t *__restrict__ a2, int n2, int key2, bool strict2, int lane, int &r1, int &r2) {
+    int lo1 = 0, hi1 = n1, lo2 = 0, hi2 = n2;
+    while (hi1 > lo1 || hi2 > lo2) {
+        const int ch1 = (hi1 - lo1 + 63) >> 6, ch2 = (hi2 - lo2 + 63) >> 6;
+        const int p1 = lo1 + lane * ch1, p2 = lo2 + lane * ch2;
+        const bool act1 = hi1 > lo1 && p1 < hi1, act2 = hi2 > lo2 && p2 < hi2;
+        int x1 = 0, x2 = 0;
+        if (act1) x1 = a1[p1];
+        if (act2) x2 = a2[p2];
+        const int c1 = __popcll(__ballot(act1 && (strict1 ? (x1 <= key1) : (x1 < key1))));
+        const int c2 = __popcll(__ballot(act2 && (strict2 ? (x2 <= key2) : (x2 < key2))));
+        if (hi1 > lo1) {
+            if (c1 == 0) {
+                hi1 = lo1;
+            } else {
+                const int nhi = lo1 + c1 * ch1;
+                lo1 = lo1 + (c1 - 1) * ch1 + 1;
+                hi1 = nhi < hi1 ? nhi : hi1;
+            }
+        }
+        if (hi2 > lo2) {
+            if (c2 == 0) {
+                hi2 = lo2;
+            } else {
+                const int nhi = lo2 + c2 * ch2;
+                lo2 = lo2 + (c2 - 1) * ch2 + 1;
+                hi2 = nhi < hi2 ? nhi : hi2;
+            }
+        }
+    }
+    r1 = lo1;
+    r2 = lo2;
+}
+
 // ----------------------------------------------------------------------------- select + seed
 // Algorithm 2 lines 1-2: the run of buckets whose [min,max] meets [lo,hi]; the valid part of
 // the sorted prefix of the two edge buckets by search; the seed population (valid sorted part
 // then appended tail of every selected bucket, in bucket order) and one stratified, jittered
-// seed per stratum.  One wavefront per query.
+// seed per stratum.  One wavefront per query.  The bucket table is read once, into LDS; the two
+// searches run in lockstep.
+//
+// The same launch files the query for the launch order (q_bin etc. non-null): queries that select
+// the same buckets read the same vectors, so the search runs them grouped by first selected
+// bucket, each XCD taking contiguous runs of that order (see k_order).  bin of a query = its first
+// selected bucket (the bucket it is scoped to, for a candidate search); bin B = nothing selected.
+// This launch only counts the bins (atomics whose result nobody waits for); k_order ranks and
+// places.  Only the order in which queries run changes; every query's result and counters are
+// what they are in any order.
 __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ table, int32_t B,
                                                     const int32_t *__restrict__ attr,
                                                     const int32_t *__restrict__ lo_, const int32_t *__restrict__ hi_,
                                                     const int32_t *__restrict__ only_bucket, int32_t S, uint32_t salt,
-                                                    QueryPlan *__restrict__ plans, uint32_t *__restrict__ seeds) {
-    __shared__ int32_t pre[GRAB_MAX_BUCKETS + 1];
+                                                    QueryPlan *__restrict__ plans, uint32_t *__restrict__ seeds,
+                                                    int32_t *__restrict__ q_bin, int32_t *__restrict__ bin_count) {
+    extern __shared__ int32_t sm_sel[];
+    int32_t *tbase = sm_sel, *tnsort = sm_sel + B, *tntot = sm_sel + 2 * B, *pre = sm_sel + 3 * B;   // pre[B + 1]
     const int64_t q = blockIdx.x;
     const int lane = threadIdx.x;
     const int lo = lo_[q], hi = hi_[q];
@@ -60,22 +107,31 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
     // slot outside the slab of bucket b; INT32_MIN = nothing
     const int only = only_bucket ? only_bucket[q] : -1;
     const int ex = (only <= -2 && only != INT32_MIN) ? -2 - only : -1;   // excluded bucket
+    // bucket intervals are ordered, so counting gives the run: buckets entirely below lo come
+    // first, buckets starting at or below hi form a prefix
+    int below = 0, start_ok = 0;
+    for (int b = lane; b < B; b += 64) {
+        const int32_t *t = table + T_COLS * b;
+        tbase[b] = t[T_BASE]; tnsort[b] = t[T_NSORT]; tntot[b] = t[T_NTOT];
+        below += t[T_MAX] < lo;
+        start_ok += t[T_MIN] <= hi;
+    }
+    __syncthreads();
     int b0 = 0, b1 = -1;
     if (only >= 0) {
         b0 = b1 = only;
     } else if (ex >= 0) {
         b0 = 0; b1 = B - 1;
     } else if (only == -1 && lo <= hi) {
-        // bucket intervals are ordered, so counting gives the run: buckets entirely below lo
-        // come first, buckets starting at or below hi form a prefix
-        int below = 0, start_ok = 0;
-        for (int b = lane; b < B; b += 64) {
-            below += table[T_COLS * b + T_MAX] < lo;
-            start_ok += table[T_COLS * b + T_MIN] <= hi;
-        }
         b0 = wave_sum(below);
         b1 = wave_sum(start_ok) - 1;
         if (b1 < b0) { b0 = 0; b1 = -1; }
+    }
+    if (q_bin && lane == 0) {
+        int bin = only >= 0 ? only : (ex >= 0 ? ex : (b1 < b0 ? B : b0));
+        if (bin < 0 || bin > B) bin = B;
+        q_bin[q] = bin;
+        atomicAdd(&bin_count[GRAB_BIN_STRIDE * bin], 1);
     }
     QueryPlan p;
     p.b0 = b0; p.b1 = b1; p.V = 0; p.n_seeds = 0;
@@ -86,20 +142,21 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
         for (int j = lane; j < S; j += 64) seeds[q * S + j] = GRAB_EMPTY;
         return;
     }
-    const int32_t *t0 = table + T_COLS * b0, *t1 = table + T_COLS * b1;
-    const int base0 = t0[T_BASE], ns0 = t0[T_NSORT], nt0 = t0[T_NTOT];
-    const int base1 = t1[T_BASE], ns1 = t1[T_NSORT], nt1 = t1[T_NTOT];
+    const int base0 = tbase[b0], ns0 = tnsort[b0], nt0 = tntot[b0];
+    const int base1 = tbase[b1], ns1 = tnsort[b1], nt1 = tntot[b1];
     int sa0, se0, se1 = 0, tail0, tail1 = 0;
     if (only >= 0 || ex >= 0) {   // whole slabs, nothing to check: the "sorted span" is every occupied slot
         sa0 = 0; se0 = nt0; tail0 = 0;
         se1 = nt1; tail1 = 0;
     } else {
-        sa0 = wave_bound(attr + base0, ns0, lo, false, lane);
-        se0 = (b1 == b0) ? wave_bound(attr + base0, ns0, hi, true, lane) : ns0;
-        if (se0 < sa0) se0 = sa0;
+        int up;
+        wave_bound2(attr + base0, ns0, lo, false, attr + base1, ns1, hi, true, lane, sa0, up);
         tail0 = nt0 - ns0;
-        if (b1 > b0) {
-            se1 = wave_bound(attr + base1, ns1, hi, true, lane);
+        if (b1 == b0) {
+            se0 = up < sa0 ? sa0 : up;
+        } else {
+            se0 = ns0;
+            se1 = up;
             tail1 = nt1 - ns1;
         }
     }
@@ -113,7 +170,7 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
             if (b == ex) c = 0;
             else if (b == b0) c = (se0 - sa0) + tail0;
             else if (b == b1) c = se1 + tail1;
-            else c = table[T_COLS * b + T_NTOT];
+            else c = tntot[b];
         }
         int inc = c;
 #pragma unroll
@@ -143,7 +200,7 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
             int b = b0 + l;
             if (b == b0) slot = off < se0 - sa0 ? base0 + sa0 + off : base0 + ns0 + (off - (se0 - sa0));
             else if (b == b1) slot = off < se1 ? base1 + off : base1 + ns1 + (off - se1);
-            else slot = table[T_COLS * b + T_BASE] + off;
+            else slot = tbase[b] + off;
         }
         seeds[q * S + j] = slot;
     }
@@ -153,13 +210,13 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
             // everything before the excluded slab, and everything after it
             const int32_t *te = table + T_COLS * ex;
             p.s0 = base0; p.e0 = te[T_BASE];
-            p.ms = te[T_BASE] + te[T_CAP]; p.e1 = base1 + t1[T_CAP];
+            p.ms = te[T_BASE] + te[T_CAP]; p.e1 = base1 + table[T_COLS * b1 + T_CAP];
             if (V == 0) { p.b0 = 0; p.b1 = -1; }     // nothing lies outside the only bucket
         } else {
             p.s0 = base0 + sa0; p.e0 = base0 + se0;
             p.t0s = base0 + ns0; p.t0e = base0 + ns0 + tail0;
             if (b1 > b0) {
-                p.ms = table[T_COLS * (b0 + 1) + T_BASE];
+                p.ms = tbase[b0 + 1];
                 p.e1 = base1 + se1;
                 p.t1s = base1 + ns1; p.t1e = base1 + ns1 + tail1;
             }
@@ -172,96 +229,86 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
 
 // ------------------------------------------------------------------------------ launch order
 #define GRAB_ORDER_RUN 256   // short run length, see k_order
-// Queries that select the same buckets read the same vectors.  The search therefore launches them
-// grouped by first selected bucket (a counting sort: k_order_bin counts and ranks, k_order
-// places), and gives each XCD contiguous runs of that order (workgroups go round the eight XCDs).
-// Only the order in which queries run changes; every query's result and counters are what they
-// are in any order.
-__global__ void k_order_reset(int32_t *__restrict__ bin_count, int nbins, uint32_t *__restrict__ order, int64_t order_len) {
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < nbins) bin_count[i] = 0;
-    if (i < order_len) order[i] = GRAB_EMPTY;
+// Counter block of the launch order: bin i has its own 128-byte line (atomics to one line are
+// served one after another, and a batch sends thousands at once): word 0 of the line = queries in
+// the bin (counted by k_select_seed), word 1 = positions of the bin already handed out (k_order);
+// after the last line: finished k_order workgroups.  All zero between calls: k_order's last
+// workgroup clears them; k_order_reset does it when that is in doubt (fresh memory, a launch that
+// failed in between).
+__global__ void k_order_reset(int32_t *__restrict__ bin_count, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) bin_count[i] = 0;
 }
 
-// bin of a query = its first selected bucket (the bucket it is restricted to, for an append's
-// search); bin B = its range meets no bucket.  (Finer bins, by the position of lo inside the
-// bucket's interval, gained nothing.)  Rank inside the bin: LDS counts per workgroup, one global
-// atomic per workgroup and bin.
-__global__ __launch_bounds__(256) void k_order_bin(const int32_t *__restrict__ table, int32_t B,
-                                                   const int32_t *__restrict__ lo_, const int32_t *__restrict__ hi_,
-                                                   const int32_t *__restrict__ only_bucket, int64_t nq,
-                                                   int32_t *__restrict__ q_bin, int32_t *__restrict__ q_rank,
-                                                   int32_t *__restrict__ bin_count) {
-    __shared__ int32_t cnt[GRAB_MAX_BUCKETS + 1], base[GRAB_MAX_BUCKETS + 1];
-    const int last = B;
-    for (int i = threadIdx.x; i <= last; i += 256) cnt[i] = 0;
-    __syncthreads();
-    const int64_t q = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    int bin = last, local = 0;
-    if (q < nq) {
-        if (only_bucket && only_bucket[q] != -1) {
-            const int sc = only_bucket[q];      // scoped queries: by the bucket they are scoped to
-            bin = sc >= 0 ? sc : (sc == INT32_MIN ? last : -2 - sc);
-        } else {
-            const int lo = lo_[q], hi = hi_[q];
-            if (lo <= hi) {
-                int l = 0, r = B;    // first bucket whose max is not below lo (bucket intervals are ordered)
-                while (l < r) {
-                    const int m = (l + r) >> 1;
-                    if (table[T_COLS * m + T_MAX] < lo) l = m + 1; else r = m;
-                }
-                if (l < B && table[T_COLS * l + T_MIN] <= hi) bin = l;
+// Places the queries in the launch order: position in bucket order = start of the bin + rank;
+// workgroup w of the search kernel runs query order[w] (GRAB_EMPTY: none).  Rank: LDS counts per
+// workgroup, one global atomic per workgroup and bin.  Runs of `run` consecutive positions go
+// round the XCDs: the i-th workgroup of XCD c (w = 8 i + c) takes element i % run of run
+// (i / run) * 8 + c.  Evenly filled bins: runs_per_xcd long runs per XCD (one gives the most
+// sharing).  When one bin holds a large share of the batch, what a query costs follows its bin (a
+// query that starts in the last bucket cannot be wide), and long runs would leave some XCDs with
+// all the expensive queries: short runs then.
+// One thread per entry of `order`: it marks its own entry empty if no position maps there, and
+// files query t (t < nq).  The last workgroup to finish zeroes the counter block for the next call.
+__global__ __launch_bounds__(256) void k_order(const int32_t *__restrict__ q_bin, int32_t *__restrict__ bin_count, int nbins,
+                                               int64_t nq, uint32_t *__restrict__ order, int64_t order_len, int runs_per_xcd) {
+    __shared__ int32_t start[GRAB_MAX_BUCKETS + 2], cnt[GRAB_MAX_BUCKETS + 1], base[GRAB_MAX_BUCKETS + 1];
+    __shared__ int s_biggest, last_block;
+    const int tid = threadIdx.x, lane = tid & 63;
+    for (int i = tid; i < nbins; i += 256) cnt[i] = 0;
+    if (tid < 64) {   // exclusive prefix of the bin counts (every workgroup recomputes it: at most 1025 words)
+        int carry = 0, biggest = 0;
+        for (int i0 = 0; i0 < nbins; i0 += 64) {
+            const int i = i0 + lane;
+            const int c = i < nbins ? bin_count[GRAB_BIN_STRIDE * i] : 0;
+            biggest = max(biggest, c);
+            int inc = c;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                int up = __shfl_up(inc, d);
+                if (lane >= d) inc += up;
             }
+            if (i < nbins) start[i] = carry + inc - c;
+            carry += __shfl(inc, 63);
         }
-        if (bin < 0 || bin > last) bin = last;
-        local = atomicAdd(&cnt[bin], 1);
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) biggest = max(biggest, __shfl_xor(biggest, d));
+        if (lane == 0) s_biggest = biggest;
     }
     __syncthreads();
-    for (int i = threadIdx.x; i <= last; i += 256)
-        if (cnt[i] > 0) base[i] = atomicAdd(&bin_count[i], cnt[i]);
-    __syncthreads();
-    if (q < nq) { q_bin[q] = bin; q_rank[q] = base[bin] + local; }
-}
-
-__global__ __launch_bounds__(64) void k_order(const int32_t *__restrict__ q_bin, const int32_t *__restrict__ q_rank,
-                                              const int32_t *__restrict__ bin_count, int nbins, int64_t nq,
-                                              uint32_t *__restrict__ order, int64_t order_len, int runs_per_xcd) {
-    __shared__ int32_t start[GRAB_MAX_BUCKETS + 2];
-    const int lane = threadIdx.x;
-    // exclusive prefix of the bin counts (every workgroup recomputes it: at most 1025 words)
-    int carry = 0, biggest = 0;
-    for (int i0 = 0; i0 < nbins; i0 += 64) {
-        const int i = i0 + lane;
-        const int c = i < nbins ? bin_count[i] : 0;
-        biggest = max(biggest, c);
-        int inc = c;
-#pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            int up = __shfl_up(inc, d);
-            if (lane >= d) inc += up;
-        }
-        if (i < nbins) start[i] = carry + inc - c;
-        carry += __shfl(inc, 63);
-    }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) biggest = max(biggest, __shfl_xor(biggest, d));   // all lanes still active
-    __syncthreads();
-    const int64_t q = (int64_t)blockIdx.x * 64 + lane;
-    if (q >= nq) return;
-    const int bin = q_bin[q];
-    if (bin < 0 || bin >= nbins) return;
-    const int64_t pos = (int64_t)start[bin] + q_rank[q];      // position in bucket order
-    if (pos < 0 || pos >= nq) return;
-    // Runs of `run` consecutive positions go round the XCDs: the i-th workgroup of XCD c (w = 8 i + c)
-    // takes element i % run of run (i / run) * 8 + c.  Evenly filled bins: runs_per_xcd long runs per
-    // XCD (one gives the most sharing).  When one bin holds a large share of the batch, what a query
-    // costs follows its bin (a query that starts in the last bucket cannot be wide), and long runs
-    // would leave some XCDs with all the expensive queries: short runs then.
     const int64_t parts = 8 * (int64_t)runs_per_xcd;
-    const int64_t run = (int64_t)biggest * 16 > nq ? GRAB_ORDER_RUN : (nq + parts - 1) / parts;
-    const int64_t g = pos / run, e = pos % run;
-    const int64_t w = ((g / 8) * run + e) * 8 + g % 8;
-    if (w < order_len) order[w] = (uint32_t)q;
+    const int64_t run = (int64_t)s_biggest * 16 > nq ? GRAB_ORDER_RUN : (nq + parts - 1) / parts;
+    const int64_t t = (int64_t)blockIdx.x * 256 + tid;
+    if (t < order_len) {   // the position that maps to entry t
+        const int64_t i = t / 8, c = t % 8;
+        const int64_t pos = ((i / run) * 8 + c) * run + i % run;
+        if (pos >= nq) order[t] = GRAB_EMPTY;
+    }
+    int bin = -1, local = 0;
+    if (t < nq) {
+        bin = q_bin[t];
+        if (bin < 0 || bin >= nbins) bin = -1;
+        else local = atomicAdd(&cnt[bin], 1);
+    }
+    __syncthreads();
+    for (int i = tid; i < nbins; i += 256)
+        if (cnt[i] > 0) base[i] = atomicAdd(&bin_count[GRAB_BIN_STRIDE * i + 1], cnt[i]);
+    __syncthreads();
+    if (bin >= 0) {
+        const int64_t pos = (int64_t)start[bin] + base[bin] + local;      // position in bucket order
+        if (pos >= 0 && pos < nq) {
+            const int64_t g = pos / run, e = pos % run;
+            const int64_t w = ((g / 8) * run + e) * 8 + g % 8;
+            if (w < order_len) order[w] = (uint32_t)t;
+        }
+    }
+    // every use of the counters above is done: count this workgroup out, the last one clears them
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) last_block = atomicAdd(&bin_count[GRAB_BIN_STRIDE * nbins], 1) == (int)gridDim.x - 1;
+    __syncthreads();
+    if (last_block)
+        for (int i = tid; i <= nbins; i += 256) { bin_count[GRAB_BIN_STRIDE * i] = 0; bin_count[GRAB_BIN_STRIDE * i + 1] = 0; }
 }
 
 // ------------------------------------------------------------------------------- beam search
@@ -598,45 +645,54 @@ grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batc
 int64_t grab_order_len(int64_t nq) { return (nq + 8 * GRAB_ORDER_RUN - 1) / (8 * GRAB_ORDER_RUN) * (8 * GRAB_ORDER_RUN); }
 
 grab_status grab_plan_order(grab_index *ix, SearchLaunch &s) {
-    s.q_bin = s.q_rank = s.bin_count = nullptr;
+    s.q_bin = s.bin_count = nullptr;
     s.order = nullptr;
     s.order_len = 0;
+    s.order_dirty = nullptr;
     if (s.nq < 2048) return GRAB_OK;   // a batch that does not even fill the device once gains nothing
     // room for either run length k_order may choose: nq rounded up to eight short runs
     const int64_t len = grab_order_len(s.nq);
     grab_status st;
     if ((st = grab_reserve(ix, ix->q_bin, (size_t)s.nq * 4)) != GRAB_OK) return st;
-    if ((st = grab_reserve(ix, ix->q_rank, (size_t)s.nq * 4)) != GRAB_OK) return st;
     if ((st = grab_reserve(ix, ix->q_order, (size_t)len * 4)) != GRAB_OK) return st;
-    if ((st = grab_reserve(ix, ix->bin_count, (size_t)(GRAB_MAX_BUCKETS + 1) * 4)) != GRAB_OK) return st;
-    s.q_bin = (int32_t *)ix->q_bin.p; s.q_rank = (int32_t *)ix->q_rank.p; s.bin_count = (int32_t *)ix->bin_count.p;
+    const void *before = ix->bin_count.p;
+    if ((st = grab_reserve(ix, ix->bin_count, GRAB_BIN_BLOCK_BYTES)) != GRAB_OK) return st;
+    if (ix->bin_count.p != before) ix->order_dirty = true;    // fresh memory: counters not yet zero
+    s.q_bin = (int32_t *)ix->q_bin.p; s.bin_count = (int32_t *)ix->bin_count.p;
     s.order = (uint32_t *)ix->q_order.p;
     s.order_len = len;
+    s.order_dirty = &ix->order_dirty;
     return GRAB_OK;
 }
 
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
     if (s.nq == 0) return GRAB_OK;
     const int nbins = ix->B + 1;   // the last bin takes the queries whose range meets no bucket
+    const size_t lds = (size_t)(4 * ix->B + 1) * 4;
     if (s.order) {
-        const int64_t n = s.order_len > nbins ? s.order_len : nbins;
-        k_order_reset<<<dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ix->stream>>>(s.bin_count, nbins, s.order, s.order_len);
-        GRAB_HIP(ix, hipGetLastError());
+        // the counters are left zero by the k_order of the previous call; if that is in doubt
+        // (fresh memory, a launch that failed in between) they are cleared first
+        const bool dirty = !s.order_dirty || *s.order_dirty;
+        if (s.order_dirty) *s.order_dirty = true;
+        if (dirty) {
+            const int words = GRAB_BIN_STRIDE * nbins + 2;
+            k_order_reset<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, ix->stream>>>(s.bin_count, words);
+            GRAB_HIP(ix, hipGetLastError());
+        }
     }
-    k_select_seed<<<dim3((unsigned)s.nq), dim3(64), 0, ix->stream>>>(ix->table, ix->B, ix->attr, s.lo, s.hi, s.only_bucket,
-                                                                    s.n_seeds, s.salt, s.plans, s.seeds);
+    k_select_seed<<<dim3((unsigned)s.nq), dim3(64), lds, ix->stream>>>(ix->table, ix->B, ix->attr, s.lo, s.hi, s.only_bucket,
+                                                                      s.n_seeds, s.salt, s.plans, s.seeds,
+                                                                      s.order ? s.q_bin : nullptr, s.bin_count);
     GRAB_HIP(ix, hipGetLastError());
     if (s.order) {
         // measured: rows of 512 B (1M x 128) run fastest with one run per XCD (headline 481 us against
         // 502 us with four and 516 us in input order); rows of 3,840 B (1M x 960) with four (3.82 ms
         // against 4.06 ms with one and 4.19 ms in input order)
-        k_order_bin<<<dim3((unsigned)((s.nq + 255) / 256)), dim3(256), 0, ix->stream>>>(ix->table, ix->B, s.lo, s.hi, s.only_bucket,
-                                                                                     s.nq, s.q_bin, s.q_rank, s.bin_count);
+        k_order<<<dim3((unsigned)((s.order_len + 255) / 256)), dim3(256), 0, ix->stream>>>(s.q_bin, s.bin_count, nbins, s.nq,
+                                                                                        s.order, s.order_len,
+                                                                                        ix->dim >= 512 ? 4 : 1);
         GRAB_HIP(ix, hipGetLastError());
-        k_order<<<dim3((unsigned)((s.nq + 63) / 64)), dim3(64), 0, ix->stream>>>(s.q_bin, s.q_rank, s.bin_count, nbins, s.nq,
-                                                                              s.order, s.order_len,
-                                                                              ix->dim >= 512 ? 4 : 1);
-        GRAB_HIP(ix, hipGetLastError());
+        if (s.order_dirty) *s.order_dirty = false;
     }
     return GRAB_OK;
 }
