@@ -69,6 +69,11 @@ def main():
     ap.add_argument("--rewire-from-targets", action="store_true",
                     help="remote mode 1: construct by target bucket first (mode 0), then rewrite the remote parts with grab_build_remote "
                          "under mode 1, whose candidate searches then run over a graph that already has cross-bucket edges")
+    ap.add_argument("--batch-size", type=int, default=0,
+                    help="issue the workload's queries in consecutive calls of this many (Section 5.1 evaluates in batches of 100); "
+                         "0: one call for all of them.  A step is still one pass over all queries")
+    ap.add_argument("--batch-curve", action="store_true",
+                    help="also time single calls of 64 ... 40,000 queries at the chosen setting (reported as batch_curve)")
     ap.add_argument("--rounds", type=int, default=0, help="dynamic workload: stop after this many appends (0: all)")
     ap.add_argument("--holdout-stream", type=int, default=101, help="query stream of the recall check on fresh queries")
     ap.add_argument("--parity", action="store_true", help="dynamic workload: compare the whole index and one search batch with the oracle after every append")
@@ -189,8 +194,15 @@ def main():
         ix.set_param("search_width", w)
         return beam
 
+    bs = args.batch_size if 0 < args.batch_size < nq else 0
+
     def run_once(beam):
-        ix.search_range(qd, lod, hid, k, beam, ids, dist)
+        if not bs:
+            ix.search_range(qd, lod, hid, k, beam, ids, dist)
+            return
+        for s0 in range(0, nq, bs):
+            e0 = min(nq, s0 + bs)
+            ix.search_range(qd[s0:e0], lod[s0:e0], hid[s0:e0], k, beam, ids[s0:e0], dist[s0:e0])
 
     def timed(beam, reps):
         run_once(beam)
@@ -246,12 +258,33 @@ def main():
     ix.set_param("profile", 1)
     beam_ms, select_ms = [], []
     for _ in range(max(5, min(args.steps, 20))):
-        run_once(beam)
+        ix.search_range(qd, lod, hid, k, beam, ids, dist)      # one call for the whole batch: the kernel's own rate
         s_ms, b_ms = ix.get_timing()
         select_ms.append(s_ms)
         beam_ms.append(b_ms)
     ix.set_param("profile", 0)
     ctr = ix.get_counters(nq).astype(np.float64)
+    # ---- single calls of other sizes at the chosen setting (queries of the same stream, cycled)
+    curve = None
+    if args.batch_curve:
+        curve = []
+        for n_b in (64, 100, 256, 1024, 2048, 4096, 10000, 20000, 40000):
+            sel = torch.arange(n_b, device=dev) % nq
+            qb, lob, hib = qd[sel].contiguous(), lod[sel].contiguous(), hid[sel].contiguous()
+            idb = torch.empty((n_b, k), dtype=torch.int32, device=dev)
+            dib = torch.empty((n_b, k), dtype=torch.float32, device=dev)
+            for _ in range(3):
+                ix.search_range(qb, lob, hib, k, beam, idb, dib)
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            reps = 30
+            for _ in range(reps):
+                ix.search_range(qb, lob, hib, k, beam, idb, dib)
+            torch.cuda.synchronize()
+            us = (time.perf_counter() - t) / reps * 1e6
+            curve.append({"queries": n_b, "us_per_call": round(us, 1), "queries_per_s": round(n_b / us * 1e6, 0)})
+        ix.search_range(qd, lod, hid, k, beam, ids, dist)      # counters and outputs of the full batch again
+        torch.cuda.synchronize()
     # algorithmic bytes per query: query row + one feature row per distance evaluation (seeds
     # included) + one adjacency row per expanded parent + 4 B per tail attribute read + output
     row = cfg.dim * 4
@@ -349,10 +382,11 @@ def main():
                    "beam": chosen[0], "n_seeds": chosen[1], "search_width": chosen[2], "visited_cap": max(chosen[3], chosen[1]),
                    "max_iter": (chosen[4] if len(chosen) > 4 and chosen[4] > 0 else 2 * chosen[0]),
                    "recall_at_10": None if chosen_recall is None else round(chosen_recall, 4),
-                   "recall_at_10_holdout": holdout, "graph": args.graph, "remote_mode": args.remote_mode},
+                   "recall_at_10_holdout": holdout, "graph": args.graph, "remote_mode": args.remote_mode,
+                   "batch_size": bs or nq},
         "roofline": roofline, "cpu_baseline": cpu, "parity_vs_oracle": parity, "build": build,
         # every swept setting: [beam, n_seeds, search_width, visited_cap, max_iter (0 = 2 x beam), recall@10, queries/s]
-        "sweep": sweep,
+        "sweep": sweep, "batch_curve": curve,
         "hbm_frac_of_peak": round(achieved / PEAK_HBM_GBS, 4),
     }
     ix.close()
