@@ -9,6 +9,9 @@
 #include <cstring>
 
 #include <rocprim/device/device_radix_sort.hpp>
+#include <rocprim/device/device_select.hpp>
+#include <rocprim/iterator/counting_iterator.hpp>
+#include <rocprim/iterator/transform_iterator.hpp>
 
 #include "grab_device.h"
 
@@ -435,10 +438,10 @@ struct RewireArgs {
     uint32_t *A;
     const int32_t *table;
     const u64 *key1s;       // sorted (target << 1 | kind); ~0 for "no request"
-    const uint32_t *order;  // request index at each sorted position
-    const u64 *key2;        // by request index: distance image << 32 | source slot
-    const float *reqd;      // by request index: dist(target, source)
+    const uint4 *rec;       // by sorted position: {source slot, dist(target, source) bits, source bucket, source attribute}
+    const u64 *heads;       // per (target, kind) group, in sorted order: position of its first request << 32 | key; one workgroup each
     int64_t nreq;
+    uint32_t n_heads;
     int32_t kl, kr, metric, B;
     float a;                // alpha squared: the bias acts on squared distances (see bias_base)
     // proximal / global reading of the remote part (mode 1)
@@ -457,158 +460,282 @@ __device__ __forceinline__ int bucket_of_slot_dev(const int32_t *__restrict__ ta
     return l;
 }
 
+// sorted position -> (position << 32 | key): what a group head is listed as, so that the wavefront
+// of a group knows its target before it has read anything else
+struct HeadEntry {
+    const u64 *key1s;
+    __host__ __device__ u64 operator()(uint32_t p) const { return ((u64)p << 32) | (key1s[p] & 0xFFFFFFFFull); }
+};
+
+// Bucket of a slot (the same slot in every lane): the last bucket whose slab base is <= slot,
+// counted 64 buckets at a time, one base per lane
+__device__ __forceinline__ int wave_bucket_of(const int32_t *__restrict__ table, int32_t B, uint32_t slot, int lane) {
+    int c = 0;
+    for (int b0 = 0; b0 < B; b0 += 64)
+        c += __popcll(__ballot(b0 + lane < B && (uint32_t)table[T_COLS * (b0 + lane) + T_BASE] <= slot));
+    return c - 1;
+}
+
+// what the rewiring needs of each request, in sorted order, so that a group finds its requests
+// without chasing the sort permutation: source slot, distance, bucket and attribute of the source
+// (a new object: request index / K is its position in the batch); marks the group heads
+__global__ void k_request_records(const u64 *__restrict__ key1s, const uint32_t *__restrict__ order, const u64 *__restrict__ key2,
+                                  const float *__restrict__ reqd, const int32_t *__restrict__ bucket,
+                                  const int32_t *__restrict__ new_attr, int32_t K, int64_t nreq, uint4 *__restrict__ rec,
+                                  unsigned char *__restrict__ head) {
+    const int64_t p = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    if (p >= nreq) return;
+    const u64 key = key1s[p];
+    head[p] = key != ~0ull && (p == 0 || key1s[p - 1] != key);
+    if (key == ~0ull) return;
+    const uint32_t ridx = order[p];
+    const uint32_t i = ridx / (uint32_t)K;
+    rec[p] = make_uint4((uint32_t)(key2[ridx] & 0xFFFFFFFFull), __float_as_uint(reqd[ridx]), (uint32_t)bucket[i], (uint32_t)new_attr[i]);
+}
+
+// Lane, among those with `in` set (at least one), whose (image, slot) pair is the largest; every
+// lane returns it.  Two 32-bit reductions: the largest image first, the slot only among its ties.
+__device__ __forceinline__ int farthest_lane(bool in, uint32_t image, uint32_t slot, int lane) {
+    const uint32_t m = wave_max_u32(in ? image : 0u, lane);
+    u64 tie = __ballot(in && image == m);
+    if (__popcll(tie) > 1) {
+        const uint32_t sm = wave_max_u32(in && image == m ? slot : 0u, lane);
+        tie = __ballot(in && image == m && slot == sm);
+    }
+    return __ffsll((long long)tie) - 1;
+}
+
+// requests of a local group evaluated per pass over the target's neighbour rows (the target itself
+// rides along in the first pass); bounded by the LDS the staged query rows take
+template <int NCH>
+struct RewireShape {
+    static constexpr int G = NCH <= 4 ? 5 : (NCH <= 8 ? 3 : (NCH <= 32 ? 2 : 1));
+};
+
 // Reverse rewiring (Section 4.4 step 3): the wavefront that sits on the first request of a
 // (target, kind) group applies the whole group in order.
 // Local kind: Eq. 2 with Eq. 3's effective distance decides whether the newcomer may enter; it
 // then fills an empty entry or overwrites, among the entries it points to itself, the one
-// farthest from the target (the target still reaches it through the newcomer).  Remote kind: the entry of the target's remote part that lies in the newcomer's
-// bucket is overwritten iff the newcomer's biased distance to the target is smaller.
+// farthest from the target (the target still reaches it through the newcomer).  The rows of the
+// target's neighbours are read once per pass: the target and up to G requesting nodes are staged in
+// LDS and all their distances to those rows are taken while the rows sit in registers; an entry
+// rewritten by an earlier request of the same pass is a new node whose row is staged too, so the
+// later requests get their distance to it from LDS.  Remote kind: the entry of the target's remote
+// part that lies in the newcomer's bucket is overwritten iff the newcomer's biased distance to the
+// target is smaller.
 template <int NCH>
 __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
-    constexpr int D = NCH * 32;
+    constexpr int D = NCH * 32, D4 = NCH * 8, G = RewireShape<NCH>::G;
+    constexpr bool WHOLE = EvalShape<NCH>::CB == NCH;   // a whole row fits the register batch
     const int lane = threadIdx.x;
-    // one wavefront per sorted position; only the one on the first request of a group works.  (A
-    // wavefront that walks a stretch of positions and applies the groups starting in it one after
-    // another was slower, 8.7 ms against 6.6 ms per 100,000 objects: a group is a chain of
-    // dependent memory round trips, and many short-lived wavefronts overlap those chains better.)
-    const int64_t p0 = blockIdx.x;
-    const u64 key = a.key1s[p0];
-    if (key == ~0ull) return;
-    if (p0 > 0 && a.key1s[p0 - 1] == key) return;
+    // one wavefront per (target, kind) group, which it applies in order
+    const u64 head = a.heads[blockIdx.x];
+    const int64_t p0 = (int64_t)(head >> 32);
+    const u64 key = head & 0xFFFFFFFFull;
+    // the first 64 positions from the head on (requests of the group are contiguous)
+    int64_t pp = p0 + lane;
+    bool mine_req = pp < a.nreq && a.key1s[pp] == key;
+    uint4 rc = pp < a.nreq ? a.rec[pp] : make_uint4(0u, 0u, 0u, 0u);
     unsigned st_applied = 0, st_pass = 0;
-    {
     const uint32_t v = (uint32_t)(key >> 1);
     const int kind = (int)(key & 1ull);
     const int K = a.kl + a.kr, off = kind ? a.kl : 0, len = kind ? a.kr : a.kl;
     uint32_t *R = reinterpret_cast<uint32_t *>(smem);   // current part of v's row
     uint32_t *Rl = R + 64;                                // same with empty entries pointing at row 0
-    float *dq = reinterpret_cast<float *>(Rl + 64);       // local: dist(q, R[j]); remote: dist(v, R[j])
-    uint32_t *qrow = reinterpret_cast<uint32_t *>(dq + 64);  // the requesting node's own row
-    float *dv = reinterpret_cast<float *>(qrow + 128);       // local: dist(v, R[j])
-    float *qlds = dv + 64;
-    float4 qreg[EvalShape<NCH>::QREG ? NCH : 1];
+    float *Dall = reinterpret_cast<float *>(Rl + 64);     // [0]: dist(v, R[j]); [1 + k]: dist(request k of the pass, R[j])
+    uint32_t *qrow = reinterpret_cast<uint32_t *>(Dall + (G + 1) * 64);   // the requesting nodes' own rows, 128 entries each
+    uint32_t *rq = qrow + G * 128;                        // sources of up to 64 requests of the group,
+    float *rd = reinterpret_cast<float *>(rq + 64);       // their distances to v,
+    int32_t *rb = reinterpret_cast<int32_t *>(rd + 64);   // their buckets
+    int32_t *ra = rb + 64;                                // and attributes
+    float *qs = reinterpret_cast<float *>(ra + 64);       // staged rows: v, then the requesting nodes of the pass
+    float *dq = Dall;   // remote kind: dist(v, R[j])
     if (lane < len) {
         uint32_t e = a.A[(size_t)v * K + off + lane];
         R[lane] = e;
         Rl[lane] = e == GRAB_EMPTY ? 0u : e;
     }
-    __syncthreads();
     bool changed = false;
     if (kind == 1) {
-        load_query<NCH>(a.X + (size_t)v * D, qreg, qlds, lane);
-        if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-        eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);   // dist(v, R[j])
         __syncthreads();
-        const int bv = a.mode == 1 ? bucket_of_slot_dev(a.table, a.B, v) : 0;
+        for (int t = lane; t < D4; t += 64) reinterpret_cast<float4 *>(qs)[t] = reinterpret_cast<const float4 *>(a.X)[(size_t)v * D4 + t];
+        __syncthreads();
+        if (len <= 8) eval_rows_few<NCH>(a.X, qs, Rl, len, lane, a.metric, Dall);   // dist(v, R[j])
+        else eval_rows_multi<NCH, 1>(a.X, qs, 1u, Rl, 0, len, lane, a.metric, Dall);
         const int32_t attr_v = a.mode == 1 ? a.attr[v] : 0;
-        for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
-            const uint32_t ridx = a.order[p];
-            const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
-            const float dvq = a.reqd[ridx];
-            const float lhs = a.a * bias_base(dvq, a.metric);
-            const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
-            int at = -1;
-            if (a.mode == 1) {
-                // q competes for the positions of its class; an empty one or one holding a node of
-                // v's own bucket (a redundant local edge) is taken at once, else the farthest gives way
-                long long diff = (long long)a.attr[q] - (long long)attr_v;
-                if (diff < 0) diff = -diff;
-                const int j0 = diff <= a.window ? 0 : a.kp, j1 = diff <= a.window ? a.kp : len;
-                const bool inc = lane >= j0 && lane < j1;
-                const u64 free_m = __ballot(inc && (mine == GRAB_EMPTY || bucket_of_slot_dev(a.table, a.B, mine) == bv));
-                if (free_m) {
-                    at = __ffsll((long long)free_m) - 1;
-                } else if (j1 > j0) {
-                    u64 kf = inc ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : 0ull;
-                    u64 kmax = kf;
-#pragma unroll
-                    for (int s = 32; s > 0; s >>= 1) {
-                        uint32_t hi = __shfl_xor((uint32_t)(kmax >> 32), s), lo = __shfl_xor((uint32_t)kmax, s);
-                        u64 other = ((u64)hi << 32) | lo;
-                        kmax = other > kmax ? other : kmax;
-                    }
-                    const int far = __ffsll((long long)__ballot(inc && kf == kmax)) - 1;
-                    if (lhs < bias_base(dq[far], a.metric)) at = far;
-                }
-            } else {
-            const int bq = bucket_of_slot_dev(a.table, a.B, q);
-            const bool inb = mine != GRAB_EMPTY && bucket_of_slot_dev(a.table, a.B, mine) == bq;
-            if (__ballot(inb)) {
-                u64 kf = inb ? (((u64)dist_image(dq[lane]) << 32) | (u64)mine) : 0ull;
-                u64 kmax = kf;
-#pragma unroll
-                for (int s = 32; s > 0; s >>= 1) {
-                    uint32_t hi = __shfl_xor((uint32_t)(kmax >> 32), s), lo = __shfl_xor((uint32_t)kmax, s);
-                    u64 other = ((u64)hi << 32) | lo;
-                    kmax = other > kmax ? other : kmax;
-                }
-                const int far = __ffsll((long long)__ballot(inb && kf == kmax)) - 1;
-                if (lhs < bias_base(dq[far], a.metric)) at = far;
-            } else {
-                const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
-                if (empties) at = __ffsll((long long)empties) - 1;
-            }
-            }
-            __syncthreads();
-            if (at >= 0) {
-                if (lane == at) { R[at] = q; Rl[at] = q; dq[at] = dvq; }
-                changed = true;
-                ++st_applied;
-            }
-            __syncthreads();
+        // bucket of the entry this lane looks after; a rewritten entry takes its source's
+        uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
+        const int bv = a.mode == 1 ? wave_bucket_of(a.table, a.B, v, lane) : 0;
+        int bmine = -1;
+        for (int j = 0; j < len; ++j) {
+            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)mine, j);
+            const int be = e != GRAB_EMPTY ? wave_bucket_of(a.table, a.B, e, lane) : -1;
+            if (lane == j) bmine = be;
         }
-    } else {
-        load_query<NCH>(a.X + (size_t)v * D, qreg, qlds, lane);
-        if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-        eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dv);   // dist(v, R[j]), kept current below
         __syncthreads();
-        for (int64_t p = p0; p < a.nreq && a.key1s[p] == key; ++p) {
-            const uint32_t ridx = a.order[p];
-            const uint32_t q = (uint32_t)(a.key2[ridx] & 0xFFFFFFFFull);
-            const float dvq = a.reqd[ridx];
-            const float lhs = a.a * bias_base(dvq, a.metric);
-            for (int x = lane; x < K; x += 64) qrow[x] = a.A[(size_t)q * K + x];
-            load_query<NCH>(a.X + (size_t)q * D, qreg, qlds, lane);
-            if constexpr (!EvalShape<NCH>::QREG) __syncthreads();
-            eval_rows<NCH>(a.X, qreg, qlds, Rl, len, lane, a.metric, dq);
+        for (;;) {
+            const u64 same = __ballot(mine_req);
+            const int gp = same == ~0ull ? 64 : __ffsll((long long)~same) - 1;
+            if (gp == 0) break;
+            if (lane < gp) { rq[lane] = rc.x; rd[lane] = __uint_as_float(rc.y); rb[lane] = (int32_t)rc.z; ra[lane] = (int32_t)rc.w; }
             __syncthreads();
-            const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
-            const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < bias_base(dq[lane], a.metric));
-            if (__ballot(blocked) == 0) {
-                ++st_pass;
-                const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+            for (int t = 0; t < gp; ++t) {
+                const uint32_t q = rq[t];
+                const float dvq = rd[t];
+                const float lhs = a.a * bias_base(dvq, a.metric);
                 int at = -1;
-                if (empties) {
-                    at = __ffsll((long long)empties) - 1;
-                } else {
-                    // victim: among the entries q points to itself (v still reaches them through q),
-                    // the one farthest from v (ties: smaller slot)
-                    bool covered = false;
-                    if (lane < len)
-                        for (int x = 0; x < K; ++x) covered |= qrow[x] == mine;
-                    u64 kf = covered ? (((u64)(~dist_image(dv[lane])) << 32) | (u64)mine) : ~0ull;
-                    u64 kmin = kf;
-#pragma unroll
-                    for (int s = 32; s > 0; s >>= 1) {
-                        uint32_t hi = __shfl_xor((uint32_t)(kmin >> 32), s), lo = __shfl_xor((uint32_t)kmin, s);
-                        u64 other = ((u64)hi << 32) | lo;
-                        kmin = other < kmin ? other : kmin;
+                if (a.mode == 1) {
+                    // q competes for the positions of its class; an empty one or one holding a node of
+                    // v's own bucket (a redundant local edge) is taken at once, else the farthest gives way
+                    long long diff = (long long)ra[t] - (long long)attr_v;
+                    if (diff < 0) diff = -diff;
+                    const int j0 = diff <= a.window ? 0 : a.kp, j1 = diff <= a.window ? a.kp : len;
+                    const bool inc = lane >= j0 && lane < j1;
+                    const u64 free_m = __ballot(inc && (mine == GRAB_EMPTY || bmine == bv));
+                    if (free_m) {
+                        at = __ffsll((long long)free_m) - 1;
+                    } else if (j1 > j0) {
+                        const int far = farthest_lane(inc, dist_image(dq[lane]), mine, lane);
+                        if (lhs < bias_base(dq[far], a.metric)) at = far;
                     }
-                    if (kmin != ~0ull) at = __ffsll((long long)__ballot(covered && kf == kmin)) - 1;
+                } else {
+                    const int bq = rb[t];
+                    const bool inb = mine != GRAB_EMPTY && bmine == bq;
+                    if (__ballot(inb)) {
+                        const int far = farthest_lane(inb, dist_image(dq[lane]), mine, lane);
+                        if (lhs < bias_base(dq[far], a.metric)) at = far;
+                    } else {
+                        const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+                        if (empties) at = __ffsll((long long)empties) - 1;
+                    }
                 }
                 __syncthreads();
                 if (at >= 0) {
-                    if (lane == at) { R[at] = q; Rl[at] = q; dv[at] = dvq; }
+                    if (lane == at) { R[at] = q; dq[at] = dvq; mine = q; bmine = rb[t]; }
                     changed = true;
                     ++st_applied;
                 }
+                __syncthreads();
             }
+            if (gp < 64) break;
+            pp += 64;
+            mine_req = pp < a.nreq && a.key1s[pp] == key;
+            rc = pp < a.nreq ? a.rec[pp] : make_uint4(0u, 0u, 0u, 0u);
+        }
+    } else {
+        const float4 *X4 = reinterpret_cast<const float4 *>(a.X);
+        float4 *qs4 = reinterpret_cast<float4 *>(qs);
+        const int sub = lane & 7, grp = lane >> 3;
+        const int K8 = (K + 7) & ~7;
+        bool first = true;
+        __syncthreads();
+        for (;;) {
+            // up to 64 requests of the group
+            const u64 same = __ballot(mine_req);
+            const int gp = same == ~0ull ? 64 : __ffsll((long long)~same) - 1;
+            if (gp == 0) break;
+            if (lane < gp) { rq[lane] = rc.x; rd[lane] = __uint_as_float(rc.y); }
             __syncthreads();
+            for (int c0 = 0; c0 < gp; c0 += G) {
+                const int ng = min(G, gp - c0);
+                const unsigned qmask = (first ? 1u : 0u) | (((1u << ng) - 1u) << 1);
+                // the neighbour rows are on their way while the query rows are staged
+                RowRegs<NCH> rr;
+                if constexpr (WHOLE) {
+                    rows_pick<NCH>(Rl, 0, len, lane, rr);
+                    rows_issue<NCH>(a.X, 0, lane, rr);
+                }
+                for (int t = lane; t < (G + 1) * D4; t += 64) {
+                    const int g = t / D4, c = t - g * D4;
+                    if ((qmask >> g) & 1u) qs4[t] = X4[(size_t)(g == 0 ? v : rq[c0 + g - 1]) * D4 + c];
+                }
+                // the requesting nodes' rows, padded to whole groups of eight entries with a value no slot has
+                for (int k = 0; k < ng; ++k)
+                    for (int x = lane; x < K8; x += 64)
+                        qrow[k * 128 + x] = x < K ? a.A[(size_t)rq[c0 + k] * K + x] : 0xFFFFFFFEu;
+                __syncthreads();
+                if constexpr (WHOLE) {
+                    float acc[G + 1][EvalShape<NCH>::R];
+#pragma unroll
+                    for (int g = 0; g <= G; ++g)
+#pragma unroll
+                        for (int r = 0; r < EvalShape<NCH>::R; ++r) acc[g][r] = 0.0f;
+                    rows_fma<NCH, G + 1>(rr, qs, qmask, 0, lane, a.metric, acc);
+                    rows_store<NCH, G + 1>(rr, acc, qmask, 0, lane, a.metric, Dall);
+                    eval_rows_multi<NCH, G + 1>(a.X, qs, qmask, Rl, 8 * EvalShape<NCH>::R, len, lane, a.metric, Dall);
+                } else {
+                    eval_rows_multi<NCH, G + 1>(a.X, qs, qmask, Rl, 0, len, lane, a.metric, Dall);
+                }
+                __syncthreads();
+                first = false;
+                for (int k = 0; k < ng; ++k) {
+                    const uint32_t q = rq[c0 + k];
+                    const float dvq = rd[c0 + k];
+                    const float lhs = a.a * bias_base(dvq, a.metric);
+                    const uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
+                    const float dql = Dall[(1 + k) * 64 + lane], dvl = Dall[lane];
+                    const bool blocked = lane < len && mine != GRAB_EMPTY && !(lhs < bias_base(dql, a.metric));
+                    int at = -1;
+                    if (__ballot(blocked) == 0) {
+                        ++st_pass;
+                        const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+                        if (empties) {
+                            at = __ffsll((long long)empties) - 1;
+                        } else {
+                            // victim: among the entries q points to itself (v still reaches them through q),
+                            // the one farthest from v (ties: smaller slot)
+                            bool covered = false;
+                            if (len <= 32) {
+                                // two lanes per entry, each compares it with one half of q's row
+                                const uint32_t e = (lane & 31) < len ? R[lane & 31] : GRAB_EMPTY;
+                                const uint4 *h4 = reinterpret_cast<const uint4 *>(qrow + k * 128) + (lane >> 5) * (K8 >> 3);
+                                bool c = false;
+                                for (int x = 0; x < (K8 >> 3); ++x) {
+                                    const uint4 w = h4[x];
+                                    c |= w.x == e || w.y == e || w.z == e || w.w == e;
+                                }
+                                const u64 cm = __ballot(c);
+                                covered = lane < len && (((cm | (cm >> 32)) >> lane) & 1ull);
+                            } else if (lane < len) {
+                                for (int x = 0; x < K; ++x) covered |= qrow[k * 128 + x] == mine;
+                            }
+                            if (__ballot(covered)) {
+                                // farthest from v, ties to the smaller slot
+                                const uint32_t img = dist_image(dvl);
+                                const uint32_t m = wave_max_u32(covered ? img : 0u, lane);
+                                u64 tie = __ballot(covered && img == m);
+                                if (__popcll(tie) > 1) {
+                                    const uint32_t sm = wave_min_u32(covered && img == m ? mine : GRAB_EMPTY, lane);
+                                    tie = __ballot(covered && img == m && mine == sm);
+                                }
+                                at = __ffsll((long long)tie) - 1;
+                            }
+                        }
+                    }
+                    __syncthreads();
+                    if (at >= 0) {
+                        if (lane == at) { R[at] = q; Rl[at] = q; Dall[at] = dvq; }
+                        // entry `at` now holds q: the later requests of this pass take their distance to it
+                        // from the staged rows, one request per group of eight lanes
+                        const int kk = k + 1 + grp;
+                        if (kk < ng) {
+                            const float d = dist_lds_rows<NCH>(qs + (size_t)(1 + kk) * D, qs + (size_t)(1 + k) * D, lane, a.metric);
+                            if (sub == 0) Dall[(1 + kk) * 64 + at] = d;
+                        }
+                        changed = true;
+                        ++st_applied;
+                    }
+                    __syncthreads();
+                }
+            }
+            if (gp < 64) break;
+            pp += 64;
+            mine_req = pp < a.nreq && a.key1s[pp] == key;
+            rc = pp < a.nreq ? a.rec[pp] : make_uint4(0u, 0u, 0u, 0u);
         }
     }
     if (changed && lane < len) a.A[(size_t)v * K + off + lane] = R[lane];
-    }
     if (lane == 0) a.grp_out[p0] = st_applied | (st_pass << 16);
 }
 
@@ -655,8 +782,9 @@ grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireAr
         size_t lds = (size_t)f.beam * 16 + 64 * 4 * 9 + (size_t)((2 * f.beam + 3) & ~3) * 4 + qbytes;
         k_forward<NCH><<<dim3((unsigned)((m + 7) / 8 * 8)), dim3(64), lds, ix->stream>>>(f);
     } else {
-        size_t lds = 64 * 4 * 4 + 128 * 4 + qbytes;
-        k_rewire<NCH><<<dim3((unsigned)r.nreq), dim3(64), lds, ix->stream>>>(r);
+        constexpr int G = RewireShape<NCH>::G;
+        size_t lds = 64 * 4 * (2 + (G + 1) + 4) + (size_t)G * 128 * 4 + (size_t)(G + 1) * ix->dim * 4;
+        if (r.n_heads > 0) k_rewire<NCH><<<dim3(r.n_heads), dim3(64), lds, ix->stream>>>(r);
     }
     GRAB_HIP(ix, hipGetLastError());
     return GRAB_OK;
@@ -683,7 +811,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     const int64_t nreq = m * K;
     grab_status rc;
     // ---- arena
-    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_CG_S, A_CG_D, A_SCOPE, A_NODE_OUT, A_GRP_OUT, A_N };
+    enum { A_BUCKET, A_KEYS, A_IDX, A_KEYS_S, A_IDX_S, A_STARTS, A_COUNTS, A_SLOT, A_LO, A_HI, A_CL_S, A_CL_D, A_KEY1, A_KEY2, A_REQD, A_ORD0, A_ORD1, A_ORD2, A_K2S, A_K1G, A_K1S, A_TMP, A_CG_S, A_CG_D, A_SCOPE, A_NODE_OUT, A_GRP_OUT, A_REC, A_HEAD, A_HEADS, A_NHEADS, A_N };
     size_t need[A_N];
     for (size_t &x : need) x = 0;
     need[A_BUCKET] = need[A_KEYS] = need[A_IDX] = need[A_KEYS_S] = need[A_IDX_S] = need[A_SLOT] = need[A_LO] = need[A_HI] = (size_t)m * 4;
@@ -691,6 +819,10 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     need[A_CL_S] = need[A_CL_D] = (size_t)m * beam * 4;
     need[A_NODE_OUT] = (size_t)m * 8;
     need[A_GRP_OUT] = (size_t)nreq * 4;
+    need[A_HEADS] = (size_t)nreq * 8;
+    need[A_REC] = (size_t)nreq * 16;
+    need[A_HEAD] = (size_t)nreq;
+    need[A_NHEADS] = 16;
     const RemoteRule rule = grab_remote_rule(ix, kr);
     if (rule.mode == 1) {
         need[A_CG_S] = need[A_CG_D] = (size_t)m * beam * 4;
@@ -703,7 +835,12 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
                                            (uint32_t *)nullptr, (size_t)m, 0, 32, st));
     GRAB_HIP(ix, rocprim::radix_sort_pairs(nullptr, tmp2, (u64 *)nullptr, (u64 *)nullptr, (uint32_t *)nullptr,
                                            (uint32_t *)nullptr, (size_t)nreq, 0, 64, st));
-    need[A_TMP] = (tmp1 > tmp2 ? tmp1 : tmp2) + 16;
+    size_t tmp3 = 0;
+    if (nreq >= (int64_t)1 << 31) return grab_fail(ix, GRAB_EINVAL, "batch of %lld objects is too large for one call", (long long)m);
+    typedef rocprim::transform_iterator<rocprim::counting_iterator<uint32_t>, HeadEntry, u64> HeadIt;
+    GRAB_HIP(ix, rocprim::select(nullptr, tmp3, HeadIt(rocprim::counting_iterator<uint32_t>(0), HeadEntry{nullptr}), (unsigned char *)nullptr,
+                                 (u64 *)nullptr, (uint32_t *)nullptr, (size_t)nreq, st));
+    need[A_TMP] = (tmp1 > tmp2 ? (tmp1 > tmp3 ? tmp1 : tmp3) : (tmp2 > tmp3 ? tmp2 : tmp3)) + 16;
     if ((int)ix->app.size() < A_N) ix->app.resize(A_N);
     for (int i = 0; i < A_N; ++i)
         if ((rc = grab_reserve(ix, ix->app[i], need[i])) != GRAB_OK) return rc;
@@ -786,10 +923,20 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp2, (u64 *)P(A_KEY2), (u64 *)P(A_K2S), (uint32_t *)P(A_ORD0),
                                            (uint32_t *)P(A_ORD1), (size_t)nreq, 0, 64, st));
     k_gather_u64<<<blocks_for(nreq), TPB, 0, st>>>((const u64 *)P(A_KEY1), (const uint32_t *)P(A_ORD1), nreq, (u64 *)P(A_K1G));
+    // (target << 1 | kind) takes 33 bits; the "no request" key has them all set and sorts last
     GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp2, (u64 *)P(A_K1G), (u64 *)P(A_K1S), (uint32_t *)P(A_ORD1),
-                                           (uint32_t *)P(A_ORD2), (size_t)nreq, 0, 64, st));
-    r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.order = (const uint32_t *)P(A_ORD2);
-    r.key2 = (const u64 *)P(A_KEY2); r.reqd = (const float *)P(A_REQD); r.nreq = nreq;
+                                           (uint32_t *)P(A_ORD2), (size_t)nreq, 0, 33, st));
+    // per sorted position what the rewiring needs of the request; the positions where a group starts
+    k_request_records<<<blocks_for(nreq), TPB, 0, st>>>((const u64 *)P(A_K1S), (const uint32_t *)P(A_ORD2), (const u64 *)P(A_KEY2),
+                                                        (const float *)P(A_REQD), bucket, d_attrs, K, nreq, (uint4 *)P(A_REC),
+                                                        (unsigned char *)P(A_HEAD));
+    GRAB_HIP(ix, rocprim::select(P(A_TMP), tmp3, HeadIt(rocprim::counting_iterator<uint32_t>(0), HeadEntry{(const u64 *)P(A_K1S)}),
+                                 (unsigned char *)P(A_HEAD), (u64 *)P(A_HEADS), (uint32_t *)P(A_NHEADS), (size_t)nreq, st));
+    uint32_t n_heads = 0;
+    GRAB_HIP(ix, hipMemcpyAsync(&n_heads, P(A_NHEADS), 4, hipMemcpyDeviceToHost, st));
+    GRAB_HIP(ix, hipStreamSynchronize(st));
+    r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.rec = (const uint4 *)P(A_REC);
+    r.heads = (const u64 *)P(A_HEADS); r.n_heads = n_heads; r.nreq = nreq;
     r.kl = kl; r.kr = kr; r.metric = ix->metric; r.table = ix->table; r.B = B;
     r.mode = rule.mode; r.kp = rule.n_proximal; r.window = rule.window; r.attr = ix->attr; r.grp_out = (uint32_t *)P(A_GRP_OUT);
     r.a = ix->prm.alpha * ix->prm.alpha;

@@ -65,6 +65,19 @@ __device__ __forceinline__ u64 shfl_xor64(u64 k, int m) {
     return ((u64)(uint32_t)__shfl_xor((int)(k >> 32), m) << 32) | (u64)(uint32_t)__shfl_xor((int)(k & 0xFFFFFFFFull), m);
 }
 
+// maximum / minimum over the wavefront, in every lane, by lane exchanges that stay out of LDS
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t x, int lane) {
+    uint32_t o;
+    o = xchg32<1>(x, lane); x = x > o ? x : o;
+    o = xchg32<2>(x, lane); x = x > o ? x : o;
+    o = xchg32<4>(x, lane); x = x > o ? x : o;
+    o = xchg32<8>(x, lane); x = x > o ? x : o;
+    o = xchg32<16>(x, lane); x = x > o ? x : o;
+    o = xchg32<32>(x, lane); x = x > o ? x : o;
+    return x;
+}
+__device__ __forceinline__ uint32_t wave_min_u32(uint32_t x, int lane) { return ~wave_max_u32(~x, lane); }
+
 // value of lane (lane ^ (K-1)): the mirror image inside aligned blocks of K lanes
 template <int K>
 __device__ __forceinline__ uint32_t mirror32(uint32_t x, int lane) {
@@ -255,6 +268,178 @@ __device__ __forceinline__ void eval_rows(const float *__restrict__ X, const flo
         for (int r = 0; r < R; ++r)
             if (act[r] && (lane & 7) == 0) dist_out[base + r * 8 + (lane >> 3)] = s[r];
     }
+}
+
+// Distances of slots to up to G query rows at once: the rows are read once and every query
+// (qs[g][dim] in LDS, used iff bit g of qmask is set) is applied to them while they sit in
+// registers, each (query, row) pair in the summation order of eval_batch.  The three steps are
+// separate so that a caller can issue the row loads before its query rows have reached LDS.
+template <int NCH>
+struct RowRegs {
+    float4 buf[EvalShape<NCH>::R][EvalShape<NCH>::CB];
+    uint32_t v[EvalShape<NCH>::R];
+    bool act[EvalShape<NCH>::R];
+};
+// which rows this lane group takes in the batch that starts at L[base]
+template <int NCH>
+__device__ __forceinline__ void rows_pick(const uint32_t *L, int base, int n, int lane, RowRegs<NCH> &rr) {
+#pragma unroll
+    for (int r = 0; r < EvalShape<NCH>::R; ++r) {
+        const int idx = base + r * 8 + (lane >> 3);
+        rr.act[r] = idx < n;
+        rr.v[r] = rr.act[r] ? L[idx] : 0u;
+    }
+}
+// loads pieces c0 .. c0 + CB of those rows
+template <int NCH>
+__device__ __forceinline__ void rows_issue(const float *__restrict__ X, int c0, int lane, RowRegs<NCH> &rr) {
+    constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R, D4 = NCH * 8;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)rr.v[r] * D4 + (lane & 7);
+#pragma unroll
+        for (int cc = 0; cc < CB; ++cc)
+            rr.buf[r][cc] = rr.act[r] ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
+    }
+}
+template <int NCH, int G>
+__device__ __forceinline__ void rows_fma(const RowRegs<NCH> &rr, const float *qs, unsigned qmask, int c0, int lane, int metric,
+                                         float (&acc)[G][EvalShape<NCH>::R]) {
+    constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R, D4 = NCH * 8;
+    const float4 *q4 = reinterpret_cast<const float4 *>(qs);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (!((qmask >> g) & 1u)) continue;
+#pragma unroll
+        for (int cc = 0; cc < CB; ++cc) {
+            const float4 qv = q4[g * D4 + (c0 + cc) * 8 + (lane & 7)];
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float4 x = rr.buf[r][cc];
+                if (metric == GRAB_L2SQ) {
+                    const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+                    acc[g][r] = __builtin_fmaf(dx, dx, acc[g][r]);
+                    acc[g][r] = __builtin_fmaf(dy, dy, acc[g][r]);
+                    acc[g][r] = __builtin_fmaf(dz, dz, acc[g][r]);
+                    acc[g][r] = __builtin_fmaf(dw, dw, acc[g][r]);
+                } else {
+                    acc[g][r] = __builtin_fmaf(qv.x, x.x, acc[g][r]);
+                    acc[g][r] = __builtin_fmaf(qv.y, x.y, acc[g][r]);
+                    acc[g][r] = __builtin_fmaf(qv.z, x.z, acc[g][r]);
+                    acc[g][r] = __builtin_fmaf(qv.w, x.w, acc[g][r]);
+                }
+            }
+        }
+    }
+}
+// out[g * 64 + j] = dist(query g, L[j]) for the rows of the batch at `base`
+template <int NCH, int G>
+__device__ __forceinline__ void rows_store(const RowRegs<NCH> &rr, float (&acc)[G][EvalShape<NCH>::R], unsigned qmask, int base,
+                                           int lane, int metric, float *out) {
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        if (!((qmask >> g) & 1u)) continue;
+#pragma unroll
+        for (int r = 0; r < EvalShape<NCH>::R; ++r) {
+            float t = acc[g][r];
+            t += dpp_move<0xB1>(t);
+            t += dpp_move<0x4E>(t);
+            t += dpp_move<0x141>(t);
+            if (rr.act[r] && (lane & 7) == 0) out[g * 64 + base + r * 8 + (lane >> 3)] = metric == GRAB_L2SQ ? t : -t;
+        }
+    }
+}
+// all batches from L[base0] on; n <= 64.  Callers synchronise before qs is written and after out is read.
+template <int NCH, int G>
+__device__ __forceinline__ void eval_rows_multi(const float *__restrict__ X, const float *qs, unsigned qmask,
+                                                const uint32_t *L, int base0, int n, int lane, int metric, float *out) {
+    constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R;
+    for (int base = base0; base < n; base += 8 * R) {
+        RowRegs<NCH> rr;
+        rows_pick<NCH>(L, base, n, lane, rr);
+        float acc[G][R];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int r = 0; r < R; ++r) acc[g][r] = 0.0f;
+#pragma unroll
+        for (int c0 = 0; c0 < NCH; c0 += CB) {
+            rows_issue<NCH>(X, c0, lane, rr);
+            rows_fma<NCH, G>(rr, qs, qmask, c0, lane, metric, acc);
+        }
+        rows_store<NCH, G>(rr, acc, qmask, base, lane, metric, out);
+    }
+}
+
+// dist(query row in LDS, L[j]) for n <= 8 slots, one per group of eight lanes, in the summation
+// order of eval_batch; out[j] receives it
+template <int NCH>
+__device__ __forceinline__ void eval_rows_few(const float *__restrict__ X, const float *q, const uint32_t *L, int n, int lane,
+                                              int metric, float *out) {
+    constexpr int CB = EvalShape<NCH>::CB, D4 = NCH * 8;
+    const int sub = lane & 7, grp = lane >> 3;
+    const bool act = grp < n;
+    const uint32_t v = act ? L[grp] : 0u;
+    const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v * D4 + sub;
+    const float4 *q4 = reinterpret_cast<const float4 *>(q);
+    float acc = 0.0f;
+#pragma unroll
+    for (int c0 = 0; c0 < NCH; c0 += CB) {
+        float4 buf[CB];
+#pragma unroll
+        for (int cc = 0; cc < CB; ++cc) buf[cc] = act ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+        for (int cc = 0; cc < CB; ++cc) {
+            const float4 qv = q4[(c0 + cc) * 8 + sub], x = buf[cc];
+            if (metric == GRAB_L2SQ) {
+                const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+                acc = __builtin_fmaf(dx, dx, acc);
+                acc = __builtin_fmaf(dy, dy, acc);
+                acc = __builtin_fmaf(dz, dz, acc);
+                acc = __builtin_fmaf(dw, dw, acc);
+            } else {
+                acc = __builtin_fmaf(qv.x, x.x, acc);
+                acc = __builtin_fmaf(qv.y, x.y, acc);
+                acc = __builtin_fmaf(qv.z, x.z, acc);
+                acc = __builtin_fmaf(qv.w, x.w, acc);
+            }
+        }
+    }
+    float t = acc;
+    t += dpp_move<0xB1>(t);
+    t += dpp_move<0x4E>(t);
+    t += dpp_move<0x141>(t);
+    if (act && sub == 0) out[grp] = metric == GRAB_L2SQ ? t : -t;
+}
+
+// dist(query row qa, row qb), both dim floats in LDS, by one group of eight lanes in the summation
+// order of eval_batch; every lane of the group returns it
+template <int NCH>
+__device__ __forceinline__ float dist_lds_rows(const float *qa, const float *qb, int lane, int metric) {
+    const int sub = lane & 7;
+    const float4 *a4 = reinterpret_cast<const float4 *>(qa), *b4 = reinterpret_cast<const float4 *>(qb);
+    float acc = 0.0f;
+#pragma unroll 4
+    for (int c = 0; c < NCH; ++c) {
+        const float4 qv = a4[c * 8 + sub], x = b4[c * 8 + sub];
+        if (metric == GRAB_L2SQ) {
+            const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+            acc = __builtin_fmaf(dx, dx, acc);
+            acc = __builtin_fmaf(dy, dy, acc);
+            acc = __builtin_fmaf(dz, dz, acc);
+            acc = __builtin_fmaf(dw, dw, acc);
+        } else {
+            acc = __builtin_fmaf(qv.x, x.x, acc);
+            acc = __builtin_fmaf(qv.y, x.y, acc);
+            acc = __builtin_fmaf(qv.z, x.z, acc);
+            acc = __builtin_fmaf(qv.w, x.w, acc);
+        }
+    }
+    float t = acc;
+    t += dpp_move<0xB1>(t);
+    t += dpp_move<0x4E>(t);
+    t += dpp_move<0x141>(t);
+    return metric == GRAB_L2SQ ? t : -t;
 }
 
 // Remote edge selection (Section 4.3, Remote Edge Construction) for one node per wavefront.
