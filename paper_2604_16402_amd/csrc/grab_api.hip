@@ -144,6 +144,7 @@ void grab_destroy(grab_index *ix) {
         if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : ix->app_ev)
         if (e) (void)hipEventDestroy(e);
+    if (ix->sync_ev) (void)hipEventDestroy(ix->sync_ev);
     delete ix;
 }
 
@@ -225,7 +226,7 @@ grab_status grab_build_buckets(grab_index *ix, const float *vectors, const int32
     B_HIP(hipMalloc((void **)&ix->slot2id, n_slots * 4));
     B_HIP(hipMalloc((void **)&ix->id2slot, n_slots * 4));
     B_HIP(hipMalloc((void **)&ix->table, sizeof(int32_t) * T_COLS * n_buckets));
-    B_HIP(hipHostMalloc((void **)&ix->h_table, sizeof(int32_t) * T_COLS * n_buckets, hipHostMallocDefault));
+    B_HIP(hipHostMalloc((void **)&ix->h_table, sizeof(int32_t) * ((size_t)T_COLS * n_buckets + n_buckets + 4), hipHostMallocDefault));
     B_HIP(hipMemsetAsync(ix->X, 0, n_slots * row, ix->stream));
     B_HIP(hipMemsetAsync(ix->attr, 0, n_slots * 4, ix->stream));
     B_HIP(hipMemsetAsync(ix->slot2id, 0xFF, n_slots * 4, ix->stream));

@@ -96,13 +96,28 @@ __global__ void k_write_new(const float4 *__restrict__ vecs, const int32_t *__re
     }
 }
 
-__global__ void k_widen(const int32_t *__restrict__ attrs, const int32_t *__restrict__ bucket, int64_t m,
-                        int32_t *__restrict__ table) {
-    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (i >= m) return;
-    int32_t *t = table + T_COLS * bucket[i];
-    atomicMin(&t[T_MIN], attrs[i]);
-    atomicMax(&t[T_MAX], attrs[i]);
+// min / max of the new attributes per bucket: reduced in LDS first, so that a bucket's table entry
+// sees one atomic pair per workgroup instead of one per object
+#define WIDEN_PER_BLOCK 4096
+__global__ __launch_bounds__(TPB) void k_widen(const int32_t *__restrict__ attrs, const int32_t *__restrict__ bucket, int64_t m,
+                                               int32_t B, int32_t *__restrict__ table) {
+    __shared__ int32_t mn[GRAB_MAX_BUCKETS], mx[GRAB_MAX_BUCKETS];
+    for (int b = threadIdx.x; b < B; b += TPB) { mn[b] = INT32_MAX; mx[b] = INT32_MIN; }
+    __syncthreads();
+    const int64_t i0 = (int64_t)blockIdx.x * WIDEN_PER_BLOCK, i1 = i0 + WIDEN_PER_BLOCK < m ? i0 + WIDEN_PER_BLOCK : m;
+    for (int64_t i = i0 + threadIdx.x; i < i1; i += TPB) {
+        const int b = bucket[i];
+        const int32_t x = attrs[i];
+        atomicMin(&mn[b], x);
+        atomicMax(&mx[b], x);
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < B; b += TPB)
+        if (mn[b] <= mx[b]) {
+            int32_t *t = table + T_COLS * b;
+            atomicMin(&t[T_MIN], mn[b]);
+            atomicMax(&t[T_MAX], mx[b]);
+        }
 }
 
 __global__ void k_grow(int32_t *__restrict__ table, const int32_t *__restrict__ counts, int32_t B) {
@@ -125,9 +140,10 @@ __global__ void k_iota(uint32_t *__restrict__ a, int64_t n) {
 // row) to the rows rows[0..n), the same list for every group, in the summation order of
 // eval_batch with `mine` in the place of the query.  f(j, s) is called by every lane of a group
 // with the distance s between its row and rows[j].
-template <int NCH, typename F>
+// `done()` is asked after every batch of rows (the same answer in every lane): true ends the scan early.
+template <int NCH, typename F, typename S>
 __device__ __forceinline__ void group_vs_rows(const float *__restrict__ X, const float4 (&mine)[NCH], const uint32_t *rows,
-                                              int n, int lane, int metric, F &&f) {
+                                              int n, int lane, int metric, F &&f, S &&done) {
     constexpr int RR = NCH <= 2 ? 8 : (NCH <= 4 ? 4 : 2);   // rows in flight
     constexpr int D4 = NCH * 8;
     const int sub = lane & 7;
@@ -165,6 +181,7 @@ __device__ __forceinline__ void group_vs_rows(const float *__restrict__ X, const
             t += dpp_move<0x141>(t);
             if (j0 + r < n) f(j0 + r, metric == GRAB_L2SQ ? t : -t);
         }
+        if (done()) break;
     }
 }
 
@@ -177,13 +194,20 @@ __global__ void k_zero_stats(u64 *__restrict__ stats) {
 }
 
 // distance evaluations and expanded parents of a candidate search, summed over its queries
-__global__ void k_sum_search_counters(const uint32_t *__restrict__ counters, int64_t nq, u64 *__restrict__ stats) {
-    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
+__global__ __launch_bounds__(TPB) void k_sum_search_counters(const uint32_t *__restrict__ counters, int64_t nq, u64 *__restrict__ stats) {
+    __shared__ u64 acc[2];
+    if (threadIdx.x < 2) acc[threadIdx.x] = 0;
+    __syncthreads();
     u64 ev = 0, pa = 0;
-    if (i < nq) { pa = counters[i * 8 + 1]; ev = counters[i * 8 + 2]; }
+    for (int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x; i < nq; i += (int64_t)gridDim.x * TPB) {
+        pa += counters[i * 8 + 1];
+        ev += counters[i * 8 + 2];
+    }
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) { ev += shfl_xor64(ev, m); pa += shfl_xor64(pa, m); }
-    if ((threadIdx.x & 63) == 0) { atomicAdd(&stats[ST_SEARCH_EVALS], ev); atomicAdd(&stats[ST_SEARCH_PARENTS], pa); }
+    if ((threadIdx.x & 63) == 0) { atomicAdd(&acc[0], ev); atomicAdd(&acc[1], pa); }
+    __syncthreads();
+    if (threadIdx.x == 0) { atomicAdd(&stats[ST_SEARCH_EVALS], acc[0]); atomicAdd(&stats[ST_SEARCH_PARENTS], acc[1]); }
 }
 
 struct ForwardArgs {
@@ -234,7 +258,9 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
     uint32_t *rej = reinterpret_cast<uint32_t *>(keptd + 64);
     float *rejd = reinterpret_cast<float *>(rej + 64);
     float *dtmp = rejd + 64;
-    uint32_t *pk = reinterpret_cast<uint32_t *>(dtmp + 64);     // mode 1: remote picks,
+    uint32_t *alive = reinterpret_cast<uint32_t *>(dtmp + 64);  // rows of the chunk's candidates not hidden by a kept row,
+    uint32_t *alive_g = alive + 8;                              // and their places in the chunk
+    uint32_t *pk = alive_g + 8;                                 // mode 1: remote picks,
     float *pkd = reinterpret_cast<float *>(pk + 64);            //         their distances,
     uint32_t *rowl = reinterpret_cast<uint32_t *>(pkd + 64);    //         the local part of the new row,
     uint32_t *ul = rowl + 64;                                   //         local candidates not in it
@@ -272,10 +298,21 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) mine[c] = row[c * 8];
             }
-            bool hid = false;
-            group_vs_rows<NCH>(a.X, mine, kept, nk, lane, a.metric, [&](int, float s) { hid |= !(mydq < s); });
-            group_vs_rows<NCH>(a.X, mine, cs + t0, G, lane, a.metric, [&](int h, float s) { if (sub == 0) dtmp[grp * 8 + h] = s; });
+            // a candidate is out as soon as one kept row hides it: the scan of the kept rows ends when
+            // every candidate of the chunk is out
+            bool hid = t0 + grp >= nc;
+            group_vs_rows<NCH>(a.X, mine, kept, nk, lane, a.metric, [&](int, float s) { hid |= !(mydq < s); },
+                               [&]() { return __ballot(!hid) == 0; });
             const u64 hm = __ballot(hid);
+            // candidates of the chunk still in: only they can be kept, so only their rows can hide a
+            // later one of them
+            int na = 0;
+            for (int g = 0; g < G; ++g)
+                if (((hm >> (8 * g)) & 1ull) == 0) { if (lane == 0) alive[na] = cs[t0 + g]; if (lane == 0) alive_g[na] = (uint32_t)g; ++na; }
+            __syncthreads();
+            if (na > 1)
+                group_vs_rows<NCH>(a.X, mine, alive, na, lane, a.metric, [&](int h, float s) { if (sub == 0) dtmp[grp * 8 + alive_g[h]] = s; },
+                                   []() { return false; });
             __syncthreads();
             uint32_t keptmask = 0;
             for (int g = 0; g < G && nk < a.kl; ++g) {
@@ -448,7 +485,7 @@ struct RewireArgs {
     int32_t mode, kp;
     int64_t window;
     const int32_t *attr;
-    uint32_t *grp_out;      // by sorted position of a group's first request: requests applied | passed << 16
+    uint32_t *grp_out;      // per group, in the order of `heads`: requests applied | passed << 16
 };
 
 __device__ __forceinline__ int bucket_of_slot_dev(const int32_t *__restrict__ table, int32_t B, uint32_t slot) {
@@ -482,12 +519,14 @@ __device__ __forceinline__ int wave_bucket_of(const int32_t *__restrict__ table,
 __global__ void k_request_records(const u64 *__restrict__ key1s, const uint32_t *__restrict__ order, const u64 *__restrict__ key2,
                                   const float *__restrict__ reqd, const int32_t *__restrict__ bucket,
                                   const int32_t *__restrict__ new_attr, int32_t K, int64_t nreq, uint4 *__restrict__ rec,
-                                  unsigned char *__restrict__ head) {
+                                  unsigned char *__restrict__ head, uint32_t *__restrict__ n_valid) {
     const int64_t p = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (p >= nreq) return;
     const u64 key = key1s[p];
     head[p] = key != ~0ull && (p == 0 || key1s[p - 1] != key);
-    if (key == ~0ull) return;
+    // the "no request" keys sort last: the real requests are the positions before the first of them
+    if (key == ~0ull) { if (p == 0) *n_valid = 0; return; }
+    if (p + 1 == nreq || key1s[p + 1] == ~0ull) *n_valid = (uint32_t)(p + 1);
     const uint32_t ridx = order[p];
     const uint32_t i = ridx / (uint32_t)K;
     rec[p] = make_uint4((uint32_t)(key2[ridx] & 0xFFFFFFFFull), __float_as_uint(reqd[ridx]), (uint32_t)bucket[i], (uint32_t)new_attr[i]);
@@ -736,34 +775,33 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
         }
     }
     if (changed && lane < len) a.A[(size_t)v * K + off + lane] = R[lane];
-    if (lane == 0) a.grp_out[p0] = st_applied | (st_pass << 16);
+    if (lane == 0) a.grp_out[blockIdx.x] = st_applied | (st_pass << 16);
 }
 
 // Work counters of the call from what the kernels left behind: requests and groups by kind from
-// the sorted keys, applied / passed requests from the group heads, scan lengths from the new nodes
-__global__ __launch_bounds__(TPB) void k_reduce_stats(const u64 *__restrict__ key1s, const uint32_t *__restrict__ grp_out, int64_t nreq,
-                                                      const uint32_t *__restrict__ node_out, int64_t m, u64 *__restrict__ stats) {
+// the list of group heads (a group ends where the next one starts), applied / passed requests from
+// what each group's wavefront reported, scan lengths from the new nodes
+__global__ __launch_bounds__(TPB) void k_reduce_stats(const u64 *__restrict__ heads, const uint32_t *__restrict__ grp_out, uint32_t n_heads,
+                                                      const uint32_t *__restrict__ n_valid, const uint32_t *__restrict__ node_out,
+                                                      int64_t m, u64 *__restrict__ stats) {
     __shared__ u64 acc[ST_N];
     if (threadIdx.x < ST_N) acc[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t p = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    u64 v[ST_N];
+    u64 v[ST_SEARCH_EVALS];
 #pragma unroll
-    for (int x = 0; x < ST_N; ++x) v[x] = 0;
-    if (p < nreq) {
-        const u64 key = key1s[p];
-        if (key != ~0ull) {
-            const int kind = (int)(key & 1ull);
-            v[ST_REQ_LOCAL + kind] = 1;
-            if (p == 0 || key1s[p - 1] != key) {
-                const uint32_t g = grp_out[p];
-                v[ST_GROUPS_LOCAL + kind] = 1;
-                v[ST_APPLIED_LOCAL + kind] = g & 0xFFFFu;
-                v[ST_LOCAL_PASS] = g >> 16;
-            }
-        }
+    for (int x = 0; x < ST_SEARCH_EVALS; ++x) v[x] = 0;
+    const int64_t stride = (int64_t)gridDim.x * TPB, t0 = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    for (int64_t h = t0; h < n_heads; h += stride) {
+        const u64 e = heads[h];
+        const uint32_t pos = (uint32_t)(e >> 32), end = h + 1 < n_heads ? (uint32_t)(heads[h + 1] >> 32) : *n_valid;
+        const int kind = (int)(e & 1ull);
+        const uint32_t g = grp_out[h];
+        v[ST_REQ_LOCAL + kind] += end - pos;
+        v[ST_GROUPS_LOCAL + kind] += 1;
+        v[ST_APPLIED_LOCAL + kind] += g & 0xFFFFu;
+        v[ST_LOCAL_PASS] += g >> 16;
     }
-    if (p < m) { v[ST_SCANNED] = node_out[2 * p]; v[ST_REMOTE_ROWS] = node_out[2 * p + 1]; }
+    for (int64_t i = t0; i < m; i += stride) { v[ST_SCANNED] += node_out[2 * i]; v[ST_REMOTE_ROWS] += node_out[2 * i + 1]; }
 #pragma unroll
     for (int x = 0; x < ST_SEARCH_EVALS; ++x) {
         u64 t = v[x];
@@ -779,7 +817,7 @@ template <int NCH>
 grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireArgs &r, int64_t m, int phase) {
     const size_t qbytes = EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4;
     if (phase == 0) {
-        size_t lds = (size_t)f.beam * 16 + 64 * 4 * 9 + (size_t)((2 * f.beam + 3) & ~3) * 4 + qbytes;
+        size_t lds = (size_t)f.beam * 16 + 64 * 4 * 9 + 64 + (size_t)((2 * f.beam + 3) & ~3) * 4 + qbytes;
         k_forward<NCH><<<dim3((unsigned)((m + 7) / 8 * 8)), dim3(64), lds, ix->stream>>>(f);
     } else {
         constexpr int G = RewireShape<NCH>::G;
@@ -853,27 +891,20 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
 
     // ---- 1, 2: bucket and slot of every new object (pre-batch table), capacity check on the host
     k_assign_bucket<<<blocks_for(m), TPB, 0, st>>>(ix->table, B, d_attrs, m, ix->n, bucket, (uint32_t *)P(A_KEYS), (uint32_t *)P(A_IDX));
+    int bucket_bits = 1;
+    while ((1 << bucket_bits) < B) ++bucket_bits;
     GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp1, (uint32_t *)P(A_KEYS), (uint32_t *)P(A_KEYS_S), (uint32_t *)P(A_IDX),
-                                           (uint32_t *)P(A_IDX_S), (size_t)m, 0, 32, st));
+                                           (uint32_t *)P(A_IDX_S), (size_t)m, 0, bucket_bits, st));
     k_bucket_spans<<<blocks_for(B), TPB, 0, st>>>((uint32_t *)P(A_KEYS_S), m, B, starts, counts);
     k_assign_slots<<<blocks_for(m), TPB, 0, st>>>((uint32_t *)P(A_KEYS_S), (uint32_t *)P(A_IDX_S), m, starts, ix->table, slot);
     GRAB_HIP(ix, hipGetLastError());
-    {
-        int32_t *h_counts = new (std::nothrow) int32_t[B];
-        if (!h_counts) return grab_fail(ix, GRAB_ENOMEM, "host allocation failed");
-        hipError_t e = hipMemcpyAsync(h_counts, counts, (size_t)B * 4, hipMemcpyDeviceToHost, st);
-        if (e == hipSuccess) e = hipStreamSynchronize(st);
-        int full = -1;
-        if (e == hipSuccess)
-            for (int b = 0; b < B; ++b)
-                if (ix->h_table[T_COLS * b + T_NTOT] + h_counts[b] > ix->h_table[T_COLS * b + T_CAP]) { full = b; break; }
-        int over = full >= 0 ? h_counts[full] : 0;
-        delete[] h_counts;
-        if (e != hipSuccess) return grab_fail(ix, GRAB_EHIP, "append failed: %s", hipGetErrorString(e));
-        if (full >= 0)
-            return grab_fail(ix, GRAB_EFULL, "bucket %d holds %d of %d slots and the batch adds %d", full,
-                             ix->h_table[T_COLS * full + T_NTOT], ix->h_table[T_COLS * full + T_CAP], over);
-    }
+    // the per-bucket counts travel to pinned host memory while the candidate search, which writes
+    // nothing into the index, is already queued behind them; the host looks at them after queueing it
+    int32_t *h_counts = ix->h_table + (size_t)T_COLS * B;
+    uint32_t *h_nheads = (uint32_t *)(h_counts + B);
+    if (!ix->sync_ev) GRAB_HIP(ix, hipEventCreateWithFlags(&ix->sync_ev, hipEventDisableTiming));
+    GRAB_HIP(ix, hipMemcpyAsync(h_counts, counts, (size_t)B * 4, hipMemcpyDeviceToHost, st));
+    GRAB_HIP(ix, hipEventRecord(ix->sync_ev, st));
     // ---- 3: local candidate search against the pre-batch index (new rows are not visible yet)
     k_zero_stats<<<1, 64, 0, st>>>(stats);
     mark(0);
@@ -887,9 +918,10 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     s.out_slots = true;
     s.only_bucket = bucket; s.out_ids = (uint32_t *)P(A_CL_S); s.out_dist = (float *)P(A_CL_D);
     if ((rc = grab_plan_order(ix, s)) != GRAB_OK) return rc;
+    s.sorted_queries = (const uint32_t *)P(A_IDX_S);   // the batch in bucket order: the launch order needs no counting
     if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
     if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
-    k_sum_search_counters<<<blocks_for(m), TPB, 0, st>>>(s.counters, m, stats);
+    k_sum_search_counters<<<dim3(64), TPB, 0, st>>>(s.counters, m, stats);
     ix->last_nq = 0;
     if (rule.mode == 1 && kr > 0) {
         // ---- 3': the same search over every other bucket (Section 4.4: candidates from the global scope)
@@ -897,9 +929,15 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
         s.only_bucket = (const int32_t *)P(A_SCOPE); s.out_ids = (uint32_t *)P(A_CG_S); s.out_dist = (float *)P(A_CG_D);
         if ((rc = grab_launch_select(ix, s)) != GRAB_OK) return rc;
         if ((rc = grab_launch_beam(ix, s)) != GRAB_OK) return rc;
-        k_sum_search_counters<<<blocks_for(m), TPB, 0, st>>>(s.counters, m, stats);
+        k_sum_search_counters<<<dim3(64), TPB, 0, st>>>(s.counters, m, stats);
     }
     mark(1);
+    // ---- capacity check (nothing has been written so far)
+    GRAB_HIP(ix, hipEventSynchronize(ix->sync_ev));
+    for (int b = 0; b < B; ++b)
+        if (ix->h_table[T_COLS * b + T_NTOT] + h_counts[b] > ix->h_table[T_COLS * b + T_CAP])
+            return grab_fail(ix, GRAB_EFULL, "bucket %d holds %d of %d slots and the batch adds %d", b,
+                             ix->h_table[T_COLS * b + T_NTOT], ix->h_table[T_COLS * b + T_CAP], h_counts[b]);
     // ---- 4: forward selection, new adjacency rows, reverse requests
     ForwardArgs f;
     f.X = ix->X; f.A = ix->A; f.vecs = d_vecs; f.slot = slot;
@@ -929,12 +967,12 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     // per sorted position what the rewiring needs of the request; the positions where a group starts
     k_request_records<<<blocks_for(nreq), TPB, 0, st>>>((const u64 *)P(A_K1S), (const uint32_t *)P(A_ORD2), (const u64 *)P(A_KEY2),
                                                         (const float *)P(A_REQD), bucket, d_attrs, K, nreq, (uint4 *)P(A_REC),
-                                                        (unsigned char *)P(A_HEAD));
+                                                        (unsigned char *)P(A_HEAD), (uint32_t *)P(A_NHEADS) + 1);
     GRAB_HIP(ix, rocprim::select(P(A_TMP), tmp3, HeadIt(rocprim::counting_iterator<uint32_t>(0), HeadEntry{(const u64 *)P(A_K1S)}),
                                  (unsigned char *)P(A_HEAD), (u64 *)P(A_HEADS), (uint32_t *)P(A_NHEADS), (size_t)nreq, st));
-    uint32_t n_heads = 0;
-    GRAB_HIP(ix, hipMemcpyAsync(&n_heads, P(A_NHEADS), 4, hipMemcpyDeviceToHost, st));
+    GRAB_HIP(ix, hipMemcpyAsync(h_nheads, P(A_NHEADS), 4, hipMemcpyDeviceToHost, st));
     GRAB_HIP(ix, hipStreamSynchronize(st));
+    const uint32_t n_heads = *h_nheads;
     r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.rec = (const uint4 *)P(A_REC);
     r.heads = (const u64 *)P(A_HEADS); r.n_heads = n_heads; r.nreq = nreq;
     r.kl = kl; r.kr = kr; r.metric = ix->metric; r.table = ix->table; r.B = B;
@@ -943,9 +981,9 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     mark(3);
     if ((rc = launch_append(ix, f, r, m, 1)) != GRAB_OK) return rc;
     mark(4);
-    k_reduce_stats<<<blocks_for(nreq > m ? nreq : m), TPB, 0, st>>>(r.key1s, r.grp_out, nreq, f.node_out, m, stats);
+    k_reduce_stats<<<dim3(256), TPB, 0, st>>>(r.heads, r.grp_out, n_heads, (const uint32_t *)P(A_NHEADS) + 1, f.node_out, m, stats);
     // ---- 6: table
-    k_widen<<<blocks_for(m), TPB, 0, st>>>(d_attrs, bucket, m, ix->table);
+    k_widen<<<dim3((unsigned)((m + WIDEN_PER_BLOCK - 1) / WIDEN_PER_BLOCK)), TPB, 0, st>>>(d_attrs, bucket, m, B, ix->table);
     k_grow<<<blocks_for(B), TPB, 0, st>>>(ix->table, counts, B);
     GRAB_HIP(ix, hipGetLastError());
     GRAB_HIP(ix, hipMemcpyAsync(ix->h_table, ix->table, sizeof(int32_t) * T_COLS * B, hipMemcpyDeviceToHost, st));

@@ -92,7 +92,7 @@ struct grab_index {
     uint32_t *slot2id = nullptr; // [n_slots]
     uint32_t *id2slot = nullptr; // [n_slots] (ids grow up to the slot count)
     int32_t *table = nullptr;    // [B][6] device copy
-    int32_t *h_table = nullptr;  // host copy (pinned)
+    int32_t *h_table = nullptr;  // host copy (pinned), followed by B + 4 words that insertion reads results into
 
     // graph (device)
     int32_t kl = 0, kr = 0;
@@ -114,6 +114,7 @@ struct grab_index {
     DevBuf app_stats;            // work counters of the last insertion (12 x uint64)
     bool app_has_stats = false, app_timed = false;
     hipEvent_t app_ev[5] = {nullptr, nullptr, nullptr, nullptr, nullptr};
+    hipEvent_t sync_ev = nullptr;   // lets the host wait for one copy while later kernels are already queued
 
     bool profile = false;
     bool timed = false;          // the last search recorded events
@@ -164,6 +165,9 @@ struct SearchLaunch {
     uint32_t *order = nullptr;   // [order_len]: query of each workgroup, GRAB_EMPTY for none
     int64_t order_len = 0;
     bool *order_dirty = nullptr; // host flag: bin_count may not be zero (null: always clear it first)
+    // device [nq] or nullptr: the queries already listed by bin (a batch sorted by the bucket it is
+    // scoped to); the launch order is then read off this list and nothing is counted
+    const uint32_t *sorted_queries = nullptr;
 };
 // Reserves the buffers that let the search run its queries grouped by first selected bucket, one
 // contiguous run of that order per XCD (queries that read the same buckets then share L2 and the

@@ -311,6 +311,20 @@ __global__ __launch_bounds__(256) void k_order(const int32_t *__restrict__ q_bin
         for (int i = tid; i <= nbins; i += 256) { bin_count[GRAB_BIN_STRIDE * i] = 0; bin_count[GRAB_BIN_STRIDE * i + 1] = 0; }
 }
 
+// The launch order read off a list of the queries that is already in bin order (a batch sorted by
+// the bucket each query is scoped to): entry t of `order` takes the query at the position that
+// k_order would map there, with runs_per_xcd long runs per XCD.
+__global__ __launch_bounds__(256) void k_order_sorted(const uint32_t *__restrict__ sorted, int64_t nq, uint32_t *__restrict__ order,
+                                                      int64_t order_len, int runs_per_xcd) {
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= order_len) return;
+    const int64_t parts = 8 * (int64_t)runs_per_xcd;
+    const int64_t run = (nq + parts - 1) / parts;
+    const int64_t i = t / 8, c = t % 8;
+    const int64_t pos = ((i / run) * 8 + c) * run + i % run;
+    order[t] = pos < nq ? sorted[pos] : GRAB_EMPTY;
+}
+
 // ------------------------------------------------------------------------------- beam search
 struct BeamArgs {
     const float *X;
@@ -669,7 +683,8 @@ grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
     if (s.nq == 0) return GRAB_OK;
     const int nbins = ix->B + 1;   // the last bin takes the queries whose range meets no bucket
     const size_t lds = (size_t)(4 * ix->B + 1) * 4;
-    if (s.order) {
+    const bool counted = s.order && !s.sorted_queries;
+    if (counted) {
         // the counters are left zero by the k_order of the previous call; if that is in doubt
         // (fresh memory, a launch that failed in between) they are cleared first
         const bool dirty = !s.order_dirty || *s.order_dirty;
@@ -682,9 +697,14 @@ grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
     }
     k_select_seed<<<dim3((unsigned)s.nq), dim3(64), lds, ix->stream>>>(ix->table, ix->B, ix->attr, s.lo, s.hi, s.only_bucket,
                                                                       s.n_seeds, s.salt, s.plans, s.seeds,
-                                                                      s.order ? s.q_bin : nullptr, s.bin_count);
+                                                                      counted ? s.q_bin : nullptr, s.bin_count);
     GRAB_HIP(ix, hipGetLastError());
-    if (s.order) {
+    if (s.order && s.sorted_queries) {
+        k_order_sorted<<<dim3((unsigned)((s.order_len + 255) / 256)), dim3(256), 0, ix->stream>>>(s.sorted_queries, s.nq, s.order,
+                                                                                               s.order_len, ix->dim >= 512 ? 4 : 1);
+        GRAB_HIP(ix, hipGetLastError());
+    }
+    if (counted) {
         // measured: rows of 512 B (1M x 128) run fastest with one run per XCD (headline 481 us against
         // 502 us with four and 516 us in input order); rows of 3,840 B (1M x 960) with four (3.82 ms
         // against 4.06 ms with one and 4.19 ms in input order)
