@@ -125,12 +125,6 @@ __global__ void k_grow(int32_t *__restrict__ table, const int32_t *__restrict__ 
     if (b < B) table[T_COLS * b + T_NTOT] += counts[b];
 }
 
-__global__ void k_gather_u64(const u64 *__restrict__ src, const uint32_t *__restrict__ order, int64_t n,
-                             u64 *__restrict__ dst) {
-    int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
-    if (i < n) dst[i] = src[order[i]];
-}
-
 __global__ void k_iota(uint32_t *__restrict__ a, int64_t n) {
     int64_t i = (int64_t)blockIdx.x * TPB + threadIdx.x;
     if (i < n) a[i] = (uint32_t)i;
@@ -479,6 +473,7 @@ struct RewireArgs {
     const u64 *heads;       // per (target, kind) group, in sorted order: position of its first request << 32 | key; one workgroup each
     int64_t nreq;
     uint32_t n_heads;
+    uint32_t *big_heads, *n_big;   // groups of more than 64 requests, left to a second launch
     int32_t kl, kr, metric, B;
     float a;                // alpha squared: the bias acts on squared distances (see bias_base)
     // proximal / global reading of the remote part (mode 1)
@@ -524,6 +519,7 @@ __global__ void k_request_records(const u64 *__restrict__ key1s, const uint32_t 
     if (p >= nreq) return;
     const u64 key = key1s[p];
     head[p] = key != ~0ull && (p == 0 || key1s[p - 1] != key);
+    if (p == 0) n_valid[1] = 0;   // the rewiring's count of groups left to its second launch
     // the "no request" keys sort last: the real requests are the positions before the first of them
     if (key == ~0ull) { if (p == 0) *n_valid = 0; return; }
     if (p + 1 == nreq || key1s[p + 1] == ~0ull) *n_valid = (uint32_t)(p + 1);
@@ -562,20 +558,64 @@ struct RewireShape {
 // later requests get their distance to it from LDS.  Remote kind: the entry of the target's remote
 // part that lies in the newcomer's bucket is overwritten iff the newcomer's biased distance to the
 // target is smaller.
-template <int NCH>
-__global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
+// The next requests of a group in (distance image, source slot) order, written to rq / rd / rb / ra;
+// returns how many.  BIG = false: the whole group (at most 64 requests, held one per lane in rc)
+// is ranked by counting.  BIG = true: the 64 smallest keys above `last`, found by a pass over all
+// requests of the group; what a request carries besides its key is read again from its source.
+template <bool BIG>
+__device__ __forceinline__ int next_requests(const RewireArgs &a, int64_t p0, int gt, const uint4 *raw, u64 &last, int lane,
+                                             uint32_t *rq, float *rd, int32_t *rb, int32_t *ra) {
+    int nb;
+    if constexpr (!BIG) {
+        const uint4 rc = raw[lane];
+        const u64 mykey = lane < gt ? (((u64)dist_image(__uint_as_float(rc.y)) << 32) | (u64)rc.x) : SENT;
+        int rank = 0;
+        for (int j = 0; j < gt; ++j) rank += read_lane64(mykey, j) < mykey ? 1 : 0;
+        if (lane < gt) { rq[rank] = rc.x; rd[rank] = __uint_as_float(rc.y); rb[rank] = (int32_t)rc.z; ra[rank] = (int32_t)rc.w; }
+        nb = gt;
+    } else {
+        LaneQueue<1> best;
+        best.clear();
+        for (int64_t pp = p0; pp < p0 + gt; pp += 64) {
+            u64 ck = SENT;
+            if (pp + lane < p0 + gt) {
+                const uint4 r = a.rec[pp + lane];
+                const u64 k2 = ((u64)dist_image(__uint_as_float(r.y)) << 32) | (u64)r.x;
+                if (k2 > last) ck = k2;
+            }
+            ck = sort_lanes(ck, 64, lane);
+            best.merge(ck, 64, lane);
+        }
+        const u64 bk = best.k[0];
+        nb = __popcll(__ballot(bk != SENT));
+        const uint32_t src = (uint32_t)(bk & 0xFFFFFFFFull);
+        if (lane < nb) { rq[lane] = src; rd[lane] = image_dist((uint32_t)(bk >> 32)); ra[lane] = a.attr[src]; }
+        for (int j = 0; j < nb; ++j) {
+            const int bj = wave_bucket_of(a.table, a.B, (uint32_t)(read_lane64(bk, j) & 0xFFFFFFFFull), lane);
+            if (lane == j) rb[j] = bj;
+        }
+        last = read_lane64(bk, nb - 1);
+    }
+    __syncthreads();
+    return nb;
+}
+
+// BIG = false: one workgroup per group; a group of more than 64 requests is only noted in
+// a.big_heads.  BIG = true: a few workgroups share out the noted groups (a second launch).
+template <int NCH, bool BIG>
+__global__ __launch_bounds__(64, 4) void k_rewire(RewireArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     constexpr int D = NCH * 32, D4 = NCH * 8, G = RewireShape<NCH>::G;
     constexpr bool WHOLE = EvalShape<NCH>::CB == NCH;   // a whole row fits the register batch
     const int lane = threadIdx.x;
-    // one wavefront per (target, kind) group, which it applies in order
-    const u64 head = a.heads[blockIdx.x];
+    for (uint32_t hi = blockIdx.x; hi < (BIG ? *a.n_big : a.n_heads); hi += BIG ? gridDim.x : a.n_heads) {
+    // one wavefront per (target, kind) group, which it applies in (distance, source) order
+    const uint32_t head_index = BIG ? a.big_heads[hi] : hi;
+    const u64 head = a.heads[head_index];
     const int64_t p0 = (int64_t)(head >> 32);
     const u64 key = head & 0xFFFFFFFFull;
-    // the first 64 positions from the head on (requests of the group are contiguous)
-    int64_t pp = p0 + lane;
-    bool mine_req = pp < a.nreq && a.key1s[pp] == key;
-    uint4 rc = pp < a.nreq ? a.rec[pp] : make_uint4(0u, 0u, 0u, 0u);
+    // the first 64 positions from the head on (requests of the group are contiguous, in no order)
+    const bool in_first = p0 + lane < a.nreq && a.key1s[p0 + lane] == key;
     unsigned st_applied = 0, st_pass = 0;
     const uint32_t v = (uint32_t)(key >> 1);
     const int kind = (int)(key & 1ull);
@@ -584,42 +624,62 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
     uint32_t *Rl = R + 64;                                // same with empty entries pointing at row 0
     float *Dall = reinterpret_cast<float *>(Rl + 64);     // [0]: dist(v, R[j]); [1 + k]: dist(request k of the pass, R[j])
     uint32_t *qrow = reinterpret_cast<uint32_t *>(Dall + (G + 1) * 64);   // the requesting nodes' own rows, 128 entries each
-    uint32_t *rq = qrow + G * 128;                        // sources of up to 64 requests of the group,
+    uint32_t *rq = qrow + G * 128;                        // sources of up to 64 requests of the group, in order,
     float *rd = reinterpret_cast<float *>(rq + 64);       // their distances to v,
     int32_t *rb = reinterpret_cast<int32_t *>(rd + 64);   // their buckets
     int32_t *ra = rb + 64;                                // and attributes
     float *qs = reinterpret_cast<float *>(ra + 64);       // staged rows: v, then the requesting nodes of the pass
-    float *dq = Dall;   // remote kind: dist(v, R[j])
+    float *dq = Dall;                                     // remote kind: dist(v, R[j])
+    uint4 *raw = reinterpret_cast<uint4 *>(qs + (size_t)(G + 1) * D);   // the records of those positions as they come
+    raw[lane] = p0 + lane < a.nreq ? a.rec[p0 + lane] : make_uint4(0u, 0u, 0u, 0u);
     if (lane < len) {
         uint32_t e = a.A[(size_t)v * K + off + lane];
         R[lane] = e;
         Rl[lane] = e == GRAB_EMPTY ? 0u : e;
     }
+    // size of the group
+    int gt;
+    {
+        const u64 same = __ballot(in_first);
+        gt = same == ~0ull ? 64 : __ffsll((long long)~same) - 1;
+        if (gt == 64)
+            for (int64_t pp = p0 + 64;; pp += 64) {
+                const u64 more = __ballot(pp + lane < a.nreq && a.key1s[pp + lane] == key);
+                const int g = more == ~0ull ? 64 : __ffsll((long long)~more) - 1;
+                gt += g;
+                if (g < 64) break;
+            }
+    }
+    if constexpr (!BIG) {
+        if (gt > 64) {
+            if (lane == 0) a.big_heads[atomicAdd(a.n_big, 1u)] = head_index;
+            continue;
+        }
+    }
+    __syncthreads();   // the previous group of this workgroup is done with the arrays below
     bool changed = false;
+    u64 last = 0;   // groups beyond 64 requests: the largest (distance, source) key applied so far
+    int done = 0;
+    __syncthreads();
     if (kind == 1) {
-        __syncthreads();
+        // distances of the row's entries to v, and the bucket of the entry each lane looks after
         for (int t = lane; t < D4; t += 64) reinterpret_cast<float4 *>(qs)[t] = reinterpret_cast<const float4 *>(a.X)[(size_t)v * D4 + t];
         __syncthreads();
         if (len <= 8) eval_rows_few<NCH>(a.X, qs, Rl, len, lane, a.metric, Dall);   // dist(v, R[j])
         else eval_rows_multi<NCH, 1>(a.X, qs, 1u, Rl, 0, len, lane, a.metric, Dall);
         const int32_t attr_v = a.mode == 1 ? a.attr[v] : 0;
-        // bucket of the entry this lane looks after; a rewritten entry takes its source's
-        uint32_t mine = lane < len ? R[lane] : GRAB_EMPTY;
+        uint32_t mine_r = lane < len ? R[lane] : GRAB_EMPTY;
         const int bv = a.mode == 1 ? wave_bucket_of(a.table, a.B, v, lane) : 0;
         int bmine = -1;
         for (int j = 0; j < len; ++j) {
-            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)mine, j);
+            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)mine_r, j);
             const int be = e != GRAB_EMPTY ? wave_bucket_of(a.table, a.B, e, lane) : -1;
             if (lane == j) bmine = be;
         }
         __syncthreads();
-        for (;;) {
-            const u64 same = __ballot(mine_req);
-            const int gp = same == ~0ull ? 64 : __ffsll((long long)~same) - 1;
-            if (gp == 0) break;
-            if (lane < gp) { rq[lane] = rc.x; rd[lane] = __uint_as_float(rc.y); rb[lane] = (int32_t)rc.z; ra[lane] = (int32_t)rc.w; }
-            __syncthreads();
-            for (int t = 0; t < gp; ++t) {
+        do {
+            const int nb = next_requests<BIG>(a, p0, gt, raw, last, lane, rq, rd, rb, ra);
+            for (int t = 0; t < nb; ++t) {
                 const uint32_t q = rq[t];
                 const float dvq = rd[t];
                 const float lhs = a.a * bias_base(dvq, a.metric);
@@ -631,53 +691,44 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
                     if (diff < 0) diff = -diff;
                     const int j0 = diff <= a.window ? 0 : a.kp, j1 = diff <= a.window ? a.kp : len;
                     const bool inc = lane >= j0 && lane < j1;
-                    const u64 free_m = __ballot(inc && (mine == GRAB_EMPTY || bmine == bv));
+                    const u64 free_m = __ballot(inc && (mine_r == GRAB_EMPTY || bmine == bv));
                     if (free_m) {
                         at = __ffsll((long long)free_m) - 1;
                     } else if (j1 > j0) {
-                        const int far = farthest_lane(inc, dist_image(dq[lane]), mine, lane);
+                        const int far = farthest_lane(inc, dist_image(dq[lane]), mine_r, lane);
                         if (lhs < bias_base(dq[far], a.metric)) at = far;
                     }
                 } else {
                     const int bq = rb[t];
-                    const bool inb = mine != GRAB_EMPTY && bmine == bq;
+                    const bool inb = mine_r != GRAB_EMPTY && bmine == bq;
                     if (__ballot(inb)) {
-                        const int far = farthest_lane(inb, dist_image(dq[lane]), mine, lane);
+                        const int far = farthest_lane(inb, dist_image(dq[lane]), mine_r, lane);
                         if (lhs < bias_base(dq[far], a.metric)) at = far;
                     } else {
-                        const u64 empties = __ballot(lane < len && mine == GRAB_EMPTY);
+                        const u64 empties = __ballot(lane < len && mine_r == GRAB_EMPTY);
                         if (empties) at = __ffsll((long long)empties) - 1;
                     }
                 }
                 __syncthreads();
                 if (at >= 0) {
-                    if (lane == at) { R[at] = q; dq[at] = dvq; mine = q; bmine = rb[t]; }
+                    if (lane == at) { R[at] = q; dq[at] = dvq; mine_r = q; bmine = rb[t]; }
                     changed = true;
                     ++st_applied;
                 }
                 __syncthreads();
             }
-            if (gp < 64) break;
-            pp += 64;
-            mine_req = pp < a.nreq && a.key1s[pp] == key;
-            rc = pp < a.nreq ? a.rec[pp] : make_uint4(0u, 0u, 0u, 0u);
-        }
+            done += nb;
+        } while (BIG && done < gt);
     } else {
         const float4 *X4 = reinterpret_cast<const float4 *>(a.X);
         float4 *qs4 = reinterpret_cast<float4 *>(qs);
         const int sub = lane & 7, grp = lane >> 3;
         const int K8 = (K + 7) & ~7;
         bool first = true;
-        __syncthreads();
-        for (;;) {
-            // up to 64 requests of the group
-            const u64 same = __ballot(mine_req);
-            const int gp = same == ~0ull ? 64 : __ffsll((long long)~same) - 1;
-            if (gp == 0) break;
-            if (lane < gp) { rq[lane] = rc.x; rd[lane] = __uint_as_float(rc.y); }
-            __syncthreads();
-            for (int c0 = 0; c0 < gp; c0 += G) {
-                const int ng = min(G, gp - c0);
+        do {
+            const int nb = next_requests<BIG>(a, p0, gt, raw, last, lane, rq, rd, rb, ra);
+            for (int c0 = 0; c0 < nb; c0 += G) {
+                const int ng = min(G, nb - c0);
                 const unsigned qmask = (first ? 1u : 0u) | (((1u << ng) - 1u) << 1);
                 // the neighbour rows are on their way while the query rows are staged
                 RowRegs<NCH> rr;
@@ -768,14 +819,12 @@ __global__ __launch_bounds__(64) void k_rewire(RewireArgs a) {
                     __syncthreads();
                 }
             }
-            if (gp < 64) break;
-            pp += 64;
-            mine_req = pp < a.nreq && a.key1s[pp] == key;
-            rc = pp < a.nreq ? a.rec[pp] : make_uint4(0u, 0u, 0u, 0u);
-        }
+            done += nb;
+        } while (BIG && done < gt);
     }
     if (changed && lane < len) a.A[(size_t)v * K + off + lane] = R[lane];
-    if (lane == 0) a.grp_out[blockIdx.x] = st_applied | (st_pass << 16);
+    if (lane == 0) a.grp_out[head_index] = st_applied | (st_pass << 16);
+    }
 }
 
 // Work counters of the call from what the kernels left behind: requests and groups by kind from
@@ -821,8 +870,11 @@ grab_status launch_append_t(grab_index *ix, const ForwardArgs &f, const RewireAr
         k_forward<NCH><<<dim3((unsigned)((m + 7) / 8 * 8)), dim3(64), lds, ix->stream>>>(f);
     } else {
         constexpr int G = RewireShape<NCH>::G;
-        size_t lds = 64 * 4 * (2 + (G + 1) + 4) + (size_t)G * 128 * 4 + (size_t)(G + 1) * ix->dim * 4;
-        if (r.n_heads > 0) k_rewire<NCH><<<dim3(r.n_heads), dim3(64), lds, ix->stream>>>(r);
+        size_t lds = 64 * 4 * (2 + (G + 1) + 4) + (size_t)G * 128 * 4 + (size_t)(G + 1) * ix->dim * 4 + 64 * 16;
+        if (r.n_heads > 0) {
+            k_rewire<NCH, false><<<dim3(r.n_heads), dim3(64), lds, ix->stream>>>(r);
+            k_rewire<NCH, true><<<dim3(r.n_heads < 2048u ? r.n_heads : 2048u), dim3(64), lds, ix->stream>>>(r);
+        }
     }
     GRAB_HIP(ix, hipGetLastError());
     return GRAB_OK;
@@ -866,8 +918,8 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
         need[A_CG_S] = need[A_CG_D] = (size_t)m * beam * 4;
         need[A_SCOPE] = (size_t)m * 4;
     }
-    need[A_KEY1] = need[A_KEY2] = need[A_K2S] = need[A_K1G] = need[A_K1S] = (size_t)nreq * 8;
-    need[A_REQD] = need[A_ORD0] = need[A_ORD1] = need[A_ORD2] = (size_t)nreq * 4;
+    need[A_KEY1] = need[A_KEY2] = need[A_K1S] = (size_t)nreq * 8;
+    need[A_REQD] = need[A_ORD0] = need[A_ORD2] = (size_t)nreq * 4;
     size_t tmp1 = 0, tmp2 = 0;
     GRAB_HIP(ix, rocprim::radix_sort_pairs(nullptr, tmp1, (uint32_t *)nullptr, (uint32_t *)nullptr, (uint32_t *)nullptr,
                                            (uint32_t *)nullptr, (size_t)m, 0, 32, st));
@@ -956,13 +1008,11 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     const int32_t row_f4 = ix->dim / 4;
     k_write_new<<<blocks_for(m * row_f4), TPB, 0, st>>>((const float4 *)d_vecs, d_attrs, slot, m, ix->n, row_f4, (float4 *)ix->X,
                                                         ix->attr, ix->slot2id, ix->id2slot);
-    // ---- 5: requests ordered by (target, kind, distance, source): two stable radix passes
+    // ---- 5: requests grouped by (target, kind): one radix sort over the 33 bits of (target << 1 | kind);
+    // the "no request" key has them all set and sorts last.  Inside a group the rewiring itself
+    // puts the requests in (distance, source) order.
     k_iota<<<blocks_for(nreq), TPB, 0, st>>>((uint32_t *)P(A_ORD0), nreq);
-    GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp2, (u64 *)P(A_KEY2), (u64 *)P(A_K2S), (uint32_t *)P(A_ORD0),
-                                           (uint32_t *)P(A_ORD1), (size_t)nreq, 0, 64, st));
-    k_gather_u64<<<blocks_for(nreq), TPB, 0, st>>>((const u64 *)P(A_KEY1), (const uint32_t *)P(A_ORD1), nreq, (u64 *)P(A_K1G));
-    // (target << 1 | kind) takes 33 bits; the "no request" key has them all set and sorts last
-    GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp2, (u64 *)P(A_K1G), (u64 *)P(A_K1S), (uint32_t *)P(A_ORD1),
+    GRAB_HIP(ix, rocprim::radix_sort_pairs(P(A_TMP), tmp2, (u64 *)P(A_KEY1), (u64 *)P(A_K1S), (uint32_t *)P(A_ORD0),
                                            (uint32_t *)P(A_ORD2), (size_t)nreq, 0, 33, st));
     // per sorted position what the rewiring needs of the request; the positions where a group starts
     k_request_records<<<blocks_for(nreq), TPB, 0, st>>>((const u64 *)P(A_K1S), (const uint32_t *)P(A_ORD2), (const u64 *)P(A_KEY2),
@@ -975,6 +1025,7 @@ grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_
     const uint32_t n_heads = *h_nheads;
     r.X = ix->X; r.A = ix->A; r.key1s = (const u64 *)P(A_K1S); r.rec = (const uint4 *)P(A_REC);
     r.heads = (const u64 *)P(A_HEADS); r.n_heads = n_heads; r.nreq = nreq;
+    r.big_heads = (uint32_t *)P(A_ORD0); r.n_big = (uint32_t *)P(A_NHEADS) + 2;
     r.kl = kl; r.kr = kr; r.metric = ix->metric; r.table = ix->table; r.B = B;
     r.mode = rule.mode; r.kp = rule.n_proximal; r.window = rule.window; r.attr = ix->attr; r.grp_out = (uint32_t *)P(A_GRP_OUT);
     r.a = ix->prm.alpha * ix->prm.alpha;

@@ -69,11 +69,11 @@ def test_hand_worked_victim_choice_on_gpu():
     ix.close()
 
 
-def _pair(n, dim, B, kl, kr, n_cap, seed, components=16, metric=W.L2SQ):
+def _pair(n, dim, B, kl, kr, n_cap, seed, components=16, metric=W.L2SQ, batch=None):
     import torch
     from paper_2604_16402_amd import binding
     cfg = W.Config(f"a{seed}", n, dim, components, 0.3, n, B, kl, kr, 400, (0.1,), metric=metric, seed=seed,
-                   append_rounds=3, append_batch=max(64, n // 8))
+                   append_rounds=3, append_batch=batch or max(64, n // 8))
     X, a = W.base_vectors(cfg), W.attributes(cfg)
     ora = O.Index(X, a, B, n_cap=n_cap, metric=metric)
     la, ra = HG.build_graph(X, ora.bucket_of_ids(), B, kl, kr, metric=metric,
@@ -123,6 +123,26 @@ def test_append_matches_oracle(n, dim, B, kl, kr, n_cap, beam, width, rcands):
     gt, _ = O.exact_filtered_knn(allX, alla, q[:100], lo[:100], hi[:100], 10)
     assert O.recall_at_k(ids[:100], gt) > 0.75     # soft: the graph is small and shallow here
     assert (ids[ids != 0xFFFFFFFF] >= n).any()
+    ix.close()
+
+
+@pytest.mark.parametrize("mode", [0, 1])
+def test_targets_with_more_than_64_requests(mode):
+    # a small index and a large batch: every existing object is asked for an edge by far more new
+    # objects than one wavefront holds at once, so the rewiring walks its request lists in pages
+    cfg, ix, ora, X, a = _pair(400, 64, 4, 8, 4, 400 + 4 * 3600, seed=31, components=4, batch=6000)
+    for k, v in [("append_beam", 32), ("n_seeds", 32), ("remote_mode", mode)]:
+        ix.set_param(k, v)
+        ora.params[k] = v
+    for r in range(2):
+        nx, na = W.append_vectors(cfg, r), W.append_attributes(cfg, r)
+        ix.append_batch(nx, na)
+        ora.append(nx, na, threads=O.max_threads())
+        _same_index(ix, ora)
+        st = ix.get_append_stats()
+        assert st == ora.last_append_stats
+        if r == 0:
+            assert st["requests_local"] > 64 * st["groups_local"] and st["requests_remote"] > 0
     ix.close()
 
 
