@@ -390,7 +390,18 @@ grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int3
     KnnArgs k;
     k.X = ix->X; k.table = ix->table; k.tgt = tgt; k.out_s = cand_s; k.out_d = cand_d;
     k.out_stride = pool; k.out_off = 0; k.n_slots = N; k.P = pool; k.metric = ix->metric; k.exclude_self = 1;
-    if ((rc = launch_graph(ix, &k, nullptr, tiles)) != GRAB_OK) { cleanup(); return rc; }
+    {
+        // scores on the matrix cores pick the few candidates whose exact distances are then taken;
+        // without memory for that, or where too many distances are equal, every pair is evaluated in fp32
+        KnnFilter *flt = nullptr;
+        bool redo = true;
+        if (grab_knn_prepare(ix, &flt) == GRAB_OK) {
+            rc = grab_knn_pass(ix, flt, tgt, cand_s, cand_d, pool, 0, pool, 1, &redo);
+            grab_knn_release(flt);
+            if (rc != GRAB_OK) { cleanup(); return rc; }
+        }
+        if (redo && (rc = launch_graph(ix, &k, nullptr, tiles)) != GRAB_OK) { cleanup(); return rc; }
+    }
     PruneArgs p;
     p.X = ix->X; p.slot2id = ix->slot2id; p.cand_s = cand_s; p.cand_d = cand_d; p.F = F; p.Fd = Fd; p.P = pool; p.metric = ix->metric;
     if ((rc = launch_graph(ix, nullptr, &p, tiles)) != GRAB_OK) { cleanup(); return rc; }
@@ -487,11 +498,18 @@ grab_status grab_build_remote_device(grab_index *ix, const SearchLaunch &proto) 
         KnnArgs k;
         k.X = ix->X; k.table = ix->table; k.n_slots = N; k.metric = ix->metric;
         grab_status rc;
+        KnnFilter *flt = nullptr;
+        (void)grab_knn_prepare(ix, &flt);   // null: every pair in fp32
         for (int j = 0; j < kr; ++j) {
             k.tgt = tgt + (size_t)j * B; k.out_s = ix->A; k.out_d = nullptr;
             k.out_stride = K; k.out_off = kl + j; k.P = 1; k.exclude_self = 0;
-            if ((rc = launch_graph(ix, &k, nullptr, tiles)) != GRAB_OK) { cleanup(); return rc; }
+            bool redo = true;
+            if (flt && (rc = grab_knn_pass(ix, flt, k.tgt, k.out_s, nullptr, K, kl + j, 1, 0, &redo)) != GRAB_OK) {
+                grab_knn_release(flt); cleanup(); return rc;
+            }
+            if (redo && (rc = launch_graph(ix, &k, nullptr, tiles)) != GRAB_OK) { grab_knn_release(flt); cleanup(); return rc; }
         }
+        grab_knn_release(flt);
         G_HIP(hipGetLastError());
         G_HIP(hipStreamSynchronize(st));
         cleanup();

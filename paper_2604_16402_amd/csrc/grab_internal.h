@@ -191,3 +191,9 @@ grab_status grab_build_graph_device(grab_index *ix, int32_t kl, int32_t kr, int3
 grab_status grab_build_remote_device(grab_index *ix, const SearchLaunch &proto);
 grab_status grab_append_device(grab_index *ix, const float *d_vecs, const int32_t *d_attrs, int64_t m,
                                const SearchLaunch &proto);
+// construction's nearest-neighbour passes as a matrix-core filter with an exact re-rank (grab_knn.hip)
+struct KnnFilter;
+grab_status grab_knn_prepare(grab_index *ix, KnnFilter **out);
+void grab_knn_release(KnnFilter *f);
+grab_status grab_knn_pass(grab_index *ix, KnnFilter *f, const int32_t *d_tgt, uint32_t *out_s, float *out_d, int64_t out_stride,
+                          int64_t out_off, int32_t P, int32_t exclude_self, bool *overflow);
