@@ -27,9 +27,18 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int FT = 128;        // source rows, and targets per step, of a workgroup (2 x 2 wavefronts of 64 x 64)
-constexpr int FT_KC = 32;      // floats of a row staged per step
-constexpr int FT_PITCH = 40;   // bf16 per staged row: 64 bytes of data, 16 of padding (conflict-free 16-byte reads)
+constexpr int FT = 128;        // source rows, and targets per step, of a workgroup (2 x 4 wavefronts of 64 x 32)
+// A step stages 16 * KS floats of every row; rows are cut so that a pass over a row takes an even
+// number of steps (two register sets take turns fetching ahead, without any copying between them)
+template <int NCH>
+struct StepShape {
+    static constexpr int KS = NCH % 2 == 0 ? 2 : NCH;             // 16-float pieces per step: 32, 96 and 160 floats go in two steps
+    static constexpr int KC = 16 * KS;                             // floats per step
+    static constexpr int STEPS = NCH * 32 / KC;                    // steps per row, even
+    static constexpr int PITCH = KC + 8;                           // bf16 per staged row: 16 bytes of padding (conflict-free 16-byte reads)
+    static constexpr int PIECES = FT * 2 * KS;                     // 16-byte pieces per matrix and term and step
+    static constexpr int NPT = (PIECES + 511) / 512;               // of them per thread
+};
 constexpr int FT_CAP = 512;    // entries of a source's candidate list
 constexpr int FT_OUT = 256;    // most candidates a source may hand to the exact re-rank
 
@@ -116,6 +125,7 @@ __device__ __forceinline__ int prune_row(const FilterArgs &a, u64 *list, int r, 
             int zeros = 0;
 #pragma unroll
             for (int j = 0; j < FT_CAP / 64; ++j) {
+                if (j * 64 >= n) continue;   // the same in every lane
                 const uint32_t img = (uint32_t)(k[j] >> 32);
                 zeros += __popcll(__ballot(k[j] != SENT && (img & hi_mask) == prefix && !((img >> bit) & 1u)));
             }
@@ -140,53 +150,65 @@ __device__ __forceinline__ int prune_row(const FilterArgs &a, u64 *list, int r, 
     return kept;
 }
 
-// 32 floats (step kc) of the workgroup's 128 source rows (from slot src0) and of 128 target rows (from
-// slot tgt0), both terms: 16 bytes per thread and piece, into registers
+// One step (16 KS floats from float kc * KC on) of the workgroup's 128 source rows (from slot src0)
+// and of 128 target rows (from slot tgt0), both terms, into registers: 16-byte pieces, NPT per thread
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));   // a plain vector: stays in registers where HIP's uint4 class does not
-struct StepRegs { u32x4 ah0, am0, bh0, bm0, ah1, am1, bh1, bm1; };
-template <int NCH>
-__device__ __forceinline__ void fetch_step(const FilterArgs &a, int64_t src0, int64_t tgt0, int kc, int tid, StepRegs &g) {
+template <int NPT>
+struct StepRegs { u32x4 ah[NPT], am[NPT], bh[NPT], bm[NPT]; };
+template <int NCH, bool ARES>
+__device__ __forceinline__ void fetch_step(const FilterArgs &a, int64_t src0, int64_t tgt0, int kc, int tid,
+                                           StepRegs<StepShape<NCH>::NPT> &g) {
+    typedef StepShape<NCH> S;
     constexpr int D = NCH * 32;
-    {
-        const int row = tid >> 2, q = tid & 3;
+#pragma unroll
+    for (int i = 0; i < S::NPT; ++i) {
+        const int idx = tid + 512 * i;
+        const int row = (S::PIECES % 512 != 0 && idx >= S::PIECES) ? 0 : idx / (2 * S::KS), q = (S::PIECES % 512 != 0 && idx >= S::PIECES) ? 0 : idx - row * (2 * S::KS);
         int64_t sa = src0 + row, sbv = tgt0 + row;
         if (sa >= a.n_slots) sa = a.n_slots - 1;
         if (sbv >= a.n_slots) sbv = a.n_slots - 1;
-        const size_t ga = (size_t)sa * D + kc * FT_KC + 8 * q, gb = (size_t)sbv * D + kc * FT_KC + 8 * q;
-        g.ah0 = *reinterpret_cast<const u32x4 *>(a.Xh + ga);
-        g.am0 = *reinterpret_cast<const u32x4 *>(a.Xm + ga);
-        g.bh0 = *reinterpret_cast<const u32x4 *>(a.Xh + gb);
-        g.bm0 = *reinterpret_cast<const u32x4 *>(a.Xm + gb);
-    }
-    {
-        const int row = (tid >> 2) + 64, q = tid & 3;
-        int64_t sa = src0 + row, sbv = tgt0 + row;
-        if (sa >= a.n_slots) sa = a.n_slots - 1;
-        if (sbv >= a.n_slots) sbv = a.n_slots - 1;
-        const size_t ga = (size_t)sa * D + kc * FT_KC + 8 * q, gb = (size_t)sbv * D + kc * FT_KC + 8 * q;
-        g.ah1 = *reinterpret_cast<const u32x4 *>(a.Xh + ga);
-        g.am1 = *reinterpret_cast<const u32x4 *>(a.Xm + ga);
-        g.bh1 = *reinterpret_cast<const u32x4 *>(a.Xh + gb);
-        g.bm1 = *reinterpret_cast<const u32x4 *>(a.Xm + gb);
+        const size_t ga = (size_t)sa * D + kc * S::KC + 8 * q, gb = (size_t)sbv * D + kc * S::KC + 8 * q;
+        if constexpr (!ARES) {
+            g.ah[i] = *reinterpret_cast<const u32x4 *>(a.Xh + ga);
+            g.am[i] = *reinterpret_cast<const u32x4 *>(a.Xm + ga);
+        }
+        g.bh[i] = *reinterpret_cast<const u32x4 *>(a.Xh + gb);
+        g.bm[i] = *reinterpret_cast<const u32x4 *>(a.Xm + gb);
     }
 }
 
+// Workgroup barrier that orders LDS traffic only: the global loads fetched ahead stay in flight
+// across it (__syncthreads would wait for them too)
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
+// Workgroup of eight wavefronts, 2 x 4: wavefront (wr, wc) owns the scores of source rows
+// 64 wr .. 64 wr + 63 against targets 32 wc .. 32 wc + 31 of the current 128.
 template <int NCH>
-__global__ __launch_bounds__(256, 2) void k_knn_filter(FilterArgs a) {
+__global__ __launch_bounds__(512) void k_knn_filter(FilterArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
+    // Rows of up to 128 floats: the workgroup's source rows stay in LDS, whole, for all of its work on
+    // them (fetched again for every 128 targets they were most of the traffic, and the traffic, not
+    // the matrix cores, set the pace); longer rows are staged 32 floats at a time like the targets.
+    typedef StepShape<NCH> S;
     constexpr int D = NCH * 32;
-    uint16_t *sA = reinterpret_cast<uint16_t *>(smem);             // [2 terms][FT][FT_PITCH]
-    uint16_t *sB = sA + 2 * FT * FT_PITCH;
-    unsigned char *tail = smem + (size_t)4 * FT * FT_PITCH * 2;
+    constexpr bool ARES = NCH <= 4;
+    constexpr int APITCH = ARES ? D + 8 : S::PITCH;                // bf16 per source row in LDS
+    constexpr int FT_PITCH = S::PITCH;
+    uint16_t *sA = reinterpret_cast<uint16_t *>(smem);             // [2 terms][FT][APITCH]
+    uint16_t *sB = sA + 2 * FT * APITCH;                           // [2 terms][FT][FT_PITCH]
+    unsigned char *tail = smem + (size_t)2 * FT * (APITCH + FT_PITCH) * 2;
     float *thr = reinterpret_cast<float *>(tail);                  // [FT] a target is listed iff its score <= thr
     float *w2 = thr + FT;                                          // [FT] twice the margin of the row
     int *cnt = reinterpret_cast<int *>(w2 + FT);                   // [FT] entries in the row's list
     int *flags = cnt + FT;                                         // [0]: some list is nearly full
     float *sc = reinterpret_cast<float *>(flags + 4) + (size_t)(threadIdx.x >> 6) * 1024;   // per wavefront: the scores of one block
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wr = w >> 1, wc = w & 1;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, wr = w >> 2, wc = w & 3;
     const int lrow = lane & 31, lhalf = lane >> 5;
     u64 *list = a.lists + (size_t)blockIdx.x * FT * FT_CAP;
     const float maxn = __uint_as_float(*a.maxnorm);
+    // a list is cut to what can still matter when it has grown to a few times P (early cuts make the
+    // threshold tight early), at the latest where the next 128 targets could overflow it
+    const int trigger = 3 * a.P + 61 < FT_CAP - FT ? 3 * a.P + 61 : FT_CAP - FT;
 
     for (int item = blockIdx.x; item < a.n_items; item += gridDim.x) {
         // source bucket of the item: the last b with blk_start[b] <= item
@@ -212,64 +234,87 @@ __global__ __launch_bounds__(256, 2) void k_knn_filter(FilterArgs a) {
         __syncthreads();
 
         // ---------------------------------------------------------------- filter: scores on the matrix cores
-        // 32 floats of every source and target row, both terms, per step: 16 bytes per thread and piece,
-        // fetched into registers one step ahead so that the loads fly while the matrix cores work
-        StepRegs g;
-        if (tn > 0) fetch_step<NCH>(a, sb + i0, tb, 0, tid, g);
+        // Every step stages 32 floats of the 128 source and 128 target rows through LDS.  Two register
+        // sets take turns, each asked for the step after next as soon as it has been written to LDS,
+        // so a fetch has two steps of matrix work to arrive.
+        if constexpr (ARES) {
+            if (tn > 0) {
+                for (int idx = tid; idx < FT * (D / 8); idx += 512) {
+                    const int row = idx / (D / 8), q = idx - row * (D / 8);
+                    int64_t sa = (int64_t)sb + i0 + row;
+                    if (sa >= a.n_slots) sa = a.n_slots - 1;
+                    *reinterpret_cast<u32x4 *>(sA + row * APITCH + 8 * q) = *reinterpret_cast<const u32x4 *>(a.Xh + (size_t)sa * D + 8 * q);
+                    *reinterpret_cast<u32x4 *>(sA + FT * APITCH + row * APITCH + 8 * q) = *reinterpret_cast<const u32x4 *>(a.Xm + (size_t)sa * D + 8 * q);
+                }
+            }
+        }
+        StepRegs<S::NPT> g0, g1;
+        const int n_steps = tn > 0 ? ((tn + FT - 1) / FT) * S::STEPS : 0;
+        if (n_steps > 0) {
+            fetch_step<NCH, ARES>(a, sb + i0, tb, 0, tid, g0);
+            fetch_step<NCH, ARES>(a, sb + i0, tb, 1, tid, g1);
+        }
+        int step = 0;
         for (int j0 = 0; j0 < tn; j0 += FT) {
-            f32x16 acc[2][2];
+            f32x16 acc[2];
 #pragma unroll
             for (int rb = 0; rb < 2; ++rb)
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb)
+                for (int i = 0; i < 16; ++i) acc[rb][i] = 0.0f;
+            const int col = 32 * wc + lrow;
+            const bool validc = j0 + col < tn;
+            const uint32_t tslot = (uint32_t)(tb + j0 + col);
+            const float hnv = validc ? a.hn[tb + j0 + col] : 0.0f;
+            // one step: the registers fetched two steps ago go to LDS, the same registers are asked for
+            // the step after next, then the matrix cores take this step from LDS
+            auto do_step = [&](StepRegs<S::NPT> &g, int kc) {
+                lds_barrier();
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[rb][cb][i] = 0.0f;
-            float hnv[2];
-#pragma unroll
-            for (int cb = 0; cb < 2; ++cb) {
-                const int col = 64 * wc + 32 * cb + lrow;
-                hnv[cb] = j0 + col < tn ? a.hn[tb + j0 + col] : 0.0f;
-            }
-#pragma unroll 1
-            for (int kc = 0; kc < NCH; ++kc) {
-                __syncthreads();
-                {
-                    const int lo = (tid >> 2) * FT_PITCH + 8 * (tid & 3), lo1 = lo + 64 * FT_PITCH;
-                    *reinterpret_cast<u32x4 *>(sA + lo) = g.ah0;
-                    *reinterpret_cast<u32x4 *>(sA + FT * FT_PITCH + lo) = g.am0;
-                    *reinterpret_cast<u32x4 *>(sB + lo) = g.bh0;
-                    *reinterpret_cast<u32x4 *>(sB + FT * FT_PITCH + lo) = g.bm0;
-                    *reinterpret_cast<u32x4 *>(sA + lo1) = g.ah1;
-                    *reinterpret_cast<u32x4 *>(sA + FT * FT_PITCH + lo1) = g.am1;
-                    *reinterpret_cast<u32x4 *>(sB + lo1) = g.bh1;
-                    *reinterpret_cast<u32x4 *>(sB + FT * FT_PITCH + lo1) = g.bm1;
+                for (int i = 0; i < S::NPT; ++i) {
+                    const int idx = tid + 512 * i;
+                    if (S::PIECES % 512 != 0 && idx >= S::PIECES) continue;
+                    const int row = idx / (2 * S::KS), q = idx - row * (2 * S::KS);
+                    const int lo = row * FT_PITCH + 8 * q;
+                    if constexpr (!ARES) {
+                        *reinterpret_cast<u32x4 *>(sA + lo) = g.ah[i];
+                        *reinterpret_cast<u32x4 *>(sA + FT * FT_PITCH + lo) = g.am[i];
+                    }
+                    *reinterpret_cast<u32x4 *>(sB + lo) = g.bh[i];
+                    *reinterpret_cast<u32x4 *>(sB + FT * FT_PITCH + lo) = g.bm[i];
                 }
-                __syncthreads();
+                lds_barrier();
                 {
-                    const bool same = kc + 1 < NCH;
-                    if (same || j0 + FT < tn) fetch_step<NCH>(a, sb + i0, tb + (same ? j0 : j0 + FT), same ? kc + 1 : 0, tid, g);
+                    // the step after next: the same place in this pass over the rows, or in the next 128
+                    // targets.  Asked for without condition (past the end the row numbers are clamped and the
+                    // data never used): a conditional load would make every later wait a wait for all loads.
+                    const int kn = kc + 2 < S::STEPS ? kc + 2 : kc + 2 - S::STEPS;
+                    fetch_step<NCH, ARES>(a, sb + i0, tb + j0 + (kc + 2 < S::STEPS ? 0 : FT), kn, tid, g);
                 }
 #pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    bf16x8 ah[2], am[2], bh[2], bm[2];
+                for (int ks = 0; ks < S::KS; ++ks) {
+                    bf16x8 ah[2], am[2];
+                    const int co = (32 * wc + lrow) * FT_PITCH + 16 * ks + 8 * lhalf;
+                    const bf16x8 bh = *reinterpret_cast<const bf16x8 *>(sB + co);
+                    const bf16x8 bm = *reinterpret_cast<const bf16x8 *>(sB + FT * FT_PITCH + co);
 #pragma unroll
                     for (int x = 0; x < 2; ++x) {
-                        const int ro = (64 * wr + 32 * x + lrow) * FT_PITCH + 16 * ks + 8 * lhalf;
-                        const int co = (64 * wc + 32 * x + lrow) * FT_PITCH + 16 * ks + 8 * lhalf;
+                        const int ro = (64 * wr + 32 * x + lrow) * APITCH + (ARES ? kc * S::KC : 0) + 16 * ks + 8 * lhalf;
                         ah[x] = *reinterpret_cast<const bf16x8 *>(sA + ro);
-                        am[x] = *reinterpret_cast<const bf16x8 *>(sA + FT * FT_PITCH + ro);
-                        bh[x] = *reinterpret_cast<const bf16x8 *>(sB + co);
-                        bm[x] = *reinterpret_cast<const bf16x8 *>(sB + FT * FT_PITCH + co);
+                        am[x] = *reinterpret_cast<const bf16x8 *>(sA + FT * APITCH + ro);
                     }
 #pragma unroll
-                    for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-                        for (int cb = 0; cb < 2; ++cb) {
-                            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bh[cb], acc[rb][cb], 0, 0, 0);
-                            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bm[cb], acc[rb][cb], 0, 0, 0);
-                            acc[rb][cb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am[rb], bh[cb], acc[rb][cb], 0, 0, 0);
-                        }
+                    for (int rb = 0; rb < 2; ++rb) {
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bh, acc[rb], 0, 0, 0);
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah[rb], bm, acc[rb], 0, 0, 0);
+                        acc[rb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(am[rb], bh, acc[rb], 0, 0, 0);
+                    }
                 }
+                ++step;
+            };
+#pragma unroll 1
+            for (int kc = 0; kc < S::STEPS; kc += 2) {
+                do_step(g0, kc);
+                do_step(g1, kc + 1);
             }
             // element i of a block in lane l: row (i / 4) * 8 + (l / 32) * 4 + i % 4, column l % 32
 #pragma unroll
@@ -278,43 +323,41 @@ __global__ __launch_bounds__(256, 2) void k_knn_filter(FilterArgs a) {
                 float4 t4[4];
 #pragma unroll
                 for (int g = 0; g < 4; ++g) t4[g] = *reinterpret_cast<const float4 *>(thr + 64 * wr + 32 * rb + 8 * g + 4 * lhalf);
+                // which of its sixteen elements are at or below their rows' thresholds: mostly none once
+                // the lists have filled
+                uint32_t hits = 0;
 #pragma unroll
-                for (int cb = 0; cb < 2; ++cb) {
-                    const int col = 64 * wc + 32 * cb + lrow;
-                    const bool validc = j0 + col < tn;
-                    const uint32_t tslot = (uint32_t)(tb + j0 + col);
-                    // most blocks hold nothing below any threshold once the lists have filled
-                    bool any = false;
+                for (int i = 0; i < 16; ++i) {
+                    const float tv = (i & 3) == 0 ? t4[i >> 2].x : ((i & 3) == 1 ? t4[i >> 2].y : ((i & 3) == 2 ? t4[i >> 2].z : t4[i >> 2].w));
+                    hits |= (hnv - acc[rb][i] <= tv ? 1u : 0u) << i;
+                }
+                if (!validc) hits = 0;
+                if (__ballot(hits != 0) == 0) continue;
+                // The block's scores go through LDS so that a lane can walk its own hits in an ordinary
+                // loop (unrolled over the sixteen elements it doubles the kernel's register count).  Each hit
+                // claims its place in its row's list by itself: the order inside a list is of no
+                // consequence, lists are cut by value and the survivors are ordered by their exact keys.
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float tv = (i & 3) == 0 ? t4[i >> 2].x : ((i & 3) == 1 ? t4[i >> 2].y : ((i & 3) == 2 ? t4[i >> 2].z : t4[i >> 2].w));
-                        any |= hnv[cb] - acc[rb][cb][i] <= tv;
-                    }
-                    if (__ballot(any && validc) == 0) continue;
-                    // The block's scores go through LDS so that the walk over its sixteen rows is an ordinary
-                    // loop (unrolled it doubles the kernel's register count).  Each hit claims its place in its
-                    // row's list by itself: the order inside a list is of no consequence, lists are cut by
-                    // value and the survivors are ordered by their exact keys.
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) sc[i * 64 + lane] = hnv[cb] - acc[rb][cb][i];
-#pragma unroll 1
-                    for (int i = 0; i < 16; ++i) {
-                        const int row = 64 * wr + 32 * rb + (i >> 2) * 8 + (i & 3) + 4 * lhalf;
-                        const float s = sc[i * 64 + lane];
-                        if (validc && s <= thr[row] && !(a.exclude_self && tslot == (uint32_t)(sb + i0 + row))) {
-                            const int pos = atomicAdd(&cnt[row], 1);
-                            if (pos < FT_CAP) list[(size_t)row * FT_CAP + pos] = ((u64)dist_image(s) << 32) | (u64)tslot;
-                            if (pos >= FT_CAP - FT) flags[0] = 1;
-                        }
-                    }
+                for (int i = 0; i < 16; ++i) sc[i * 64 + lane] = hnv - acc[rb][i];
+                while (hits) {
+                    const int i = __builtin_ctz(hits);
+                    hits &= hits - 1;
+                    const int row = 64 * wr + 32 * rb + (i >> 2) * 8 + (i & 3) + 4 * lhalf;
+                    if (a.exclude_self && tslot == (uint32_t)(sb + i0 + row)) continue;
+                    const float s = sc[i * 64 + lane];
+                    const int pos = atomicAdd(&cnt[row], 1);
+                    if (pos < FT_CAP) list[(size_t)row * FT_CAP + pos] = ((u64)dist_image(s) << 32) | (u64)tslot;
+                    if (pos >= trigger) flags[0] = 1;
                 }
             }
-            __syncthreads();
+            lds_barrier();   // the fetches for the next 128 targets stay in flight
             if (flags[0]) {
-                // lists that the next step could overflow are cut to what can still matter
+                // lists that have grown are cut to what can still matter (their entries were written by
+                // several wavefronts: wait for those stores)
+                __syncthreads();
                 u64 k[FT_CAP / 64];
-                for (int r = w; r < FT; r += 4)
-                    if (cnt[r] > FT_CAP - FT) (void)prune_row(a, list, r, lane, thr, w2, cnt, k);
+                for (int r = w; r < FT; r += 8)
+                    if (cnt[r] > trigger) (void)prune_row(a, list, r, lane, thr, w2, cnt, k);
                 __syncthreads();
                 if (tid == 0) flags[0] = 0;
             }
@@ -322,7 +365,7 @@ __global__ __launch_bounds__(256, 2) void k_knn_filter(FilterArgs a) {
         __syncthreads();
 
         // ---------------------------------------------------------------- final cut: the candidates of every row
-        for (int r = w; r < FT; r += 4) {
+        for (int r = w; r < FT; r += 8) {
             if (i0 + r >= sn) continue;
             const int64_t slot_u = (int64_t)sb + i0 + r;
             u64 k[FT_CAP / 64];
@@ -390,8 +433,8 @@ __global__ __launch_bounds__(64) void k_knn_rerank(FilterArgs a) {
 
 template <int NCH>
 grab_status launch_filter_t(grab_index *ix, const FilterArgs &a, unsigned grid) {
-    const size_t lds = (size_t)4 * FT * FT_PITCH * 2 + (size_t)FT * 12 + 16 + (size_t)4 * 1024 * 4;
-    k_knn_filter<NCH><<<dim3(grid), dim3(256), lds, ix->stream>>>(a);
+    const size_t lds = (size_t)2 * FT * ((NCH <= 4 ? NCH * 32 + 8 : StepShape<NCH>::PITCH) + StepShape<NCH>::PITCH) * 2 + (size_t)FT * 12 + 16 + (size_t)8 * 1024 * 4;
+    k_knn_filter<NCH><<<dim3(grid), dim3(512), lds, ix->stream>>>(a);
     GRAB_HIP(ix, hipGetLastError());
     const size_t lds2 = (size_t)FT_OUT * 8 + (EvalShape<NCH>::QREG ? 0 : (size_t)NCH * 32 * 4);
     if (a.P > 64) k_knn_rerank<NCH, 2><<<dim3((unsigned)a.n_slots), dim3(64), lds2, ix->stream>>>(a);
