@@ -311,7 +311,9 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBS, 4), "traffic": traffic,
                 # achieved / frac price the ALGORITHMIC bytes (what the method must move); the traffic_* pair
                 # prices the bytes the counters saw crossing from the memory fabric into L2
-                "frac_kind": "algorithmic bytes / kernel time / HBM peak",
+                "frac_kind": "algorithmic bytes / kernel time / HBM peak" + ("; cache-assisted: more bytes per second enter L2 than a pure gather of "
+                                                                               "random rows sustains on this index, shared rows come from the Infinity Cache"
+                                                                               if traffic is not None and traffic / (avg_beam_ms * 1e-3) / 1e9 > gather_gbs else ""),
                 "traffic_gbs": None if traffic is None else round(traffic / (avg_beam_ms * 1e-3) / 1e9, 1),
                 "traffic_frac": None if traffic is None else round(traffic / (avg_beam_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
                 "note": "rows served by L2 lower traffic below the algorithmic bytes; the byte counters sit between L2 and the "

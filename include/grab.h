@@ -85,7 +85,9 @@ typedef enum {
                                 down; in [0, 1], default 0.2 (the paper's example)         */
 } grab_param;
 
-/* Creates an empty index for `dim`-dimensional fp32 vectors under `metric`.
+/* Creates an empty index for `dim`-dimensional fp32 vectors under `metric`: the container of the
+ * unified memory layout of Section 4.2.4 (feature matrix, adjacency matrix, bucket <-> index maps),
+ * all of it in device memory.
  * `hip_stream` is a hipStream_t (NULL = the default stream); it must outlive the index. */
 grab_status grab_create(grab_index **out, int32_t dim, int32_t metric, void *hip_stream);
 
@@ -228,11 +230,13 @@ grab_status grab_set_param(grab_index *ix, int32_t which, double value);
  * out[4] k_remote, out[5] dim, out[6] metric, out[7] 1 if a graph is loaded. (host array) */
 grab_status grab_get_sizes(const grab_index *ix, int64_t out[8]);
 
-/* Copies out the layout: bucket_table[B][6] = {base, n_sorted, n_total, cap, min_attr,
+/* Copies out the layout of Section 4.2.4 (the maps M_B2I / M_I2B, here the bucket table and the
+ * id <-> slot arrays): bucket_table[B][6] = {base, n_sorted, n_total, cap, min_attr,
  * max_attr}, id2slot[objects], slot2id[slots].  Any pointer may be NULL to skip it. */
 grab_status grab_get_layout(grab_index *ix, int32_t *bucket_table, uint32_t *id2slot, uint32_t *slot2id);
 
-/* Copies out the adjacency in slot space: adj[slots][k_local + k_remote]. */
+/* Copies out the adjacency matrix of Section 4.2.3 (fixed degree, local entries first, then the
+ * remote ones) in slot space: adj[slots][k_local + k_remote]. */
 grab_status grab_get_graph(grab_index *ix, uint32_t *adj_slots);
 
 /* Copies out the stored feature rows and attributes in slot space (either may be NULL). */
@@ -246,7 +250,9 @@ grab_status grab_get_rows(grab_index *ix, float *vectors_slots, int32_t *attr_sl
 grab_status grab_select_range(grab_index *ix, const int32_t *lo, const int32_t *hi, int64_t nq,
                               int32_t beam, int32_t *info, uint32_t *seeds);
 
-/* Per-query counters of the most recent grab_search_range: per_query[nq][8] uint32 =
+/* Per-query counters of the most recent grab_search_range, one per step of Algorithm 2 (iterations
+ * of its loop, PopUnvisited, ComputeDistance, the seeds of line 2, the range pre-check of its
+ * lines 8-10, the visited test): per_query[nq][8] uint32 =
  * {iterations, parents expanded, distance evaluations (seeds included), seed evaluations,
  *  neighbours rejected by the scalar pre-check, slots whose attribute had to be read
  *  (appended tails of the two edge buckets), visited-set size, stop reason

@@ -50,6 +50,30 @@ def test_build_graph_matches_oracle(n, dim, B, kl, kr, pool, metric, n_cap):
     ix.close()
 
 
+@pytest.mark.parametrize("kind", ["copies", "far_from_origin", "a_few_copies"])
+def test_build_graph_where_the_score_filter_cannot_decide(kind):
+    # construction filters nearest-neighbour candidates by low-precision scores with a proven margin and
+    # re-ranks the survivors exactly; where the margin admits more candidates than its lists hold (hundreds
+    # of equal distances; distances tiny against the norms) it must fall back to evaluating every pair
+    from paper_2604_16402_amd import binding
+    rng = np.random.default_rng(17)
+    n, dim, B, kl, kr, pool = 3000, 64, 3, 16, 3, 32
+    if kind == "copies":                 # two distinct vectors: about 500 ties at distance zero per bucket
+        X = rng.standard_normal((2, dim)).astype(np.float32)[rng.integers(0, 2, n)]
+    elif kind == "a_few_copies":         # 40 distinct vectors: ties well inside what the lists hold
+        X = rng.standard_normal((40, dim)).astype(np.float32)[rng.integers(0, 40, n)]
+    else:                                # a tight cloud a thousand units from the origin
+        X = (1000.0 + 0.01 * rng.standard_normal((n, dim))).astype(np.float32)
+    a = rng.integers(0, n, n).astype(np.int32)
+    ora = O.Index(X, a, B)
+    ora.build_graph(kl, kr, pool=pool, threads=O.max_threads())
+    ix = binding.Index(dim)
+    ix.build_buckets(X, a, B)
+    ix.build_graph(kl, kr, pool)
+    assert np.array_equal(ix.get_graph(), ora.A)
+    ix.close()
+
+
 def test_build_graph_after_append_covers_the_tails():
     from paper_2604_16402_amd import binding
     cfg, X, a = _case(2400, 64, 4, W.L2SQ, seed=9)
