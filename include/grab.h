@@ -130,7 +130,9 @@ grab_status grab_load_graph(grab_index *ix, const uint32_t *local_adj, int32_t k
  * The paper draws remote candidates from a global graph built by a third-party pipeline
  * (Algorithm 1); here they come from exact search in the target bucket (GRAB_P_REMOTE_MODE 0) or
  * from the library's own search over all other buckets (mode 1, see grab_build_remote).  Distances
- * use the same fixed fp32 summation order as the search, ties go to the smaller slot.
+ * use the same fixed fp32 summation order as the search, ties go to the smaller slot.  (The nearest
+ * objects are found exactly: low-precision scores from the matrix cores only narrow each object's
+ * targets down, with a proven margin, to the few whose fixed-order distances are then taken.)
  * pool = 0 means min(4 * k_local, 128): wide enough to reach past a node's own cluster, which is
  * what gives the graph its long links.  Requires 1 <= k_local <= 64, 0 <= k_remote <= 64,
  * k_local <= pool <= 128.  Errors: GRAB_EINVAL, GRAB_ESTATE (no layout), GRAB_ENOMEM, GRAB_EHIP;
