@@ -130,55 +130,6 @@ __global__ void k_iota(uint32_t *__restrict__ a, int64_t n) {
     if (i < n) a[i] = (uint32_t)i;
 }
 
-// Distances from the row held by each group of eight lanes (mine: piece 8c+sub of that group's
-// row) to the rows rows[0..n), the same list for every group, in the summation order of
-// eval_batch with `mine` in the place of the query.  f(j, s) is called by every lane of a group
-// with the distance s between its row and rows[j].
-// `done()` is asked after every batch of rows (the same answer in every lane): true ends the scan early.
-template <int NCH, typename F, typename S>
-__device__ __forceinline__ void group_vs_rows(const float *__restrict__ X, const float4 (&mine)[NCH], const uint32_t *rows,
-                                              int n, int lane, int metric, F &&f, S &&done) {
-    constexpr int RR = NCH <= 2 ? 8 : (NCH <= 4 ? 4 : 2);   // rows in flight
-    constexpr int D4 = NCH * 8;
-    const int sub = lane & 7;
-    for (int j0 = 0; j0 < n; j0 += RR) {
-        float4 buf[RR][NCH];
-#pragma unroll
-        for (int r = 0; r < RR; ++r) {
-            const uint32_t v = j0 + r < n ? rows[j0 + r] : rows[j0];
-            const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v * D4 + sub;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) buf[r][c] = row[c * 8];
-        }
-#pragma unroll
-        for (int r = 0; r < RR; ++r) {
-            float acc = 0.0f;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const float4 qv = mine[c], x = buf[r][c];
-                if (metric == GRAB_L2SQ) {
-                    const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
-                    acc = __builtin_fmaf(dx, dx, acc);
-                    acc = __builtin_fmaf(dy, dy, acc);
-                    acc = __builtin_fmaf(dz, dz, acc);
-                    acc = __builtin_fmaf(dw, dw, acc);
-                } else {
-                    acc = __builtin_fmaf(qv.x, x.x, acc);
-                    acc = __builtin_fmaf(qv.y, x.y, acc);
-                    acc = __builtin_fmaf(qv.z, x.z, acc);
-                    acc = __builtin_fmaf(qv.w, x.w, acc);
-                }
-            }
-            float t = acc;
-            t += dpp_move<0xB1>(t);
-            t += dpp_move<0x4E>(t);
-            t += dpp_move<0x141>(t);
-            if (j0 + r < n) f(j0 + r, metric == GRAB_L2SQ ? t : -t);
-        }
-        if (done()) break;
-    }
-}
-
 // Work counters of one insertion call (device, 64-bit), reported by grab_get_append_stats
 enum { ST_REQ_LOCAL = 0, ST_REQ_REMOTE, ST_GROUPS_LOCAL, ST_GROUPS_REMOTE, ST_APPLIED_LOCAL, ST_APPLIED_REMOTE, ST_SCANNED,
        ST_REMOTE_ROWS, ST_LOCAL_PASS, ST_SEARCH_EVALS, ST_SEARCH_PARENTS, ST_SPARE, ST_N };

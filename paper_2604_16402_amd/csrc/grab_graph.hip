@@ -204,6 +204,60 @@ __global__ __launch_bounds__(64) void k_prune(PruneArgs a) {
     const int nc = __popcll(validm[0]) + __popcll(validm[1]);   // valid candidates form a prefix
     const u64 lt_mask = (1ull << lane) - 1ull;
     int nk = 0;
+    if constexpr (EvalShape<NCH>::QREG) {
+        // eight candidates at a time, one per group of eight lanes: their rows are loaded together, each
+        // is compared with the rows kept so far (the scan ends as soon as all eight are hidden) and, where
+        // two or more survive that, with the other survivors; the chunk is then resolved in candidate
+        // order exactly as a one-by-one scan would
+        uint32_t *alive = reinterpret_cast<uint32_t *>(dtmp + 128);
+        uint32_t *alive_g = alive + 8;
+        float *pair = reinterpret_cast<float *>(alive_g + 8);   // [8][8] distances between survivors
+        const int sub = lane & 7, grp = lane >> 3;
+        for (int t0 = 0; t0 < nc; t0 += 8) {
+            const int G = min(8, nc - t0);
+            const int mt = t0 + grp < nc ? t0 + grp : t0;
+            const uint32_t myc = mt < 64 ? (uint32_t)__shfl((int)cs[0], mt) : (uint32_t)__shfl((int)cs[1], mt - 64);
+            const float mydq = mt < 64 ? __shfl(cd[0], mt) : __shfl(cd[1], mt - 64);
+            float4 mine[NCH];
+            {
+                const float4 *row = reinterpret_cast<const float4 *>(a.X) + (size_t)myc * (NCH * 8) + sub;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) mine[c] = row[c * 8];
+            }
+            bool hid = t0 + grp >= nc;
+            group_vs_rows<NCH>(a.X, mine, kept, nk, lane, a.metric, [&](int, float s) { hid |= !(mydq < s); },
+                               [&]() { return __ballot(!hid) == 0; });
+            const u64 hm = __ballot(hid);
+            int na = 0;
+            for (int g = 0; g < G; ++g)
+                if (((hm >> (8 * g)) & 1ull) == 0) {
+                    const uint32_t cg = (uint32_t)__shfl((int)myc, 8 * g);
+                    if (lane == 0) { alive[na] = cg; alive_g[na] = (uint32_t)g; }
+                    ++na;
+                }
+            __syncthreads();
+            if (na > 1)
+                group_vs_rows<NCH>(a.X, mine, alive, na, lane, a.metric, [&](int h, float s) { if (sub == 0) pair[grp * 8 + alive_g[h]] = s; },
+                                   []() { return false; });
+            __syncthreads();
+            uint32_t keptmask = 0;
+            for (int g = 0; g < G; ++g) {
+                const int t = t0 + g;
+                const float dqc = __shfl(mydq, 8 * g);
+                bool ok = ((hm >> (8 * g)) & 1ull) == 0;
+                for (int h = 0; h < g; ++h)
+                    if ((keptmask >> h) & 1u) ok = ok && (dqc < pair[g * 8 + h]);
+                const uint32_t cg = (uint32_t)__shfl((int)myc, 8 * g);   // every lane takes part in the exchange
+                if (ok) {
+                    if (lane == 0) kept[nk] = cg;
+                    keptm[t >> 6] |= 1ull << (t & 63);
+                    keptmask |= 1u << g;
+                    ++nk;
+                }
+            }
+            __syncthreads();
+        }
+    } else {
     for (int t = 0; t < nc; ++t) {
         const uint32_t c = t < 64 ? (uint32_t)__shfl((int)cs[0], t) : (uint32_t)__shfl((int)cs[1], t - 64);
         const float dqc = t < 64 ? __shfl(cd[0], t) : __shfl(cd[1], t - 64);
@@ -222,6 +276,7 @@ __global__ __launch_bounds__(64) void k_prune(PruneArgs a) {
             ++nk;
         }
         __syncthreads();
+    }
     }
     const int nk0 = __popcll(keptm[0]), nr0 = __popcll(~keptm[0] & validm[0]);
 #pragma unroll
@@ -303,7 +358,7 @@ grab_status launch_graph_t(grab_index *ix, const KnnArgs *k, const PruneArgs *p,
         if (k->P > 64) k_knn<NCH, 2><<<dim3(tiles, (unsigned)ix->B), dim3(256), 0, ix->stream>>>(*k);
         else k_knn<NCH, 1><<<dim3(tiles, (unsigned)ix->B), dim3(256), 0, ix->stream>>>(*k);
     } else {
-        size_t lds = 128 * 4 * 2 + (EvalShape<NCH>::QREG ? 0 : (size_t)ix->dim * 4);
+        size_t lds = 128 * 4 * 2 + (EvalShape<NCH>::QREG ? (16 + 64) * 4 : (size_t)ix->dim * 4);
         k_prune<NCH><<<dim3((unsigned)ix->n_slots), dim3(64), lds, ix->stream>>>(*p);
     }
     GRAB_HIP(ix, hipGetLastError());
