@@ -66,8 +66,10 @@ static void free_buf(DevBuf &b) {
 
 static void drop_layout(grab_index *ix) {
     (void)hipFree(ix->X); (void)hipFree(ix->attr); (void)hipFree(ix->slot2id); (void)hipFree(ix->id2slot);
-    (void)hipFree(ix->table); (void)hipFree(ix->A);
+    (void)hipFree(ix->table); (void)hipFree(ix->A); (void)hipFree(ix->fence);
     if (ix->h_table) (void)hipHostFree(ix->h_table);
+    ix->fence = nullptr;
+    ix->order_dirty = true;   // another bucket count: the launch order's counters are cleared before their next use
     ix->X = nullptr; ix->attr = nullptr; ix->slot2id = nullptr; ix->id2slot = nullptr; ix->table = nullptr;
     ix->A = nullptr; ix->h_table = nullptr;
     ix->n = ix->n_slots = 0; ix->B = 0; ix->kl = ix->kr = 0; ix->has_graph = false;
@@ -226,6 +228,7 @@ grab_status grab_build_buckets(grab_index *ix, const float *vectors, const int32
     B_HIP(hipMalloc((void **)&ix->slot2id, n_slots * 4));
     B_HIP(hipMalloc((void **)&ix->id2slot, n_slots * 4));
     B_HIP(hipMalloc((void **)&ix->table, sizeof(int32_t) * T_COLS * n_buckets));
+    B_HIP(hipMalloc((void **)&ix->fence, sizeof(int32_t) * (size_t)(n_slots / GRAB_FENCE + n_buckets + 1)));
     B_HIP(hipHostMalloc((void **)&ix->h_table, sizeof(int32_t) * ((size_t)T_COLS * n_buckets + n_buckets + 4), hipHostMallocDefault));
     B_HIP(hipMemsetAsync(ix->X, 0, n_slots * row, ix->stream));
     B_HIP(hipMemsetAsync(ix->attr, 0, n_slots * 4, ix->stream));

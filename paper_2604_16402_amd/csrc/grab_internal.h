@@ -16,7 +16,13 @@
 #define GRAB_WAVE 64
 // counter block of the search's launch order: one 128-byte line per bin, one more for the tail
 #define GRAB_BIN_STRIDE 32
-#define GRAB_BIN_BLOCK_BYTES ((size_t)(GRAB_BIN_STRIDE * (GRAB_MAX_BUCKETS + 2)) * 4)
+#define GRAB_BIN_BLOCK_WORDS (GRAB_BIN_STRIDE * (GRAB_MAX_BUCKETS + 2))
+#define GRAB_BIN_BLOCK_BYTES ((size_t)GRAB_BIN_BLOCK_WORDS * 4)
+// Fence of a bucket: every GRAB_FENCE-th attribute of its sorted prefix, in one array for all
+// buckets; bucket b's entries start at grab_fence_offset(base of the bucket's slab, b) and never
+// reach the next bucket's (a slab of c slots holds at most c / GRAB_FENCE + 1 entries).
+#define GRAB_FENCE 128
+__host__ __device__ inline int64_t grab_fence_offset(int64_t slab_base, int32_t b) { return slab_base / GRAB_FENCE + b; }
 
 // The vector lengths the kernels are built for, in 32-float (128-byte) units: every kernel that
 // reads feature rows is instantiated once per entry, so that a whole row's loads can be issued
@@ -89,6 +95,7 @@ struct grab_index {
     int32_t B = 0;
     float *X = nullptr;          // [n_slots][dim]
     int32_t *attr = nullptr;     // [n_slots]
+    int32_t *fence = nullptr;    // every GRAB_FENCE-th attribute of each bucket's sorted prefix (see k_fence)
     uint32_t *slot2id = nullptr; // [n_slots]
     uint32_t *id2slot = nullptr; // [n_slots] (ids grow up to the slot count)
     int32_t *table = nullptr;    // [B][6] device copy
@@ -109,6 +116,7 @@ struct grab_index {
     DevBuf q_bin, q_rank, q_order, bin_count;
     int64_t last_nq = 0;
     bool order_dirty = true;     // the bin counters of the launch order may not be zero
+    int order_block = 0;         // which of the two counter blocks the next counted launch order uses
     const uint32_t *last_counters = nullptr;   // where the most recent search wrote its counters
     std::vector<DevBuf> app;     // append's work arena
     DevBuf app_stats;            // work counters of the last insertion (12 x uint64)
@@ -161,7 +169,12 @@ struct SearchLaunch {
     float *out_dist;    // device [nq][k]
     bool out_slots;
     // launch order (all nullptr: query i runs in workgroup i): see grab_plan_order
-    int32_t *q_bin = nullptr, *bin_count = nullptr;
+    int32_t *q_bin = nullptr, *q_rank = nullptr;
+    // counters of the bins: two blocks of GRAB_BIN_BLOCK_BYTES used in turn (order_block says which
+    // is next; each k_order clears the block of the call before), or one block that is cleared
+    // before every use (order_block null)
+    int32_t *bin_count = nullptr;
+    int *order_block = nullptr;
     uint32_t *order = nullptr;   // [order_len]: query of each workgroup, GRAB_EMPTY for none
     int64_t order_len = 0;
     bool *order_dirty = nullptr; // host flag: bin_count may not be zero (null: always clear it first)

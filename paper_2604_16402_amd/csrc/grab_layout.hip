@@ -100,6 +100,18 @@ __global__ void k_load_graph(const uint32_t *__restrict__ local, int32_t kl, con
     A[(int64_t)self * K + j] = out;
 }
 
+// Fence of every bucket: entry i of bucket b = the attribute at position i * GRAB_FENCE of the
+// bucket's sorted prefix.  Range selection searches the few cache lines of a fence first and then
+// the GRAB_FENCE - 1 attributes between two of its entries (Algorithm 2, line 1: the valid part of
+// an edge bucket).  The sorted prefix of a bucket never changes after the layout is built
+// (insertion appends to the tail), so neither does the fence.  blockIdx.y = bucket.
+__global__ void k_fence(const int32_t *__restrict__ table, const int32_t *__restrict__ attr, int32_t *__restrict__ fence) {
+    const int b = blockIdx.y;
+    const int32_t *t = table + T_COLS * b;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i * GRAB_FENCE < t[T_NSORT]) fence[grab_fence_offset(t[T_BASE], b) + i] = attr[(int64_t)t[T_BASE] + i * GRAB_FENCE];
+}
+
 inline unsigned blocks_for(int64_t work) { return (unsigned)((work + TPB - 1) / TPB); }
 
 }  // namespace
@@ -136,6 +148,9 @@ grab_status grab_launch_build(grab_index *ix, const float *d_vectors, const int3
     k_permute_rows<<<blocks_for(n * row_f4), TPB, 0, st>>>((const float4 *)d_vectors, ids_s, n, B, slack, row_f4,
                                                            (float4 *)ix->X);
     k_table<<<blocks_for(B), TPB, 0, st>>>(keys_s, n, B, slack, ix->table);
+    // a bucket's sorted prefix holds at most ceil(n / B) objects
+    k_fence<<<dim3(blocks_for(((n + B - 1) / B + GRAB_FENCE - 1) / GRAB_FENCE), (unsigned)B), TPB, 0, st>>>(ix->table, ix->attr,
+                                                                                                             ix->fence);
     BUILD_HIP(hipGetLastError());
     BUILD_HIP(hipMemcpyAsync(ix->h_table, ix->table, sizeof(int32_t) * T_COLS * B, hipMemcpyDeviceToHost, st));
     BUILD_HIP(hipStreamSynchronize(st));

@@ -83,10 +83,12 @@ extern "C" grab_status grab_search_range_noalloc(grab_index *ix, const float *qu
     s.out_ids = out_ids; s.out_dist = out_dist;
     if (nq >= 2048) {   // the launch order of grab_search_range, in the same parts of the array every time
         s.q_bin = reinterpret_cast<int32_t *>(base + OFF_QBIN);
+        s.q_rank = reinterpret_cast<int32_t *>(base + OFF_QRANK);
         s.bin_count = reinterpret_cast<int32_t *>(base + OFF_BINS);
         s.order = reinterpret_cast<uint32_t *>(base + OFF_ORDER);
         s.order_len = grab_order_len(nq);
-        s.order_dirty = nullptr;   // the array is shared by every handle on this GPU: clear the counters each time
+        s.order_dirty = nullptr;   // the array is shared by every handle on this GPU: one counter block,
+        s.order_block = nullptr;   // cleared before each use
     }
     ix->timed = false;
     if (ix->profile) GRAB_HIP(ix, hipEventRecord(ix->ev[0], ix->stream));

@@ -17,44 +17,44 @@ __device__ __forceinline__ uint32_t mix32(uint32_t x) {
     return x;
 }
 
-// first index i in sorted a[0..n) with a[i] >= key (strict=false) or a[i] > key (strict=true):
-// a 64-way search, each step probing 64 evenly spaced positions with the whole wave
-__device__ int wave_bound(const int32_t *__restrict__ a, int n, int key, bool strict, int lane) {
-    int lo = 0, hi = n;
-    while (hi > lo) {
-        int chunk = (hi - lo + 63) >> 6;
-        int pos = lo + lane * chunk;
-        bool below = false;
-        if (pos < hi) {
-            int x = a[pos];
-            below = strict ? (x <= key) : (x < key);
-        }
-        int c = __popcll(__ballot(below));  // sorted input: the first c probes are below
-        if (c == 0) {
-            hi = lo;
-        } else {
-            int nlo = lo + (c - 1) * chunk + 1;
-            int nhi = lo + c * chunk;
-            hi = nhi < hi ? nhi : hi;
-            lo = nlo;
-        }
-    }
-    return lo;
+// ---- half a wavefront per query ------------------------------------------------------------------
+// Bucket selection and seeding are a chain of memory round trips with little work between them, so
+// two queries share a wavefront: lanes 0-31 serve one, lanes 32-63 the other, and a batch of
+// 10,000 queries fits the device in one round of wavefronts.
+__device__ __forceinline__ int half_sum(int v) {
+#pragma unroll
+    for (int m = 16; m > 0; m >>= 1) v += __shfl_xor(v, m);
+    return v;
 }
+// the 32 bits of a ballot that belong to the caller's half
+__device__ __forceinline__ uint32_t half_ballot(bool p, int half) { return (uint32_t)(__ballot(p) >> (32 * half)); }
 
-// two searches of wave_bound's kind in lockstep, so that their memory round trips overlap
-__device__ void wave_bound2(const int32_t *__restrict__ a1, int n1, int key1, bool strict1,
-                            const int32_t *__restrict__ a2, int n2, int key2, bool strict2, int lane, int &r1, int &r2) {
-    int lo1 = 0, hi1 = n1, lo2 = 0, hi2 = n2;
-    while (hi1 > lo1 || hi2 > lo2) {
-        const int ch1 = (hi1 - lo1 + 63) >> 6, ch2 = (hi2 - lo2 + 63) >> 6;
-        const int p1 = lo1 + lane * ch1, p2 = lo2 + lane * ch2;
-        const bool act1 = hi1 > lo1 && p1 < hi1, act2 = hi2 > lo2 && p2 < hi2;
-        int x1 = 0, x2 = 0;
-        if (act1) x1 = a1[p1];
-        if (act2) x2 = a2[p2];
-        const int c1 = __popcll(__ballot(act1 && (strict1 ? (x1 <= key1) : (x1 < key1))));
-        const int c2 = __popcll(__ballot(act2 && (strict2 ? (x2 <= key2) : (x2 < key2))));
+// Two searches per half-wave in lockstep, so that their memory round trips overlap:
+// r1 = first index i of sorted a1[0..n1) with a1[i] >= key1, r2 = first index of sorted a2[0..n2)
+// with a2[i] > key2.  A 128-way search: each step probes 128 evenly spaced positions, four per
+// lane, which settles 16,384 entries in two round trips.  `on` = this half searches at all; the
+// loop runs until both halves are done.
+__device__ void half_bound2(const int32_t *__restrict__ a1, int n1, int key1, const int32_t *__restrict__ a2, int n2, int key2,
+                            bool on, int half, int hl, int &r1, int &r2) {
+    int lo1 = 0, hi1 = on ? n1 : 0, lo2 = 0, hi2 = on ? n2 : 0;
+    while (__any(hi1 > lo1 || hi2 > lo2)) {
+        const int ch1 = (hi1 - lo1 + 127) >> 7, ch2 = (hi2 - lo2 + 127) >> 7;
+        int x1[4], x2[4];
+        bool act1[4], act2[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {      // probe i = 4 * hl + j of the step
+            const int p1 = lo1 + (4 * hl + j) * ch1, p2 = lo2 + (4 * hl + j) * ch2;
+            act1[j] = p1 < hi1; act2[j] = p2 < hi2;
+            x1[j] = 0; x2[j] = 0;
+            if (act1[j]) x1[j] = a1[p1];
+            if (act2[j]) x2[j] = a2[p2];
+        }
+        int c1 = 0, c2 = 0;     // sorted input: the first c probes are below
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            c1 += __popc(half_ballot(act1[j] && x1[j] < key1, half));
+            c2 += __popc(half_ballot(act2[j] && x2[j] <= key2, half));
+        }
         if (hi1 > lo1) {
             if (c1 == 0) {
                 hi1 = lo1;
@@ -82,76 +82,89 @@ __device__ void wave_bound2(const int32_t *__restrict__ a1, int n1, int key1, bo
 // Algorithm 2 lines 1-2: the run of buckets whose [min,max] meets [lo,hi]; the valid part of
 // the sorted prefix of the two edge buckets by search; the seed population (valid sorted part
 // then appended tail of every selected bucket, in bucket order) and one stratified, jittered
-// seed per stratum.  One wavefront per query.  The bucket table is read once, into LDS; the two
-// searches run in lockstep.
+// seed per stratum.  Half a wavefront per query (workgroup w: queries 2w and 2w + 1).  The bucket
+// table is read once, into LDS; the two searches of a query run in lockstep.
 //
-// The same launch files the query for the launch order (q_bin etc. non-null): queries that select
+// The same launch files the query for the launch order (q_bin non-null): queries that select
 // the same buckets read the same vectors, so the search runs them grouped by first selected
 // bucket, each XCD taking contiguous runs of that order (see k_order).  bin of a query = its first
 // selected bucket (the bucket it is scoped to, for a candidate search); bin B = nothing selected.
-// This launch only counts the bins (atomics whose result nobody waits for); k_order ranks and
-// places.  Only the order in which queries run changes; every query's result and counters are
-// what they are in any order.
+// This launch counts the bins and hands every query its rank inside its bin (one atomic per query,
+// issued early, its answer picked up at the end); k_order turns bins and ranks into positions.
+// Only the order in which queries run changes; every query's result and counters are what they
+// are in any order.
 __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ table, int32_t B,
                                                     const int32_t *__restrict__ attr,
                                                     const int32_t *__restrict__ lo_, const int32_t *__restrict__ hi_,
-                                                    const int32_t *__restrict__ only_bucket, int32_t S, uint32_t salt,
+                                                    const int32_t *__restrict__ only_bucket, int64_t nq, int32_t S, uint32_t salt,
                                                     QueryPlan *__restrict__ plans, uint32_t *__restrict__ seeds,
-                                                    int32_t *__restrict__ q_bin, int32_t *__restrict__ bin_count) {
+                                                    const int32_t *__restrict__ fence, int32_t *__restrict__ q_bin,
+                                                    int32_t *__restrict__ q_rank, int32_t *__restrict__ bin_count) {
     extern __shared__ int32_t sm_sel[];
-    int32_t *tbase = sm_sel, *tnsort = sm_sel + B, *tntot = sm_sel + 2 * B, *pre = sm_sel + 3 * B;   // pre[B + 1]
-    const int64_t q = blockIdx.x;
-    const int lane = threadIdx.x;
-    const int lo = lo_[q], hi = hi_[q];
+    const int lane = threadIdx.x, half = lane >> 5, hl = lane & 31;
+    int32_t *tbase = sm_sel, *tnsort = sm_sel + B, *tntot = sm_sel + 2 * B;
+    int32_t *pre = sm_sel + 3 * B + half * (B + 1);   // pre[B + 1] of this half
+    const int64_t q = 2 * (int64_t)blockIdx.x + half;
+    const bool live = q < nq;
+    const int lo = live ? lo_[q] : 0, hi = live ? hi_[q] : -1;
     // scope of the query: -1 = its attribute range; b >= 0 = the slab of bucket b; -2 - b = every
     // slot outside the slab of bucket b; INT32_MIN = nothing
-    const int only = only_bucket ? only_bucket[q] : -1;
+    const int only = live ? (only_bucket ? only_bucket[q] : -1) : INT32_MIN;
     const int ex = (only <= -2 && only != INT32_MIN) ? -2 - only : -1;   // excluded bucket
     // bucket intervals are ordered, so counting gives the run: buckets entirely below lo come
-    // first, buckets starting at or below hi form a prefix
+    // first, buckets starting at or below hi form a prefix.  Both halves fill the shared columns
+    // (with the same values).
     int below = 0, start_ok = 0;
-    for (int b = lane; b < B; b += 64) {
+    for (int b = hl; b < B; b += 32) {
         const int32_t *t = table + T_COLS * b;
         tbase[b] = t[T_BASE]; tnsort[b] = t[T_NSORT]; tntot[b] = t[T_NTOT];
         below += t[T_MAX] < lo;
         start_ok += t[T_MIN] <= hi;
     }
     __syncthreads();
+    below = half_sum(below);
+    start_ok = half_sum(start_ok);
     int b0 = 0, b1 = -1;
     if (only >= 0) {
         b0 = b1 = only;
     } else if (ex >= 0) {
         b0 = 0; b1 = B - 1;
     } else if (only == -1 && lo <= hi) {
-        b0 = wave_sum(below);
-        b1 = wave_sum(start_ok) - 1;
+        b0 = below;
+        b1 = start_ok - 1;
         if (b1 < b0) { b0 = 0; b1 = -1; }
     }
-    if (q_bin && lane == 0) {
-        int bin = only >= 0 ? only : (ex >= 0 ? ex : (b1 < b0 ? B : b0));
+    const bool sel = b1 >= b0;     // false also for the half that has no query
+    // the query's bin and its rank inside the bin (order of arrival; the answer is not needed
+    // before the end of this kernel)
+    const bool filed = q_bin && live && hl == 0;
+    int bin = 0, rank = 0;
+    if (filed) {
+        bin = only >= 0 ? only : (ex >= 0 ? ex : (sel ? b0 : B));
         if (bin < 0 || bin > B) bin = B;
-        q_bin[q] = bin;
-        atomicAdd(&bin_count[GRAB_BIN_STRIDE * bin], 1);
-    }
-    QueryPlan p;
-    p.b0 = b0; p.b1 = b1; p.V = 0; p.n_seeds = 0;
-    p.s0 = p.e0 = p.t0s = p.t0e = p.ms = p.e1 = p.t1s = p.t1e = 0;
-    p.first_valid = p.end_valid = 0; p.pad0 = p.pad1 = 0;
-    if (b1 < b0) {
-        if (lane == 0) plans[q] = p;
-        for (int j = lane; j < S; j += 64) seeds[q * S + j] = GRAB_EMPTY;
-        return;
+        rank = atomicAdd(&bin_count[GRAB_BIN_STRIDE * bin], 1);
     }
     const int base0 = tbase[b0], ns0 = tnsort[b0], nt0 = tntot[b0];
-    const int base1 = tbase[b1], ns1 = tnsort[b1], nt1 = tntot[b1];
-    int sa0, se0, se1 = 0, tail0, tail1 = 0;
-    if (only >= 0 || ex >= 0) {   // whole slabs, nothing to check: the "sorted span" is every occupied slot
-        sa0 = 0; se0 = nt0; tail0 = 0;
-        se1 = nt1; tail1 = 0;
-    } else {
-        int up;
-        wave_bound2(attr + base0, ns0, lo, false, attr + base1, ns1, hi, true, lane, sa0, up);
+    const int base1 = sel ? tbase[b1] : 0, ns1 = sel ? tnsort[b1] : 0, nt1 = sel ? tntot[b1] : 0;
+    const bool whole = only >= 0 || ex >= 0;   // whole slabs, nothing to check: the "sorted span" is every occupied slot
+    int sa0 = 0, se0 = nt0, se1 = nt1, tail0 = 0, tail1 = 0, up = 0, sa = 0;
+    {
+        // first the fences (contiguous, a few cache lines), then the GRAB_FENCE - 1 attributes
+        // between the last fence entry below the bound and the next one
+        const bool on = sel && !whole;
+        int c0, c1;
+        half_bound2(fence + grab_fence_offset(base0, b0), (ns0 + GRAB_FENCE - 1) / GRAB_FENCE, lo,
+                    fence + grab_fence_offset(base1, sel ? b1 : 0), (ns1 + GRAB_FENCE - 1) / GRAB_FENCE, hi, on, half, hl, c0, c1);
+        const int w0 = c0 > 0 ? (c0 - 1) * GRAB_FENCE + 1 : 0, w1 = c1 > 0 ? (c1 - 1) * GRAB_FENCE + 1 : 0;
+        const int n0 = c0 > 0 ? min(c0 * GRAB_FENCE, ns0) - w0 : 0, n1 = c1 > 0 ? min(c1 * GRAB_FENCE, ns1) - w1 : 0;
+        half_bound2(attr + base0 + w0, n0, lo, attr + base1 + w1, n1, hi, on, half, hl, sa, up);
+        sa += w0;
+        up += w1;
+    }
+    if (sel && !whole) {
+        sa0 = sa;
         tail0 = nt0 - ns0;
+        se1 = 0;
         if (b1 == b0) {
             se0 = up < sa0 ? sa0 : up;
         } else {
@@ -161,10 +174,10 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
         }
     }
     // population count per selected bucket, exclusive prefix in LDS
-    const int nb = b1 - b0 + 1;
+    const int nb = sel ? b1 - b0 + 1 : 0;
     int carry = 0;
-    for (int i0 = 0; i0 < nb; i0 += 64) {
-        int i = i0 + lane, c = 0;
+    for (int i0 = 0; i0 < nb; i0 += 32) {
+        int i = i0 + hl, c = 0;
         if (i < nb) {
             int b = b0 + i;
             if (b == ex) c = 0;
@@ -174,88 +187,112 @@ __global__ __launch_bounds__(64) void k_select_seed(const int32_t *__restrict__ 
         }
         int inc = c;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            int up = __shfl_up(inc, d);
-            if (lane >= d) inc += up;
+        for (int d = 1; d < 32; d <<= 1) {
+            int upv = __shfl_up(inc, d);
+            if (hl >= d) inc += upv;
         }
         if (i < nb) pre[i] = carry + inc - c;
-        carry += __shfl(inc, 63);
+        carry += __shfl(inc, 32 * half + 31);
     }
-    if (lane == 0) pre[nb] = carry;
+    if (hl == 0) pre[nb] = carry;
     __syncthreads();
     const int V = carry;
     const int count = V < S ? V : S;
     const uint32_t stride = (V > S) ? (uint32_t)(V / S) : 1u;
-    for (int j = lane; j < S; j += 64) {
-        uint32_t slot = GRAB_EMPTY;
-        if (j < count) {
-            int64_t pos = j;
-            if (V > S) pos = ((int64_t)j * V) / S + (int64_t)(mix32((uint32_t)j ^ salt) % stride);
-            int l = 0, r = nb;  // last selected bucket whose prefix <= pos
-            while (r - l > 1) {
-                int m = (l + r) >> 1;
-                if (pre[m] <= pos) l = m; else r = m;
+    // floor(j V / S) = j floor(V / S) + floor(j (V mod S) / S); for S <= 4096 the last quotient is
+    // of numbers below 2^24, which one float multiplication finds to within one
+    const int vrem = V > S ? V - (int)stride * S : 0;
+    const float rcp_s = 1.0f / (float)S;
+    if (live)
+        for (int j = hl; j < S; j += 32) {
+            uint32_t slot = GRAB_EMPTY;
+            if (j < count) {
+                int pos = j;       // below V
+                if (V > S) {
+                    if (S <= 4096) {
+                        const int x = j * vrem;
+                        int qt = (int)((float)x * rcp_s);
+                        const int rm = x - qt * S;
+                        qt += (rm >= S) - (rm < 0);
+                        pos = j * (int)stride + qt;
+                    } else {
+                        pos = (int)(((int64_t)j * V) / S);
+                    }
+                    pos += (int)(mix32((uint32_t)j ^ salt) % stride);
+                }
+                int l = 0, r = nb;  // last selected bucket whose prefix <= pos
+                while (r - l > 1) {
+                    int m = (l + r) >> 1;
+                    if (pre[m] <= pos) l = m; else r = m;
+                }
+                int off = pos - pre[l];
+                int b = b0 + l;
+                if (b == b0) slot = off < se0 - sa0 ? base0 + sa0 + off : base0 + ns0 + (off - (se0 - sa0));
+                else if (b == b1) slot = off < se1 ? base1 + off : base1 + ns1 + (off - se1);
+                else slot = tbase[b] + off;
             }
-            int off = (int)(pos - pre[l]);
-            int b = b0 + l;
-            if (b == b0) slot = off < se0 - sa0 ? base0 + sa0 + off : base0 + ns0 + (off - (se0 - sa0));
-            else if (b == b1) slot = off < se1 ? base1 + off : base1 + ns1 + (off - se1);
-            else slot = tbase[b] + off;
+            seeds[q * S + j] = slot;
         }
-        seeds[q * S + j] = slot;
-    }
-    if (lane == 0) {
-        p.V = V; p.n_seeds = count;
-        if (ex >= 0) {
-            // everything before the excluded slab, and everything after it
-            const int32_t *te = table + T_COLS * ex;
-            p.s0 = base0; p.e0 = te[T_BASE];
-            p.ms = te[T_BASE] + te[T_CAP]; p.e1 = base1 + table[T_COLS * b1 + T_CAP];
-            if (V == 0) { p.b0 = 0; p.b1 = -1; }     // nothing lies outside the only bucket
-        } else {
-            p.s0 = base0 + sa0; p.e0 = base0 + se0;
-            p.t0s = base0 + ns0; p.t0e = base0 + ns0 + tail0;
-            if (b1 > b0) {
-                p.ms = tbase[b0 + 1];
-                p.e1 = base1 + se1;
-                p.t1s = base1 + ns1; p.t1e = base1 + ns1 + tail1;
+    if (live && hl == 0) {
+        QueryPlan p;
+        p.b0 = b0; p.b1 = b1; p.V = V; p.n_seeds = count;
+        p.s0 = p.e0 = p.t0s = p.t0e = p.ms = p.e1 = p.t1s = p.t1e = 0;
+        p.first_valid = p.end_valid = 0; p.pad0 = p.pad1 = 0;
+        if (sel) {
+            if (ex >= 0) {
+                // everything before the excluded slab, and everything after it
+                const int32_t *te = table + T_COLS * ex;
+                p.s0 = base0; p.e0 = te[T_BASE];
+                p.ms = te[T_BASE] + te[T_CAP]; p.e1 = base1 + table[T_COLS * b1 + T_CAP];
+                if (V == 0) { p.b0 = 0; p.b1 = -1; }     // nothing lies outside the only bucket
+            } else {
+                p.s0 = base0 + sa0; p.e0 = base0 + se0;
+                p.t0s = base0 + ns0; p.t0e = base0 + ns0 + tail0;
+                if (b1 > b0) {
+                    p.ms = tbase[b0 + 1];
+                    p.e1 = base1 + se1;
+                    p.t1s = base1 + ns1; p.t1e = base1 + ns1 + tail1;
+                }
             }
+            p.first_valid = p.s0;
+            p.end_valid = b1 > b0 ? p.e1 : p.e0;
         }
-        p.first_valid = p.s0;
-        p.end_valid = b1 > b0 ? p.e1 : p.e0;
         plans[q] = p;
     }
+    if (filed) { q_bin[q] = bin; q_rank[q] = rank; }
 }
 
 // ------------------------------------------------------------------------------ launch order
 #define GRAB_ORDER_RUN 256   // short run length, see k_order
-// Counter block of the launch order: bin i has its own 128-byte line (atomics to one line are
-// served one after another, and a batch sends thousands at once): word 0 of the line = queries in
-// the bin (counted by k_select_seed), word 1 = positions of the bin already handed out (k_order);
-// after the last line: finished k_order workgroups.  All zero between calls: k_order's last
-// workgroup clears them; k_order_reset does it when that is in doubt (fresh memory, a launch that
-// failed in between).
+// Counters of the launch order: bin i has its own 128-byte line (atomics to one line are served
+// one after another, and a batch sends thousands at once), word 0 of the line = queries in the
+// bin (counted by k_select_seed).  A block of counters must be zero when a call starts counting:
+// an index keeps two blocks and uses them in turn, and the k_order of a call clears the block of
+// the call before; k_order_reset clears when that is in doubt (fresh memory, a launch that failed
+// in between) or when there is only one block.
 __global__ void k_order_reset(int32_t *__restrict__ bin_count, int n) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) bin_count[i] = 0;
 }
 
 // Places the queries in the launch order: position in bucket order = start of the bin + rank;
-// workgroup w of the search kernel runs query order[w] (GRAB_EMPTY: none).  Rank: LDS counts per
-// workgroup, one global atomic per workgroup and bin.  Runs of `run` consecutive positions go
-// round the XCDs: the i-th workgroup of XCD c (w = 8 i + c) takes element i % run of run
-// (i / run) * 8 + c.  Evenly filled bins: runs_per_xcd long runs per XCD (one gives the most
-// sharing).  When one bin holds a large share of the batch, what a query costs follows its bin (a
-// query that starts in the last bucket cannot be wide), and long runs would leave some XCDs with
-// all the expensive queries: short runs then.
+// workgroup w of the search kernel runs query order[w] (GRAB_EMPTY: none).
+// Runs of `run` consecutive positions go round the XCDs: the i-th workgroup of XCD c (w = 8 i + c)
+// takes element i % run of run (i / run) * 8 + c.  Evenly filled bins: runs_per_xcd long runs per
+// XCD (one gives the most sharing).  When one bin holds a large share of the batch, what a query
+// costs follows its bin (a query that starts in the last bucket cannot be wide), and long runs
+// would leave some XCDs with all the expensive queries: short runs then.
 // One thread per entry of `order`: it marks its own entry empty if no position maps there, and
-// files query t (t < nq).  The last workgroup to finish zeroes the counter block for the next call.
-__global__ __launch_bounds__(256) void k_order(const int32_t *__restrict__ q_bin, int32_t *__restrict__ bin_count, int nbins,
+// files query t (t < nq).  bin_clear (may be null): the counter block to zero for a later call.
+__global__ __launch_bounds__(256) void k_order(const int32_t *__restrict__ q_bin, const int32_t *__restrict__ q_rank,
+                                               const int32_t *__restrict__ bin_count, int32_t *__restrict__ bin_clear, int nbins,
                                                int64_t nq, uint32_t *__restrict__ order, int64_t order_len, int runs_per_xcd) {
-    __shared__ int32_t start[GRAB_MAX_BUCKETS + 2], cnt[GRAB_MAX_BUCKETS + 1], base[GRAB_MAX_BUCKETS + 1];
-    __shared__ int s_biggest, last_block;
+    __shared__ int32_t start[GRAB_MAX_BUCKETS + 2];
+    __shared__ int s_biggest;
     const int tid = threadIdx.x, lane = tid & 63;
-    for (int i = tid; i < nbins; i += 256) cnt[i] = 0;
+    const int64_t t = (int64_t)blockIdx.x * 256 + tid;
+    int bin = -1, rank = 0;
+    if (t < nq) { bin = q_bin[t]; rank = q_rank[t]; }
     if (tid < 64) {   // exclusive prefix of the bin counts (every workgroup recomputes it: at most 1025 words)
         int carry = 0, biggest = 0;
         for (int i0 = 0; i0 < nbins; i0 += 64) {
@@ -275,40 +312,23 @@ __global__ __launch_bounds__(256) void k_order(const int32_t *__restrict__ q_bin
         for (int d = 32; d > 0; d >>= 1) biggest = max(biggest, __shfl_xor(biggest, d));
         if (lane == 0) s_biggest = biggest;
     }
+    if (bin_clear && t < nbins) bin_clear[GRAB_BIN_STRIDE * t] = 0;
     __syncthreads();
     const int64_t parts = 8 * (int64_t)runs_per_xcd;
     const int64_t run = (int64_t)s_biggest * 16 > nq ? GRAB_ORDER_RUN : (nq + parts - 1) / parts;
-    const int64_t t = (int64_t)blockIdx.x * 256 + tid;
     if (t < order_len) {   // the position that maps to entry t
         const int64_t i = t / 8, c = t % 8;
         const int64_t pos = ((i / run) * 8 + c) * run + i % run;
         if (pos >= nq) order[t] = GRAB_EMPTY;
     }
-    int bin = -1, local = 0;
-    if (t < nq) {
-        bin = q_bin[t];
-        if (bin < 0 || bin >= nbins) bin = -1;
-        else local = atomicAdd(&cnt[bin], 1);
-    }
-    __syncthreads();
-    for (int i = tid; i < nbins; i += 256)
-        if (cnt[i] > 0) base[i] = atomicAdd(&bin_count[GRAB_BIN_STRIDE * i + 1], cnt[i]);
-    __syncthreads();
-    if (bin >= 0) {
-        const int64_t pos = (int64_t)start[bin] + base[bin] + local;      // position in bucket order
+    if (bin >= 0 && bin < nbins) {
+        const int64_t pos = (int64_t)start[bin] + rank;      // position in bucket order
         if (pos >= 0 && pos < nq) {
             const int64_t g = pos / run, e = pos % run;
             const int64_t w = ((g / 8) * run + e) * 8 + g % 8;
             if (w < order_len) order[w] = (uint32_t)t;
         }
     }
-    // every use of the counters above is done: count this workgroup out, the last one clears them
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) last_block = atomicAdd(&bin_count[GRAB_BIN_STRIDE * nbins], 1) == (int)gridDim.x - 1;
-    __syncthreads();
-    if (last_block)
-        for (int i = tid; i <= nbins; i += 256) { bin_count[GRAB_BIN_STRIDE * i] = 0; bin_count[GRAB_BIN_STRIDE * i + 1] = 0; }
 }
 
 // The launch order read off a list of the queries that is already in bin order (a batch sorted by
@@ -659,59 +679,70 @@ grab_status grab_launch_gather_probe(grab_index *ix, int64_t waves, int32_t batc
 int64_t grab_order_len(int64_t nq) { return (nq + 8 * GRAB_ORDER_RUN - 1) / (8 * GRAB_ORDER_RUN) * (8 * GRAB_ORDER_RUN); }
 
 grab_status grab_plan_order(grab_index *ix, SearchLaunch &s) {
-    s.q_bin = s.bin_count = nullptr;
+    s.q_bin = s.q_rank = s.bin_count = nullptr;
     s.order = nullptr;
     s.order_len = 0;
     s.order_dirty = nullptr;
+    s.order_block = nullptr;
     if (s.nq < 2048) return GRAB_OK;   // a batch that does not even fill the device once gains nothing
     // room for either run length k_order may choose: nq rounded up to eight short runs
     const int64_t len = grab_order_len(s.nq);
     grab_status st;
     if ((st = grab_reserve(ix, ix->q_bin, (size_t)s.nq * 4)) != GRAB_OK) return st;
+    if ((st = grab_reserve(ix, ix->q_rank, (size_t)s.nq * 4)) != GRAB_OK) return st;
     if ((st = grab_reserve(ix, ix->q_order, (size_t)len * 4)) != GRAB_OK) return st;
     const void *before = ix->bin_count.p;
-    if ((st = grab_reserve(ix, ix->bin_count, GRAB_BIN_BLOCK_BYTES)) != GRAB_OK) return st;
+    if ((st = grab_reserve(ix, ix->bin_count, 2 * GRAB_BIN_BLOCK_BYTES)) != GRAB_OK) return st;
     if (ix->bin_count.p != before) ix->order_dirty = true;    // fresh memory: counters not yet zero
-    s.q_bin = (int32_t *)ix->q_bin.p; s.bin_count = (int32_t *)ix->bin_count.p;
+    s.q_bin = (int32_t *)ix->q_bin.p; s.q_rank = (int32_t *)ix->q_rank.p; s.bin_count = (int32_t *)ix->bin_count.p;
     s.order = (uint32_t *)ix->q_order.p;
     s.order_len = len;
     s.order_dirty = &ix->order_dirty;
+    s.order_block = &ix->order_block;
     return GRAB_OK;
 }
 
 grab_status grab_launch_select(grab_index *ix, const SearchLaunch &s) {
     if (s.nq == 0) return GRAB_OK;
     const int nbins = ix->B + 1;   // the last bin takes the queries whose range meets no bucket
-    const size_t lds = (size_t)(4 * ix->B + 1) * 4;
+    const size_t lds = (size_t)(5 * ix->B + 2) * 4;
     const bool counted = s.order && !s.sorted_queries;
+    int32_t *count = nullptr, *clear = nullptr;
     if (counted) {
-        // the counters are left zero by the k_order of the previous call; if that is in doubt
-        // (fresh memory, a launch that failed in between) they are cleared first
+        count = s.bin_count;
+        if (s.order_block) {
+            count = s.bin_count + (size_t)*s.order_block * GRAB_BIN_BLOCK_WORDS;
+            clear = s.bin_count + (size_t)(1 - *s.order_block) * GRAB_BIN_BLOCK_WORDS;
+        }
+        // the block is left zero by an earlier k_order; if that is in doubt (fresh memory, a launch
+        // that failed in between, a single block) everything is cleared first
         const bool dirty = !s.order_dirty || *s.order_dirty;
         if (s.order_dirty) *s.order_dirty = true;
         if (dirty) {
-            const int words = GRAB_BIN_STRIDE * nbins + 2;
+            const int words = (s.order_block ? 2 : 1) * GRAB_BIN_BLOCK_WORDS;
             k_order_reset<<<dim3((unsigned)((words + 255) / 256)), dim3(256), 0, ix->stream>>>(s.bin_count, words);
             GRAB_HIP(ix, hipGetLastError());
         }
     }
-    k_select_seed<<<dim3((unsigned)s.nq), dim3(64), lds, ix->stream>>>(ix->table, ix->B, ix->attr, s.lo, s.hi, s.only_bucket,
-                                                                      s.n_seeds, s.salt, s.plans, s.seeds,
-                                                                      counted ? s.q_bin : nullptr, s.bin_count);
+    k_select_seed<<<dim3((unsigned)((s.nq + 1) / 2)), dim3(64), lds, ix->stream>>>(ix->table, ix->B, ix->attr, s.lo, s.hi,
+                                                                                s.only_bucket, s.nq, s.n_seeds, s.salt, s.plans,
+                                                                                s.seeds, ix->fence, counted ? s.q_bin : nullptr,
+                                                                                s.q_rank, count);
     GRAB_HIP(ix, hipGetLastError());
+    // measured: rows of 512 B (1M x 128) run fastest with one run per XCD (headline 481 us against
+    // 502 us with four and 516 us in input order); rows of 3,840 B (1M x 960) with four (3.82 ms
+    // against 4.06 ms with one and 4.19 ms in input order)
+    const int runs_per_xcd = ix->dim >= 512 ? 4 : 1;
     if (s.order && s.sorted_queries) {
         k_order_sorted<<<dim3((unsigned)((s.order_len + 255) / 256)), dim3(256), 0, ix->stream>>>(s.sorted_queries, s.nq, s.order,
-                                                                                               s.order_len, ix->dim >= 512 ? 4 : 1);
+                                                                                               s.order_len, runs_per_xcd);
         GRAB_HIP(ix, hipGetLastError());
     }
     if (counted) {
-        // measured: rows of 512 B (1M x 128) run fastest with one run per XCD (headline 481 us against
-        // 502 us with four and 516 us in input order); rows of 3,840 B (1M x 960) with four (3.82 ms
-        // against 4.06 ms with one and 4.19 ms in input order)
-        k_order<<<dim3((unsigned)((s.order_len + 255) / 256)), dim3(256), 0, ix->stream>>>(s.q_bin, s.bin_count, nbins, s.nq,
-                                                                                        s.order, s.order_len,
-                                                                                        ix->dim >= 512 ? 4 : 1);
+        k_order<<<dim3((unsigned)((s.order_len + 255) / 256)), dim3(256), 0, ix->stream>>>(s.q_bin, s.q_rank, count, clear, nbins,
+                                                                                        s.nq, s.order, s.order_len, runs_per_xcd);
         GRAB_HIP(ix, hipGetLastError());
+        if (s.order_block) *s.order_block ^= 1;
         if (s.order_dirty) *s.order_dirty = false;
     }
     return GRAB_OK;
