@@ -356,7 +356,21 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         return;
     }
     // ---- remote part, by target bucket
+    // the candidates' j-th remote entries are requested one j ahead, so that the request flies while the
+    // rows of entry j - 1 are evaluated
+    constexpr int MAXC = 8;   // candidates per lane: queues of up to 512
+    const int nrc = a.remote_cands > 0 && a.remote_cands < nc ? a.remote_cands : nc;   // the nearest candidates only
+    uint32_t ahead[MAXC];
+    auto request = [&](int j) __attribute__((always_inline)) {
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            const int t = 64 * c + lane;
+            ahead[c] = GRAB_EMPTY;
+            if (64 * c < nrc && t < nrc) ahead[c] = a.A[(size_t)cs[t] * K + a.kl + j];
+        }
+    };
     if (a.kr > 0) {
+        request(0);
         load_query<NCH>(a.vecs + (size_t)i * D, qreg, qlds, lane);
         __syncthreads();
     }
@@ -364,12 +378,16 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         // neighbouring candidates mostly share their j-th remote entry: each distinct slot is
         // evaluated once (the minimum below does not depend on repeats)
         for (int x = lane; x < uniq_words; x += 64) uniq[x] = GRAB_EMPTY;
+        uint32_t now[MAXC];
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) now[c] = ahead[c];
+        if (j + 1 < a.kr) request(j + 1);
         __syncthreads();
         int nr = 0;
-        const int nrc = a.remote_cands > 0 && a.remote_cands < nc ? a.remote_cands : nc;   // the nearest candidates only
-        for (int c0 = 0; c0 < nrc; c0 += 64) {
-            const int t = c0 + lane;
-            uint32_t r = t < nrc ? a.A[(size_t)cs[t] * K + a.kl + j] : GRAB_EMPTY;
+#pragma unroll
+        for (int c = 0; c < MAXC; ++c) {
+            if (64 * c >= nrc) break;
+            const uint32_t r = now[c];
             bool ok = false;
             if (r != GRAB_EMPTY) {
                 uint32_t h = (uint32_t)(((u64)(r * 0x9E3779B1u) * (u64)uniq_words) >> 32);
