@@ -34,7 +34,7 @@ __device__ __forceinline__ int wave_sum(int v) {
 // where a ds_bpermute round trip costs on the order of a hundred.
 template <int CTRL>
 __device__ __forceinline__ uint32_t dpp_u32(uint32_t x) {
-    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, false);
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, CTRL, 0xF, 0xF, true);
 }
 // value of lane (lane ^ J)
 template <int J>
@@ -185,7 +185,7 @@ struct EvalShape {
 // xor 1 and xor 2, the half-row mirror pairs lane i with lane 7-i of its group
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float x) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, false));
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
 }
 
 // Gathered distances (Algorithm 2, ComputeDistance) for up to 8*R slots L[base..]: eight lanes
