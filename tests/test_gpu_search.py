@@ -62,6 +62,38 @@ def test_selection_and_seeds_are_bit_exact(c1_small, torch_dev):
     ix.close()
 
 
+@pytest.mark.parametrize("domain", [25, 1 << 20])
+def test_selection_across_the_fence_of_an_edge_bucket(torch_dev, domain):
+    """Buckets of 20,000 objects: more than 128 fence entries (the fence itself needs two probing steps), a sorted
+    prefix that is no multiple of the fence distance, and, with 25 distinct attribute values, runs of equal
+    attributes that span a dozen fence entries; bounds on, just below and just above stored values."""
+    import torch
+    from paper_2604_16402_amd import binding
+    n, B, dim = 80_001, 4, 32
+    rng = np.random.default_rng(domain)
+    X = rng.standard_normal((n, dim)).astype(np.float32)
+    a = rng.integers(0, domain, n).astype(np.int32)
+    ora = O.Index(X, a, B, n_cap=n)
+    ix = binding.Index(dim, W.L2SQ, stream=torch.cuda.current_stream(torch_dev).cuda_stream)
+    ix.build_buckets(torch.from_numpy(X).to(torch_dev), torch.from_numpy(a).to(torch_dev), B, n)
+    if domain == 25:
+        v = np.arange(-2, 28, dtype=np.int32)
+        lo, hi = [g.ravel() for g in np.meshgrid(v, v, indexing="ij")]
+    else:
+        srt = np.sort(a)
+        at = srt[rng.integers(0, n, 400)]                      # stored values, many of them next to a fence entry
+        at[:200] = srt[(rng.integers(0, n // 128, 200) * 128) % n]
+        lo = (at + rng.integers(-1, 2, 400)).astype(np.int32)
+        hi = (lo + rng.integers(-3, domain // 3, 400)).astype(np.int32)
+        hi[::7] = srt[rng.integers(0, n, len(hi[::7]))]
+    info, seeds = ix.select_range(lo.astype(np.int32), hi.astype(np.int32), 64)
+    for i in range(len(lo)):
+        want_info, want_seeds = ora.select(int(lo[i]), int(hi[i]), 64)
+        assert info[i].tolist() == want_info.tolist(), (i, lo[i], hi[i])
+        assert np.array_equal(seeds[i], want_seeds), (i, lo[i], hi[i])
+    ix.close()
+
+
 @pytest.mark.parametrize("beam,width", [(64, 1), (128, 1), (64, 4), (40, 2)])
 def test_search_matches_oracle_exactly(c1_small, torch_dev, beam, width):
     c = c1_small
