@@ -102,7 +102,9 @@ const char *grab_last_error(const grab_index *ix);
  * (attribute, id) and cut into n_buckets buckets of equal count (ranks floor(b*n/B) ..
  * floor((b+1)*n/B)); bucket b owns a contiguous slab of count_b + floor((n_cap-n)/B) slots,
  * the extra ones being tail room for grab_append_batch.  Builds the feature matrix,
- * attribute array, id<->slot maps and bucket table; drops any graph loaded before.
+ * attribute array, id<->slot maps and bucket table, and a small search aid for Algorithm 2's
+ * range selection (every 128th attribute of each bucket's sorted part: slots / 128 + n_buckets
+ * words); drops any graph loaded before.
  * Requires 1 <= n_buckets <= 1024, n_buckets <= n <= n_cap < 2^31.
  * Errors: GRAB_EINVAL (arguments), GRAB_ENOMEM, GRAB_EHIP; the index is empty afterwards. */
 grab_status grab_build_buckets(grab_index *ix, const float *vectors, const int32_t *attrs,
