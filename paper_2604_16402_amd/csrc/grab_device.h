@@ -195,27 +195,31 @@ __device__ __forceinline__ float dpp_move(float x) {
 // This fixed order makes the fp32 result reproducible bit for bit.  All loads of the batch are
 // issued before the first multiply.  Every lane of a group ends with the row's distance in
 // s[r]; v[r] is the row's slot and act[r] tells whether round r had a row for this group.
-template <int NCH>
-__device__ __forceinline__ void eval_batch(const float *__restrict__ X, const float4 *qreg, const float *qlds,
+template <int NCH, int RA>
+__device__ __forceinline__ void eval_batch_rows(const float *__restrict__ X, const float4 *qreg, const float *qlds,
                                            const uint32_t *L, int base, int n, int lane, int metric,
                                            float (&s)[EvalShape<NCH>::R], uint32_t (&v)[EvalShape<NCH>::R],
                                            bool (&act)[EvalShape<NCH>::R]) {
     constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R;
     constexpr int D4 = NCH * 8;  // 16-byte pieces per row
     const int sub = lane & 7, grp = lane >> 3;
-    float acc[R];
+    float acc[RA];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
-        int idx = base + r * 8 + grp;
-        act[r] = idx < n;
-        v[r] = act[r] ? L[idx] : 0u;
-        acc[r] = 0.0f;
+        if (r < RA) {
+            int idx = base + r * 8 + grp;
+            act[r] = idx < n;
+            v[r] = act[r] ? L[idx] : 0u;
+            acc[r] = 0.0f;
+        } else {
+            act[r] = false; v[r] = 0u; s[r] = 0.0f;
+        }
     }
 #pragma unroll
     for (int c0 = 0; c0 < NCH; c0 += CB) {
-        float4 buf[R][CB];
+        float4 buf[RA][CB];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
+        for (int r = 0; r < RA; ++r) {
             const float4 *row = reinterpret_cast<const float4 *>(X) + (size_t)v[r] * D4 + sub;
 #pragma unroll
             for (int cc = 0; cc < CB; ++cc)
@@ -227,7 +231,7 @@ __device__ __forceinline__ void eval_batch(const float *__restrict__ X, const fl
             if constexpr (EvalShape<NCH>::QREG) qv = qreg[c0 + cc];
             else qv = reinterpret_cast<const float4 *>(qlds)[(c0 + cc) * 8 + sub];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
+            for (int r = 0; r < RA; ++r) {
                 float4 x = buf[r][cc];
                 if (metric == GRAB_L2SQ) {
                     float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
@@ -245,13 +249,31 @@ __device__ __forceinline__ void eval_batch(const float *__restrict__ X, const fl
         }
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r) {
+    for (int r = 0; r < RA; ++r) {
         float t = acc[r];
         t += dpp_move<0xB1>(t);   // quad_perm [1,0,3,2]: lane ^ 1
         t += dpp_move<0x4E>(t);   // quad_perm [2,3,0,1]: lane ^ 2
         t += dpp_move<0x141>(t);  // row_half_mirror: the other half of the group of eight
         s[r] = metric == GRAB_L2SQ ? t : -t;
     }
+}
+
+// eval_batch_rows for as many rounds as the batch has rows for: a batch of at most 8 R / 4 or 8 R / 2
+// slots skips the loads and the arithmetic of the rounds that would have no row in any group
+template <int NCH>
+__device__ __forceinline__ void eval_batch(const float *__restrict__ X, const float4 *qreg, const float *qlds,
+                                           const uint32_t *L, int base, int n, int lane, int metric,
+                                           float (&s)[EvalShape<NCH>::R], uint32_t (&v)[EvalShape<NCH>::R],
+                                           bool (&act)[EvalShape<NCH>::R]) {
+    constexpr int R = EvalShape<NCH>::R;
+    const int rounds = (n - base + 7) >> 3;
+    if constexpr (R >= 4) {
+        if (rounds * 4 <= R) { eval_batch_rows<NCH, R / 4>(X, qreg, qlds, L, base, n, lane, metric, s, v, act); return; }
+    }
+    if constexpr (R >= 2) {
+        if (rounds * 2 <= R) { eval_batch_rows<NCH, R / 2>(X, qreg, qlds, L, base, n, lane, metric, s, v, act); return; }
+    }
+    eval_batch_rows<NCH, R>(X, qreg, qlds, L, base, n, lane, metric, s, v, act);
 }
 
 // distances of the n slots in L to the query, written to dist_out[0..n)

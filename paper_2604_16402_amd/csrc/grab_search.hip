@@ -486,6 +486,7 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
             eval_batch<NCH>(a.X, qreg, qlds, L, base, n, lane, a.metric, s, v, act);
 #pragma unroll
             for (int r = 0; r < R; ++r) {
+                if (base + 8 * r >= n) break;   // no group has a row in this round
                 u64 key = make_key(s[r], v[r]);
                 bool keep = act[r] && sub == 0 && key < thr;
                 u64 m = __ballot(keep);
