@@ -8,6 +8,7 @@
 // pre-check is decided from slot intervals prepared by the select kernel, so only slots in
 // the appended tails of the two edge buckets cost an attribute read.
 #include "grab_device.h"
+#include <type_traits>
 
 namespace {
 
@@ -426,6 +427,17 @@ __device__ __forceinline__ int admit(const QueryPlan &p, const uint32_t (&v)[NV]
     return n_c;
 }
 
+// f(integral constant N, args...) with the smallest N in 1..4 such that 64 N lanes-entries cover `left`
+// entries (4 if none does): a pass over few entries does not pay for four per lane
+#define GRAB_FOR_LANE_LOADS(f, left, ...)                                         \
+    do {                                                                          \
+        const int left__ = (left);                                                \
+        if (left__ <= 64) f(std::integral_constant<int, 1>{}, __VA_ARGS__);       \
+        else if (left__ <= 128) f(std::integral_constant<int, 2>{}, __VA_ARGS__); \
+        else if (left__ <= 192) f(std::integral_constant<int, 3>{}, __VA_ARGS__); \
+        else f(std::integral_constant<int, 4>{}, __VA_ARGS__);                    \
+    } while (0)
+
 // One query per wavefront; the queue of up to 64*M keys stays in registers for the whole search.
 // New keys wait in a 64-entry LDS buffer, are sorted with a lane-exchange bitonic network sized
 // to their number and merged into the queue.  A new key is dropped at once when it is not
@@ -506,16 +518,19 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
         for (int s0 = 0; s0 < p.n_seeds; s0 += a.maxc) {
             const int lim = min(p.n_seeds, s0 + a.maxc);
             int n_c = 0;
-            for (int e0 = s0; e0 < lim; e0 += 64 * NV) {
-                uint32_t sv[NV];
+            // entries e0 .. of the chunk, N per lane
+            auto admit_seeds = [&](auto nvc, int e0) __attribute__((always_inline)) {
+                constexpr int N = decltype(nvc)::value;
+                uint32_t sv[N];
 #pragma unroll
-                for (int u = 0; u < NV; ++u) {
+                for (int u = 0; u < N; ++u) {
                     const int e = e0 + 64 * u + lane;
                     sv[u] = e < lim ? sd[e] : GRAB_EMPTY;
                 }
                 uint32_t unused = 0;
-                n_c = admit<NV>(p, sv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, unused, c_tail);
-            }
+                n_c = admit<N>(p, sv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, unused, c_tail);
+            };
+            for (int e0 = s0; e0 < lim; e0 += 64 * NV) GRAB_FOR_LANE_LOADS(admit_seeds, lim - e0, e0);
             __syncthreads();
             c_vis += n_c; c_evals += n_c; c_seed += n_c;
             evaluate(n_c);
@@ -549,10 +564,11 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
             // GatherNeighbors + pre-check + visited test, all parents' rows at once
             const int total = np * a.K;
             int n_c = 0;
-            for (int e0 = 0; e0 < total; e0 += 64 * NV) {
-                uint32_t nv[NV];   // the adjacency loads of up to 64*NV entries are in flight together
+            auto admit_neighbours = [&](auto nvc, int e0) __attribute__((always_inline)) {
+                constexpr int N = decltype(nvc)::value;
+                uint32_t nv[N];   // the adjacency loads of up to 64*N entries are in flight together
 #pragma unroll
-                for (int u = 0; u < NV; ++u) {
+                for (int u = 0; u < N; ++u) {
                     const int e = e0 + 64 * u + lane;
                     nv[u] = GRAB_EMPTY;
                     if (e < total) {
@@ -561,8 +577,9 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
                         nv[u] = a.A[(size_t)par[pi] * a.K + j];
                     }
                 }
-                n_c = admit<NV>(p, nv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, c_rej, c_tail);
-            }
+                n_c = admit<N>(p, nv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, c_rej, c_tail);
+            };
+            for (int e0 = 0; e0 < total; e0 += 64 * NV) GRAB_FOR_LANE_LOADS(admit_neighbours, total - e0, e0);
             __syncthreads();
             c_vis += n_c; c_evals += n_c;
             evaluate(n_c);
