@@ -21,6 +21,12 @@ __device__ __forceinline__ float image_dist(uint32_t m) {
 __device__ __forceinline__ u64 make_key(float d, uint32_t slot) { return ((u64)dist_image(d) << 32) | ((u64)slot << 1); }
 __device__ __forceinline__ uint32_t key_slot(u64 k) { return (uint32_t)(k & 0xFFFFFFFFull) >> 1; }
 
+// number of set bits of m below the caller's lane (m the same in every lane): the caller's place
+// among the lanes that a ballot marked
+__device__ __forceinline__ int lanes_below(u64 m) {
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
 __device__ __forceinline__ int wave_sum(int v) {
 #pragma unroll
     for (int m = 32; m > 0; m >>= 1) v += __shfl_xor(v, m);

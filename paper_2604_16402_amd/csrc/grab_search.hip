@@ -368,13 +368,14 @@ struct BeamArgs {
 // intervals; reads the attribute only for slots in the appended tail of an edge bucket
 __device__ __forceinline__ bool precheck(const QueryPlan &p, uint32_t v, const int32_t *__restrict__ attr, int lo,
                                          int hi, bool &tail) {
-    const int s = (int)v;
+    // every interval of the plan has start <= end, so one unsigned comparison tests membership
     tail = false;
-    if (s >= p.s0 && s < p.e0) return true;
-    if (s >= p.ms && s < p.e1) return true;
-    if ((s >= p.t0s && s < p.t0e) || (s >= p.t1s && s < p.t1e)) {
+    if (v - (uint32_t)p.s0 < (uint32_t)(p.e0 - p.s0)) return true;
+    if (v - (uint32_t)p.ms < (uint32_t)(p.e1 - p.ms)) return true;
+    if (p.t0e == p.t0s && p.t1e == p.t1s) return false;   // no appended tails in the edge buckets (the same for every lane)
+    if (v - (uint32_t)p.t0s < (uint32_t)(p.t0e - p.t0s) || v - (uint32_t)p.t1s < (uint32_t)(p.t1e - p.t1s)) {
         tail = true;
-        int a = attr[s];
+        int a = attr[v];
         return a >= lo && a <= hi;
     }
     return false;
@@ -389,7 +390,7 @@ __device__ __forceinline__ bool precheck(const QueryPlan &p, uint32_t v, const i
 // unique per slot and the queue is a set.
 template <int NV>
 __device__ __forceinline__ int admit(const QueryPlan &p, const uint32_t (&v)[NV], const int32_t *__restrict__ attr,
-                                     int lo, int hi, uint32_t *tab, uint32_t H, uint32_t *L, int n_c, u64 lt_mask,
+                                     int lo, int hi, uint32_t *tab, uint32_t H, uint32_t *L, int n_c,
                                      uint32_t &c_rej, uint32_t &c_tail) {
     bool pend[NV], fresh[NV];
     uint32_t h[NV];
@@ -421,7 +422,7 @@ __device__ __forceinline__ int admit(const QueryPlan &p, const uint32_t (&v)[NV]
 #pragma unroll
     for (int u = 0; u < NV; ++u) {
         const u64 m = __ballot(fresh[u]);
-        if (fresh[u]) L[n_c + __popcll(m & lt_mask)] = v[u];
+        if (fresh[u]) L[n_c + lanes_below(m)] = v[u];
         n_c += __popcll(m);
     }
     return n_c;
@@ -469,7 +470,6 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
     for (int i = lane; i < H / 4; i += 64) reinterpret_cast<uint4 *>(hash)[i] = make_uint4(~0u, ~0u, ~0u, ~0u);
     __syncthreads();
 
-    const u64 lt_mask = (1ull << lane) - 1ull;
     LaneQueue<M> Q;
     Q.clear();
     u64 thr = SENT;   // worst key of a full queue, SENT while it has room
@@ -502,7 +502,7 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
                 u64 key = make_key(s[r], v[r]);
                 bool keep = act[r] && sub == 0 && key < thr;
                 u64 m = __ballot(keep);
-                if (keep) C[cnt + __popcll(m & lt_mask)] = key;
+                if (keep) C[cnt + lanes_below(m)] = key;
                 cnt += __popcll(m);
             }
             __syncthreads();
@@ -528,7 +528,7 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
                     sv[u] = e < lim ? sd[e] : GRAB_EMPTY;
                 }
                 uint32_t unused = 0;
-                n_c = admit<N>(p, sv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, unused, c_tail);
+                n_c = admit<N>(p, sv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, unused, c_tail);
             };
             for (int e0 = s0; e0 < lim; e0 += 64 * NV) GRAB_FOR_LANE_LOADS(admit_seeds, lim - e0, e0);
             __syncthreads();
@@ -572,12 +572,12 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
                     const int e = e0 + 64 * u + lane;
                     nv[u] = GRAB_EMPTY;
                     if (e < total) {
-                        uint32_t pi = ((uint32_t)e * recipK) >> 16;
-                        uint32_t j = (uint32_t)e - pi * (uint32_t)a.K;
+                        uint32_t pi = __umul24((uint32_t)e, recipK) >> 16;      // e < 512, recipK <= 65,536
+                        uint32_t j = (uint32_t)e - __umul24(pi, (uint32_t)a.K);
                         nv[u] = a.A[(size_t)par[pi] * a.K + j];
                     }
                 }
-                n_c = admit<N>(p, nv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, lt_mask, c_rej, c_tail);
+                n_c = admit<N>(p, nv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, c_rej, c_tail);
             };
             for (int e0 = 0; e0 < total; e0 += 64 * NV) GRAB_FOR_LANE_LOADS(admit_neighbours, total - e0, e0);
             __syncthreads();
