@@ -264,8 +264,9 @@ __device__ __forceinline__ void eval_batch_rows(const float *__restrict__ X, con
     }
 }
 
-// eval_batch_rows for as many rounds as the batch has rows for: a batch of at most 8 R / 4 or 8 R / 2
-// slots skips the loads and the arithmetic of the rounds that would have no row in any group
+// eval_batch_rows for as many rounds as the batch has rows for: a batch that fills a quarter, half or
+// three quarters of the 8 R slots skips the loads and the arithmetic of the rounds that would have no
+// row in any group
 template <int NCH>
 __device__ __forceinline__ void eval_batch(const float *__restrict__ X, const float4 *qreg, const float *qlds,
                                            const uint32_t *L, int base, int n, int lane, int metric,
@@ -278,6 +279,9 @@ __device__ __forceinline__ void eval_batch(const float *__restrict__ X, const fl
     }
     if constexpr (R >= 2) {
         if (rounds * 2 <= R) { eval_batch_rows<NCH, R / 2>(X, qreg, qlds, L, base, n, lane, metric, s, v, act); return; }
+    }
+    if constexpr (R == 4) {
+        if (rounds == 3) { eval_batch_rows<NCH, 3>(X, qreg, qlds, L, base, n, lane, metric, s, v, act); return; }
     }
     eval_batch_rows<NCH, R>(X, qreg, qlds, L, base, n, lane, metric, s, v, act);
 }
