@@ -574,7 +574,7 @@ __global__ __launch_bounds__(64, (NCH != 8 && M <= 4) ? 4 : 1) void k_beam_searc
                     if (e < total) {
                         uint32_t pi = __umul24((uint32_t)e, recipK) >> 16;      // e < 512, recipK <= 65,536
                         uint32_t j = (uint32_t)e - __umul24(pi, (uint32_t)a.K);
-                        nv[u] = a.A[(size_t)par[pi] * a.K + j];
+                        nv[u] = a.A[(size_t)par[pi] * (uint32_t)a.K + j];
                     }
                 }
                 n_c = admit<N>(p, nv, a.attr, lo, hi, hash, (uint32_t)H, L, n_c, c_rej, c_tail);
