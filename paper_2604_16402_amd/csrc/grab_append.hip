@@ -304,7 +304,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         float d = 0.0f;
         if (j < nk) { v = kept[j]; d = keptd[j]; }
         else if (j - nk < nrej) { v = rej[j - nk]; d = rejd[j - nk]; }
-        a.A[(size_t)self * K + j] = v;
+        a.A[(size_t)self * (uint32_t)K + j] = v;
         rowl[j] = v;
         const int64_t r = i * K + j;
         a.key1[r] = v == GRAB_EMPTY ? ~0ull : ((u64)v << 1);
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
             v = r < nu ? ul[r] : GRAB_EMPTY;
         }
         if (has) {
-            a.A[(size_t)self * K + a.kl + lane] = v;
+            a.A[(size_t)self * (uint32_t)K + a.kl + lane] = v;
             const int64_t r = i * K + a.kl + lane;
             a.key1[r] = pick ? (((u64)v << 1) | 1ull) : ~0ull;
             a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
@@ -366,7 +366,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         for (int c = 0; c < MAXC; ++c) {
             const int t = 64 * c + lane;
             ahead[c] = GRAB_EMPTY;
-            if (64 * c < nrc && t < nrc) ahead[c] = a.A[(size_t)cs[t] * K + a.kl + j];
+            if (64 * c < nrc && t < nrc) ahead[c] = a.A[(size_t)cs[t] * (uint32_t)K + a.kl + j];
         }
     };
     if (a.kr > 0) {
@@ -422,7 +422,7 @@ __global__ __launch_bounds__(64) void k_forward(ForwardArgs a) {
         if (lane == 0) {
             const uint32_t v = best == ~0ull ? GRAB_EMPTY : (uint32_t)(best & 0xFFFFFFFFull);
             const float d = best == ~0ull ? 0.0f : image_dist((uint32_t)(best >> 32));
-            a.A[(size_t)self * K + a.kl + j] = v;
+            a.A[(size_t)self * (uint32_t)K + a.kl + j] = v;
             const int64_t r = i * K + a.kl + j;
             a.key1[r] = v == GRAB_EMPTY ? ~0ull : (((u64)v << 1) | 1ull);
             a.key2[r] = ((u64)dist_image(d) << 32) | (u64)self;
@@ -602,7 +602,7 @@ __global__ __launch_bounds__(64, 4) void k_rewire(RewireArgs a) {
     uint4 *raw = reinterpret_cast<uint4 *>(qs + (size_t)(G + 1) * D);   // the records of those positions as they come
     raw[lane] = p0 + lane < a.nreq ? a.rec[p0 + lane] : make_uint4(0u, 0u, 0u, 0u);
     if (lane < len) {
-        uint32_t e = a.A[(size_t)v * K + off + lane];
+        uint32_t e = a.A[(size_t)v * (uint32_t)K + off + lane];
         R[lane] = e;
         Rl[lane] = e == GRAB_EMPTY ? 0u : e;
     }
@@ -712,7 +712,7 @@ __global__ __launch_bounds__(64, 4) void k_rewire(RewireArgs a) {
                 // the requesting nodes' rows, padded to whole groups of eight entries with a value no slot has
                 for (int k = 0; k < ng; ++k)
                     for (int x = lane; x < K8; x += 64)
-                        qrow[k * 128 + x] = x < K ? a.A[(size_t)rq[c0 + k] * K + x] : 0xFFFFFFFEu;
+                        qrow[k * 128 + x] = x < K ? a.A[(size_t)rq[c0 + k] * (uint32_t)K + x] : 0xFFFFFFFEu;
                 __syncthreads();
                 if constexpr (WHOLE) {
                     float acc[G + 1][EvalShape<NCH>::R];
@@ -791,7 +791,7 @@ __global__ __launch_bounds__(64, 4) void k_rewire(RewireArgs a) {
             done += nb;
         } while (BIG && done < gt);
     }
-    if (changed && lane < len) a.A[(size_t)v * K + off + lane] = R[lane];
+    if (changed && lane < len) a.A[(size_t)v * (uint32_t)K + off + lane] = R[lane];
     if (lane == 0) a.grp_out[head_index] = st_applied | (st_pass << 16);
     }
 }

@@ -368,17 +368,18 @@ struct BeamArgs {
 // intervals; reads the attribute only for slots in the appended tail of an edge bucket
 __device__ __forceinline__ bool precheck(const QueryPlan &p, uint32_t v, const int32_t *__restrict__ attr, int lo,
                                          int hi, bool &tail) {
-    // every interval of the plan has start <= end, so one unsigned comparison tests membership
+    // every interval of the plan has start <= end < 2^31, so one unsigned comparison tests membership
+    // (and fails for the empty entry 0xFFFFFFFF); no branch unless the edge buckets have appended tails
+    bool ok = (v - (uint32_t)p.s0 < (uint32_t)(p.e0 - p.s0)) | (v - (uint32_t)p.ms < (uint32_t)(p.e1 - p.ms));
     tail = false;
-    if (v - (uint32_t)p.s0 < (uint32_t)(p.e0 - p.s0)) return true;
-    if (v - (uint32_t)p.ms < (uint32_t)(p.e1 - p.ms)) return true;
-    if (p.t0e == p.t0s && p.t1e == p.t1s) return false;   // no appended tails in the edge buckets (the same for every lane)
-    if (v - (uint32_t)p.t0s < (uint32_t)(p.t0e - p.t0s) || v - (uint32_t)p.t1s < (uint32_t)(p.t1e - p.t1s)) {
-        tail = true;
-        int a = attr[v];
-        return a >= lo && a <= hi;
+    if (p.t0e != p.t0s || p.t1e != p.t1s) {   // the same for every lane
+        tail = !ok && ((v - (uint32_t)p.t0s < (uint32_t)(p.t0e - p.t0s)) | (v - (uint32_t)p.t1s < (uint32_t)(p.t1e - p.t1s)));
+        if (tail) {
+            const int a = attr[v];
+            ok = a >= lo && a <= hi;
+        }
     }
-    return false;
+    return ok;
 }
 
 // Pre-check and exact visited set for NV slots per lane at once.  The visited set is open
@@ -399,7 +400,7 @@ __device__ __forceinline__ int admit(const QueryPlan &p, const uint32_t (&v)[NV]
     for (int u = 0; u < NV; ++u) {
         bool tail = false, ok = false;
         const bool live = v[u] != GRAB_EMPTY;
-        if (live) ok = precheck(p, v[u], attr, lo, hi, tail);
+        ok = precheck(p, v[u], attr, lo, hi, tail);   // false for an empty entry
         c_rej += __popcll(__ballot(live && !ok));
         c_tail += __popcll(__ballot(tail));
         pend[u] = ok;
