@@ -1,6 +1,7 @@
 // Device-side helpers shared by the search and append kernels (gfx950 only): queue keys,
 // wave reductions and the gathered fp32 distance with its fixed summation order.
 #pragma once
+#include <type_traits>
 
 #include "grab_internal.h"
 
@@ -194,6 +195,32 @@ __device__ __forceinline__ float dpp_move(float x) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xF, 0xF, true));
 }
 
+// acc plus the four products of one 16-byte piece under the metric, in index order.  The metric is a
+// template argument so that a caller decides it once per batch of rows and not once per piece: a
+// branch between every four multiplications keeps the compiler from interleaving the rows' chains.
+template <bool L2>
+__device__ __forceinline__ float fma_piece(const float4 qv, const float4 x, float acc) {
+    if constexpr (L2) {
+        const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
+        acc = __builtin_fmaf(dx, dx, acc);
+        acc = __builtin_fmaf(dy, dy, acc);
+        acc = __builtin_fmaf(dz, dz, acc);
+        acc = __builtin_fmaf(dw, dw, acc);
+    } else {
+        acc = __builtin_fmaf(qv.x, x.x, acc);
+        acc = __builtin_fmaf(qv.y, x.y, acc);
+        acc = __builtin_fmaf(qv.z, x.z, acc);
+        acc = __builtin_fmaf(qv.w, x.w, acc);
+    }
+    return acc;
+}
+// f(std::true_type) under squared L2, f(std::false_type) under the inner product
+#define GRAB_WITH_METRIC(metric, f)            \
+    do {                                       \
+        if ((metric) == GRAB_L2SQ) f(std::true_type{}); \
+        else f(std::false_type{});             \
+    } while (0)
+
 // Gathered distances (Algorithm 2, ComputeDistance) for up to 8*R slots L[base..]: eight lanes
 // share a row, lane `sub` of a group takes the 16-byte pieces 8c+sub (one 128-byte line per
 // piece index across the group) and accumulates them in index order with fused multiply-adds;
@@ -231,28 +258,17 @@ __device__ __forceinline__ void eval_batch_rows(const float *__restrict__ X, con
             for (int cc = 0; cc < CB; ++cc)
                 buf[r][cc] = act[r] ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
         }
+        auto products = [&](auto l2) __attribute__((always_inline)) {
 #pragma unroll
-        for (int cc = 0; cc < CB; ++cc) {
-            float4 qv;
-            if constexpr (EvalShape<NCH>::QREG) qv = qreg[c0 + cc];
-            else qv = reinterpret_cast<const float4 *>(qlds)[(c0 + cc) * 8 + sub];
+            for (int cc = 0; cc < CB; ++cc) {
+                float4 qv;
+                if constexpr (EvalShape<NCH>::QREG) qv = qreg[c0 + cc];
+                else qv = reinterpret_cast<const float4 *>(qlds)[(c0 + cc) * 8 + sub];
 #pragma unroll
-            for (int r = 0; r < RA; ++r) {
-                float4 x = buf[r][cc];
-                if (metric == GRAB_L2SQ) {
-                    float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
-                    acc[r] = __builtin_fmaf(dx, dx, acc[r]);
-                    acc[r] = __builtin_fmaf(dy, dy, acc[r]);
-                    acc[r] = __builtin_fmaf(dz, dz, acc[r]);
-                    acc[r] = __builtin_fmaf(dw, dw, acc[r]);
-                } else {
-                    acc[r] = __builtin_fmaf(qv.x, x.x, acc[r]);
-                    acc[r] = __builtin_fmaf(qv.y, x.y, acc[r]);
-                    acc[r] = __builtin_fmaf(qv.z, x.z, acc[r]);
-                    acc[r] = __builtin_fmaf(qv.w, x.w, acc[r]);
-                }
+                for (int r = 0; r < RA; ++r) acc[r] = fma_piece<decltype(l2)::value>(qv, buf[r][cc], acc[r]);
             }
-        }
+        };
+        GRAB_WITH_METRIC(metric, products);
     }
 #pragma unroll
     for (int r = 0; r < RA; ++r) {
@@ -339,30 +355,19 @@ __device__ __forceinline__ void rows_fma(const RowRegs<NCH> &rr, const float *qs
                                          float (&acc)[G][EvalShape<NCH>::R]) {
     constexpr int CB = EvalShape<NCH>::CB, R = EvalShape<NCH>::R, D4 = NCH * 8;
     const float4 *q4 = reinterpret_cast<const float4 *>(qs);
+    auto products = [&](auto l2) __attribute__((always_inline)) {
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        if (!((qmask >> g) & 1u)) continue;
+        for (int g = 0; g < G; ++g) {
+            if (!((qmask >> g) & 1u)) continue;
 #pragma unroll
-        for (int cc = 0; cc < CB; ++cc) {
-            const float4 qv = q4[g * D4 + (c0 + cc) * 8 + (lane & 7)];
+            for (int cc = 0; cc < CB; ++cc) {
+                const float4 qv = q4[g * D4 + (c0 + cc) * 8 + (lane & 7)];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const float4 x = rr.buf[r][cc];
-                if (metric == GRAB_L2SQ) {
-                    const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
-                    acc[g][r] = __builtin_fmaf(dx, dx, acc[g][r]);
-                    acc[g][r] = __builtin_fmaf(dy, dy, acc[g][r]);
-                    acc[g][r] = __builtin_fmaf(dz, dz, acc[g][r]);
-                    acc[g][r] = __builtin_fmaf(dw, dw, acc[g][r]);
-                } else {
-                    acc[g][r] = __builtin_fmaf(qv.x, x.x, acc[g][r]);
-                    acc[g][r] = __builtin_fmaf(qv.y, x.y, acc[g][r]);
-                    acc[g][r] = __builtin_fmaf(qv.z, x.z, acc[g][r]);
-                    acc[g][r] = __builtin_fmaf(qv.w, x.w, acc[g][r]);
-                }
+                for (int r = 0; r < R; ++r) acc[g][r] = fma_piece<decltype(l2)::value>(qv, rr.buf[r][cc], acc[g][r]);
             }
         }
-    }
+    };
+    GRAB_WITH_METRIC(metric, products);
 }
 // out[g * 64 + j] = dist(query g, L[j]) for the rows of the batch at `base`
 template <int NCH, int G>
@@ -420,22 +425,11 @@ __device__ __forceinline__ void eval_rows_few(const float *__restrict__ X, const
         float4 buf[CB];
 #pragma unroll
         for (int cc = 0; cc < CB; ++cc) buf[cc] = act ? row[(c0 + cc) * 8] : make_float4(0.f, 0.f, 0.f, 0.f);
+        auto products = [&](auto l2) __attribute__((always_inline)) {
 #pragma unroll
-        for (int cc = 0; cc < CB; ++cc) {
-            const float4 qv = q4[(c0 + cc) * 8 + sub], x = buf[cc];
-            if (metric == GRAB_L2SQ) {
-                const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
-                acc = __builtin_fmaf(dx, dx, acc);
-                acc = __builtin_fmaf(dy, dy, acc);
-                acc = __builtin_fmaf(dz, dz, acc);
-                acc = __builtin_fmaf(dw, dw, acc);
-            } else {
-                acc = __builtin_fmaf(qv.x, x.x, acc);
-                acc = __builtin_fmaf(qv.y, x.y, acc);
-                acc = __builtin_fmaf(qv.z, x.z, acc);
-                acc = __builtin_fmaf(qv.w, x.w, acc);
-            }
-        }
+            for (int cc = 0; cc < CB; ++cc) acc = fma_piece<decltype(l2)::value>(q4[(c0 + cc) * 8 + sub], buf[cc], acc);
+        };
+        GRAB_WITH_METRIC(metric, products);
     }
     float t = acc;
     t += dpp_move<0xB1>(t);
@@ -451,22 +445,11 @@ __device__ __forceinline__ float dist_lds_rows(const float *qa, const float *qb,
     const int sub = lane & 7;
     const float4 *a4 = reinterpret_cast<const float4 *>(qa), *b4 = reinterpret_cast<const float4 *>(qb);
     float acc = 0.0f;
+    auto products = [&](auto l2) __attribute__((always_inline)) {
 #pragma unroll 4
-    for (int c = 0; c < NCH; ++c) {
-        const float4 qv = a4[c * 8 + sub], x = b4[c * 8 + sub];
-        if (metric == GRAB_L2SQ) {
-            const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
-            acc = __builtin_fmaf(dx, dx, acc);
-            acc = __builtin_fmaf(dy, dy, acc);
-            acc = __builtin_fmaf(dz, dz, acc);
-            acc = __builtin_fmaf(dw, dw, acc);
-        } else {
-            acc = __builtin_fmaf(qv.x, x.x, acc);
-            acc = __builtin_fmaf(qv.y, x.y, acc);
-            acc = __builtin_fmaf(qv.z, x.z, acc);
-            acc = __builtin_fmaf(qv.w, x.w, acc);
-        }
-    }
+        for (int c = 0; c < NCH; ++c) acc = fma_piece<decltype(l2)::value>(a4[c * 8 + sub], b4[c * 8 + sub], acc);
+    };
+    GRAB_WITH_METRIC(metric, products);
     float t = acc;
     t += dpp_move<0xB1>(t);
     t += dpp_move<0x4E>(t);
@@ -494,26 +477,19 @@ __device__ __forceinline__ void group_vs_rows(const float *__restrict__ X, const
 #pragma unroll
             for (int c = 0; c < NCH; ++c) buf[r][c] = row[c * 8];
         }
+        float acc[RR];
+        auto products = [&](auto l2) __attribute__((always_inline)) {
+#pragma unroll
+            for (int r = 0; r < RR; ++r) {
+                acc[r] = 0.0f;
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) acc[r] = fma_piece<decltype(l2)::value>(mine[c], buf[r][c], acc[r]);
+            }
+        };
+        GRAB_WITH_METRIC(metric, products);
 #pragma unroll
         for (int r = 0; r < RR; ++r) {
-            float acc = 0.0f;
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                const float4 qv = mine[c], x = buf[r][c];
-                if (metric == GRAB_L2SQ) {
-                    const float dx = qv.x - x.x, dy = qv.y - x.y, dz = qv.z - x.z, dw = qv.w - x.w;
-                    acc = __builtin_fmaf(dx, dx, acc);
-                    acc = __builtin_fmaf(dy, dy, acc);
-                    acc = __builtin_fmaf(dz, dz, acc);
-                    acc = __builtin_fmaf(dw, dw, acc);
-                } else {
-                    acc = __builtin_fmaf(qv.x, x.x, acc);
-                    acc = __builtin_fmaf(qv.y, x.y, acc);
-                    acc = __builtin_fmaf(qv.z, x.z, acc);
-                    acc = __builtin_fmaf(qv.w, x.w, acc);
-                }
-            }
-            float t = acc;
+            float t = acc[r];
             t += dpp_move<0xB1>(t);
             t += dpp_move<0x4E>(t);
             t += dpp_move<0x141>(t);
