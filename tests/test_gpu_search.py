@@ -112,6 +112,32 @@ def test_search_matches_oracle_exactly(c1_small, torch_dev, beam, width):
     assert np.array_equal(ctr, want_ctr)             # same traversal, step for step
 
 
+def test_launch_order_survives_batches_of_changing_size(c1_small, torch_dev):
+    """Batches of 2,048 queries and more run in bucket order, filed by counters that two calls use in turn and the
+    later call clears: batches of different sizes, one after the other on one index, must all match the oracle (a
+    rank left over from an earlier call would send two queries to one place of the order and leave one unanswered)."""
+    c = c1_small
+    ix = _gpu_index(c, torch_dev)
+    ora = c["oracle"]
+    rng = np.random.default_rng(5)
+    try:
+        want = {}
+        for nq in (2300, 4100, 2300, 300, 2048, 4100):
+            pick = rng.integers(0, len(c["queries"]), nq)
+            q, lo, hi = c["queries"][pick], c["lo"][pick].copy(), c["hi"][pick].copy()
+            lo[::9] = 20000                                   # some queries select nothing: the extra bin
+            ids, dist, ctr = _search_gpu(ix, torch_dev, q, lo, hi, 10, 32)
+            if "all" not in want:
+                want["all"] = ora.search(c["queries"], c["lo"], c["hi"], 10, 32)
+            w_ids, w_dist, w_ctr = (x[pick] for x in want["all"])
+            none = np.arange(nq) % 9 == 0
+            assert np.array_equal(ids[~none], w_ids[~none]) and np.array_equal(dist[~none], w_dist[~none])
+            assert np.array_equal(ctr[~none], w_ctr[~none])
+            assert (ids[none] == 0xFFFFFFFF).all() and np.isinf(dist[none]).all()
+    finally:
+        ix.close()
+
+
 def _random_case(n, dim, B, kl, kr, metric, seed, n_cap=None, nq=300, domain=None):
     cfg = W.Config(f"t{seed}", n, dim, 8, 0.4, domain or n, B, kl, kr, nq, (0.2,), metric=metric,
                    normalise=(metric == W.IP), seed=seed)
